@@ -1,0 +1,191 @@
+/*
+ * jpgd -- baseline-JPEG decoding on one AMD MI355X (gfx950) with the
+ * self-synchronising parallel Huffman decoder of Weissenberger & Schmidt,
+ * "Accelerating JPEG Decompression on GPUs" (arXiv 2111.09219).
+ *
+ * C ABI.  Every function returns JPGD_OK (0) or a negative jpgd_status; none
+ * aborts or throws.  Pointers marked [host] are ordinary host memory, pointers
+ * marked [device] are HIP device memory on the current device.  The library
+ * never allocates or frees device memory: the caller (PyTorch in the Python
+ * binding) owns every device buffer and the stream.
+ *
+ * Pipeline behind jpgd_decode / jpgd_decode_batch (paper, Section 4,
+ * Algorithm 1), all of it in HIP kernels:
+ *   unstuff       drop the 0x00 after every 0xFF of the entropy-coded bytes
+ *                 (the paper does not mention byte stuffing; a baseline stream
+ *                 cannot be cut into fixed-size subsequences without it)
+ *   sync (intra)  Algorithm 3, first loop: one lane per subsequence, own decode
+ *                 (Algorithm 2) then overflow into the neighbours until the
+ *                 decoder state (bit position, data unit, zig-zag index) matches
+ *   sync (inter)  Algorithm 3, second loop: one lane per sequence boundary
+ *   scan          Algorithm 1, exclusive prefix sum over s_info.n, here over
+ *                 (completed data units, DC-difference sums per component)
+ *   write         Algorithm 1 last loop / Algorithm 2 with write=true: re-decode
+ *                 from the true state and scatter coefficients; run/EOB expansion
+ *   DC            Section 4.2: per-component prefix sum of DC differences
+ *                 (carried through the scan above; see jpgd_decode)
+ *   pixels        Section 4.3: de-zigzag, dequantise, 8x8 IDCT; plus MCU ->
+ *                 image placement, chroma replication and YCbCr -> RGB
+ */
+#ifndef JPGD_H
+#define JPGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    JPGD_OK = 0,
+    JPGD_E_ARG = -1,         /* NULL pointer, bad size, bad config value                     */
+    JPGD_E_TRUNCATED = -2,   /* file or segment ends early, no end-of-image marker            */
+    JPGD_E_MARKER = -3,      /* not a JPEG, marker syntax broken, scan before frame header    */
+    JPGD_E_UNSUPPORTED = -4, /* valid JPEG outside the supported subset (see jpgd_parse)      */
+    JPGD_E_TABLE = -5,       /* missing or malformed Huffman / quantisation table             */
+    JPGD_E_CORRUPT = -6,     /* entropy-coded data inconsistent with the headers              */
+    JPGD_E_WORKSPACE = -7,   /* workspace too small or misaligned                             */
+    JPGD_E_HIP = -8          /* a HIP runtime call failed                                     */
+} jpgd_status;
+
+/*
+ * Everything the decoder needs from the headers of one file.  Plain data,
+ * filled by jpgd_parse, owned by the caller, never holds pointers.
+ */
+typedef struct {
+    uint32_t width, height;       /* pixels                                                          */
+    uint32_t ncomp;               /* 1 (grayscale) or 3 (YCbCr)                                      */
+    uint8_t hsamp[3], vsamp[3];   /* sampling factors per component                                  */
+    uint8_t tq[3], td[3], ta[3];  /* quantisation / DC / AC table ids per component                  */
+    uint16_t qt[4][64];           /* quantisation tables in the order stored in the file (zig-zag)   */
+    uint8_t qt_present[4];
+    uint8_t dht_bits[2][4][16];   /* [0 = DC, 1 = AC][table id]: number of codes of length 1..16     */
+    uint8_t dht_vals[2][4][256];  /* symbols in order of increasing code                             */
+    uint8_t dht_present[2][4];
+    uint32_t mcu_w, mcu_h;        /* pixels per MCU: 8x8, 16x8 or 16x16 (paper, Section 2)           */
+    uint32_t mcus_x, mcus_y;
+    uint32_t units_per_mcu;       /* 1, 3, 4 or 6 data units                                         */
+    uint32_t total_units;         /* data units (8x8 blocks) in the scan                             */
+    uint64_t scan_offset;         /* first entropy-coded byte inside the file                        */
+    uint64_t scan_bytes;          /* entropy-coded bytes, still byte-stuffed, up to the EOI marker   */
+    uint32_t restart_interval;    /* always 0 in an accepted file                                    */
+} jpgd_info;
+
+typedef struct {
+    uint32_t subseq_bits;  /* subsequence size in bits ("s*32" in Algorithm 1): 128, 256, ..., 4096;
+                              0 = choose per call from the stream sizes                            */
+    uint32_t overlap;      /* subsequences by which neighbouring sequences overlap (warm-up lanes
+                              in front of each sequence); 0 = the paper's disjoint sequences;
+                              must be < 192; 0xFFFFFFFF = library default                          */
+    uint32_t max_rounds;   /* upper bound on inter-sequence synchronisation rounds; 0 = number of
+                              sequences (always enough)                                             */
+    uint32_t flags;        /* JPGD_F_* */
+} jpgd_config;
+
+#define JPGD_F_NO_PIXELS 1u /* stop after the coefficients even if a pixel buffer is given */
+
+/* What a decode call did; filled on return (host memory). */
+typedef struct {
+    uint32_t subseq_bits;   /* subsequence size used                                              */
+    uint32_t n_subseq;      /* subsequences over all images (upper bound from the stuffed sizes)  */
+    uint32_t n_sequences;   /* thread blocks of the intra-sequence kernel                         */
+    uint32_t inter_rounds;  /* inter-sequence rounds run                                          */
+    uint32_t redo;          /* times scan+write were repeated because verification failed         */
+    uint32_t device_flags;  /* raw status word from the device                                    */
+} jpgd_report;
+
+/*
+ * Host only, touches no GPU.  Reads the marker segments of a baseline JPEG
+ * file (paper, Section 4.1: "after parsing the batch and extracting all
+ * necessary Huffman tables") and locates the entropy-coded segment without
+ * scanning it: it ends at the last EOI marker of the file.
+ *
+ * Accepted: SOF0, 8-bit, one scan, 1 component or 3 components with chroma
+ * sampled 1x1 and luma 1x1, 2x1, 1x2 or 2x2; no restart interval.
+ * JPGD_E_UNSUPPORTED: progressive / extended / lossless / arithmetic frames,
+ * 12-bit, other component counts or sampling, DRI != 0, several scans.
+ * JPGD_E_TABLE: table id > 3, more than 256 symbols, more codes of some
+ * length than that length can hold, a table a component refers to missing.
+ * JPGD_E_TRUNCATED / JPGD_E_MARKER: as named.
+ */
+int jpgd_parse(const uint8_t* file /*[host]*/, size_t len, jpgd_info* out /*[host]*/);
+
+/*
+ * Bytes of device workspace jpgd_decode_batch needs for these images and this
+ * config (0 on bad arguments).  The workspace must be 256-byte aligned.  Its
+ * contents need not be preserved between calls and may be uninitialised.
+ */
+size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, const jpgd_config* cfg /*[host], may be NULL*/);
+
+/*
+ * Decodes n images in one go (paper, Algorithm 1, "batched").
+ *
+ *  infos          [host]   n parsed headers
+ *  d_scans        [device] the entropy-coded bytes of all images; image i occupies
+ *                          scan_offsets[i] .. scan_offsets[i] + infos[i].scan_bytes
+ *  scan_offsets   [host]   n byte offsets into d_scans
+ *  d_coef         [device] int16 output, may not be NULL; image i gets 64*total_units
+ *                          values at element offset coef_offsets[i] (must be a multiple of 64):
+ *                          data units in scan (MCU-interleaved) order, zig-zag order inside a
+ *                          unit, quantised (not dequantised), DC un-differenced
+ *  coef_offsets   [host]
+ *  d_pixels       [device] uint8 output or NULL: image i at byte offset pixel_offsets[i],
+ *                          height x width x ncomp interleaved (gray or RGB), cropped to the
+ *                          true size
+ *  pixel_offsets  [host]   may be NULL iff d_pixels is NULL
+ *  d_workspace    [device] jpgd_workspace_bytes(...) bytes, 256-byte aligned
+ *  cfg            [host]   may be NULL for defaults
+ *  stream                  a hipStream_t (as void*); NULL = the default stream
+ *  report         [host]   may be NULL
+ *
+ * All work is enqueued on `stream`; the call returns after the stream has
+ * drained, because the device's verdict (every lane of the write pass checks
+ * that it ends in the state recorded for its subsequence) decides whether
+ * further synchronisation rounds are needed and is the source of
+ * JPGD_E_CORRUPT.  On JPGD_E_CORRUPT the outputs hold unspecified values but
+ * nothing outside them has been written.
+ *
+ * DC: the per-component prefix sum of Section 4.2 is computed hierarchically
+ * -- per-subsequence sums of DC differences during synchronisation, their
+ * exclusive scan together with the unit counts, and a running sum in the write
+ * pass -- so d_coef is written exactly once, with absolute DC values.
+ */
+int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                      int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
+                      const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
+                      const jpgd_config* cfg, void* stream, jpgd_report* report);
+
+/* One image: jpgd_decode_batch with n = 1 and all offsets 0. */
+int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
+                void* d_workspace, size_t workspace_bytes, const jpgd_config* cfg, void* stream,
+                jpgd_report* report);
+
+/*
+ * Stage-level entry points (used by the tests to check single steps against the oracle).
+ * jpgd_unstuff: d_out must hold `n + 64` bytes; *out_len [host] receives the unstuffed length.
+ */
+int jpgd_unstuff(const uint8_t* d_in /*[device]*/, size_t n, uint8_t* d_out /*[device]*/, size_t* out_len /*[host]*/,
+                 void* d_workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Copies the synchronisation result of the most recent decode call that used
+ * this workspace to the host: for image `image`, subsequence i < *n_subseq,
+ *   p[i]      bit position (unstuffed stream) of the first symbol starting at or after (i+1)*subseq_bits
+ *   u[i],z[i] data unit inside the MCU and zig-zag index at that point
+ *   units[i]  data units completed by symbols starting inside subsequence i
+ *   dcsum[3*i+c] sum of DC differences of component c among those symbols (as int16, wrapped)
+ * Arrays must have room for `capacity` entries; JPGD_E_ARG if fewer than needed.
+ */
+int jpgd_read_sync_info(const void* d_workspace, int image, uint32_t capacity, uint32_t* n_subseq,
+                        uint64_t* p, uint32_t* u, uint32_t* z, uint32_t* units, int32_t* dcsum, void* stream);
+
+const char* jpgd_strerror(int status);
+
+/* ABI version of this header: bumped on any incompatible change. */
+int jpgd_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JPGD_H */

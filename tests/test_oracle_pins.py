@@ -1,0 +1,406 @@
+"""Pins of the CPU oracle against things other than itself.
+
+Each test names what it pins and what fixes the expected value: the paper's worked example
+(Table I), codewords printed in ITU-T T.81 Annex K, closed forms, an independent encoder,
+files written by Pillow (an outside JPEG codec, used as a black box), scipy's inverse DCT.
+"""
+import io
+import os
+
+import numpy as np
+import pytest
+import scipy.fft
+from PIL import Image
+
+import jpegfile as jf
+from oracle import OracleError, OracleImage, idct8x8, unstuff_bytes, zigzag
+from workloads import encode_jpeg, small_image
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+# ITU-T T.81 Annex K.1, Table K.1 (luminance quantisation), natural (row-major) order; typed from the standard.
+K1_LUMA = [16, 11, 10, 16, 24, 40, 51, 61, 12, 12, 14, 19, 26, 58, 60, 55, 14, 13, 16, 24, 40, 57, 69, 56,
+           14, 17, 22, 29, 51, 87, 80, 62, 18, 22, 37, 56, 68, 109, 103, 77, 24, 35, 55, 64, 81, 104, 113, 92,
+           49, 64, 78, 87, 103, 121, 120, 101, 72, 92, 95, 98, 112, 100, 103, 99]
+
+
+# ----------------------------------------------------------------------------- Table I
+
+def _load_table1():
+    spec = dict(dc=[], ac=[], true=[], offset=[])
+    with open(os.path.join(GOLDEN, "table1_sync_example.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            w = line.split()
+            if w[0] == "dc_code":
+                spec["dc"].append((int(w[1][2:]), w[2]))
+            elif w[0] == "ac_code":
+                if w[1] == "EOB":
+                    spec["ac"].append((0, 0, w[2]))
+                else:
+                    spec["ac"].append((int(w[1][2:]), int(w[2][2:]), w[3]))
+            elif w[0] == "stream":
+                spec["stream"] = "".join(w[1:])
+                spec["groups"] = w[1:]
+            elif w[0] in ("true", "offset"):
+                spec[w[0]].append("EOB" if w[1] == "EOB" else tuple(int(x) for x in w[1:]))
+            elif w[0] == "offset_start_bit":
+                spec["start"] = int(w[1])
+            elif w[0] == "sync_element_index":
+                spec["sync_index"] = int(w[1])
+    return spec
+
+
+def _table1_image(spec):
+    """A 1-component JPEG header whose DHT segments give exactly the toy codewords of Table I.
+
+    Canonical codes count upward within a length, so unused filler symbols are listed ahead of a
+    codeword where the example's code is not the first of its length (DC '10' is the third 2-bit
+    code; AC '1011' the second 4-bit code)."""
+    (dc_l, dc_code), = spec["dc"]
+    assert dc_code == "10" and dc_l == 2
+    dc_bits = [0, 3] + [0] * 14
+    dc_vals = [0, 1, 2]                         # 00 -> size 0, 01 -> size 1, 10 -> size 2
+    codes = {c: (l, r) for l, r, c in spec["ac"]}
+    assert set(codes) == {"00", "01", "100", "1011"}
+    ac_bits = [0, 2, 1, 2] + [0] * 12
+    ac_vals = [0x00, (codes["01"][1] << 4) | codes["01"][0], (codes["100"][1] << 4) | codes["100"][0],
+               0x21,                             # filler for 1010
+               (codes["1011"][1] << 4) | codes["1011"][0]]
+    raw = jf.pack_bits(spec["stream"], pad_ones=False)
+    data = jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: [1] * 64},
+                       [(0, 0, dc_bits, dc_vals), (1, 0, ac_bits, ac_vals)], raw)
+    return OracleImage(data), np.frombuffer(raw, dtype=np.uint8)
+
+
+def _as_elements(symbols):
+    out = []
+    for s in symbols:
+        if s["kind"] == 2:
+            out.append("EOB")
+        else:
+            out.append((s["size"], s["run"], s["value"]))
+    return out
+
+
+def test_table1_true_decode_and_codeword_positions():
+    """Pins decode_next_symbol: code lookup, value-bit sign rule, run handling, EOB (Table I, upper part)."""
+    spec = _load_table1()
+    img, raw = _table1_image(spec)
+    sym = img.trace(raw, 32, 0)
+    assert _as_elements(sym) == spec["true"]
+    starts = np.cumsum([0] + [len(g) for g in spec["groups"]])[:-1].tolist()
+    assert [s["p"] for s in sym] == starts                       # 0,4,9,14,17,22,25,30
+    assert [s["z"] for s in sym] == [0, 1, 2, 3, 4, 6, 7, 9]     # zig-zag index before each element
+    coef = img.coefficients()
+    assert coef[0, :10].tolist() == [-2, -3, 2, -1, 0, -1, 1, 0, 1, 0] and not coef[0, 10:].any()
+
+
+def test_table1_offset_decode_synchronises():
+    """Pins decoding from an arbitrary bit and the (p, z) match rule (Table I, lower part; Section 3)."""
+    spec = _load_table1()
+    img, raw = _table1_image(spec)
+    true = img.trace(raw, 32, 0)
+    off = img.trace(raw, 32, spec["start"], u=0, z=0)
+    assert _as_elements(off) == spec["offset"]
+    k = spec["sync_index"]
+    # before the synchronisation point the two decoders disagree, from it on they are identical
+    true_at = {s["p"]: s for s in true}
+    assert off[k]["p"] == 14 and off[k]["z"] == 3 and true_at[14]["z"] == 3
+    for s in off[k:]:
+        assert true_at[s["p"]] == s
+    for s in off[:k]:
+        assert s["p"] not in true_at or true_at[s["p"]] != s
+
+
+def test_value_bits_example_from_section2():
+    """'if the codeword 100 signified l=2, r=0 then -3 would be encoded as 10000' (Section 2)."""
+    spec = _load_table1()
+    img, _ = _table1_image(spec)
+    raw = np.frombuffer(jf.pack_bits("10000" + "111"), dtype=np.uint8)
+    s = img.trace(raw, 5, 0, u=0, z=1)[0]
+    assert (s["size"], s["run"], s["value"], s["length"]) == (2, 0, -3, 5)
+
+
+# ----------------------------------------------------------------------- hand-written streams
+
+def _annexk_header_file(width, height, scan_raw):
+    """Header of an Annex-K gray file made by the input encoder, with its scan replaced by scan_raw."""
+    enc = encode_jpeg(np.full((height, width), 128, np.uint8), quality=50)
+    head = enc.data[:enc.scan_offset].tobytes()
+    return np.frombuffer(head + jf.stuff(scan_raw) + b"\xFF\xD9", dtype=np.uint8).copy()
+
+
+def test_hand_written_stream_dc_chain_runs_zrl_eob():
+    """Pins canonical code construction (codewords typed from T.81 Tables K.3/K.5), DC prediction,
+    run / ZRL / EOB expansion, on a stream assembled by hand."""
+    DC, AC = jf.K3_DC_LUMA, jf.K5_AC_LUMA
+    blocks = [
+        dict(dc=5, ac=[(0, 3), (1, -2), (0, 1)]),                  # diff +5
+        dict(dc=2, ac=[]),                                         # diff -3, immediately EOB
+        dict(dc=4, ac=[(15, None), (15, None), (2, 1)]),           # diff +2; two ZRL then run 2 -> index 35
+        dict(dc=4, ac=[(0, 1)] * 63),                              # diff 0; all 63 AC present: no EOB
+    ]
+    bits, pred, expect = "", 0, np.zeros((4, 64), np.int16)
+    for k, b in enumerate(blocks):
+        size, vb = jf.value_bits(b["dc"] - pred)
+        pred = b["dc"]
+        bits += DC[size] + vb
+        expect[k, 0] = b["dc"]
+        z = 1
+        for run, v in b["ac"]:
+            if v is None:
+                bits += AC[(15, 0)]
+                z += 16
+                continue
+            size, vb = jf.value_bits(v)
+            bits += AC[(run, size)] + vb
+            z += run
+            expect[k, z] = v
+            z += 1
+        if z < 64:
+            bits += AC[(0, 0)]
+    data = _annexk_header_file(32, 8, jf.pack_bits(bits))
+    img = OracleImage(data)
+    coef, end_bit = img.coefficients(return_end_bit=True)
+    assert np.array_equal(coef, expect)
+    assert end_bit == len(bits)
+
+
+def test_flat_image_closed_form():
+    """All-zero coefficients: every luma block is '00' + '1010' (6 bits), so 256x256 gray is 768 bytes
+    of the repeating pattern 00101000 10100010 10001010; decoded pixels are all 128."""
+    raw = jf.pack_bits("001010" * 1024)
+    assert len(raw) == 768
+    img = OracleImage(_annexk_header_file(256, 256, raw))
+    coef = img.coefficients()
+    assert not coef.any()
+    assert (img.pixels(coef) == 128).all()
+
+
+def test_dc_only_block_is_constant():
+    """A block with only a DC coefficient d decodes to the constant d*Q0/8 + 128 (IDCT of a constant)."""
+    for d in (-40, -3, 1, 17, 60):
+        size, vb = jf.value_bits(d)
+        raw = jf.pack_bits(jf.K3_DC_LUMA[size] + vb + jf.K5_AC_LUMA[(0, 0)])
+        img = OracleImage(_annexk_header_file(8, 8, raw))
+        q0 = int(img.quant_table(0)[0])
+        want = int(np.clip(np.floor(d * q0 / 8.0 + 128 + 0.5), 0, 255))
+        assert (img.pixels() == want).all()
+
+
+def test_corrupt_and_unsupported_inputs_are_reported():
+    good = encode_jpeg(small_image(3, 24, 24, ncomp=1), quality=80).data
+    with pytest.raises(OracleError) as e:
+        OracleImage(good[:40])
+    assert e.value.name == "TRUNCATED"
+    bad = good.copy()
+    bad[0] = 0
+    with pytest.raises(OracleError):
+        OracleImage(bad)
+    prog = io.BytesIO()
+    Image.fromarray(small_image(3, 24, 24)).save(prog, "JPEG", progressive=True)
+    with pytest.raises(OracleError) as e:
+        OracleImage(np.frombuffer(prog.getvalue(), np.uint8))
+    assert e.value.name == "UNSUPPORTED"
+    # a stream that ends before all blocks are decoded
+    short = _annexk_header_file(64, 64, jf.pack_bits("001010" * 3))
+    with pytest.raises(OracleError) as e:
+        OracleImage(short).coefficients()
+    assert e.value.name == "CORRUPT"
+
+
+# ------------------------------------------------------------------ canonical code invariants
+
+def _tables_of(img):
+    for cls in (0, 1):
+        for tid in (0, 1):
+            try:
+                yield cls, tid, img.huffman(cls, tid), img.codes(cls, tid)
+            except OracleError:
+                pass
+
+
+@pytest.mark.parametrize("optimize", [False, True])
+def test_canonical_code_invariants(optimize):
+    """Kraft sum <= 1 - 2^-maxlen (all-ones codeword unused), prefix-freeness, sum(BITS) = #symbols,
+    codes of equal length consecutive in list order."""
+    enc = encode_jpeg(small_image(5, 96, 80, sigma=14), quality=93, subsampling="420", optimize=optimize)
+    img = OracleImage(enc.data)
+    seen = 0
+    for cls, tid, (bits, vals), (code, length) in _tables_of(img):
+        seen += 1
+        assert int(bits.sum()) == len(vals)
+        lens = length[vals]
+        assert (lens > 0).all() and sorted(lens) == list(lens)
+        maxlen = int(lens.max())
+        kraft = sum(2.0 ** -int(l) for l in lens)
+        assert kraft <= 1.0 - 2.0 ** -maxlen + 1e-12
+        words = [format(int(code[s]), "0%db" % int(length[s])) for s in vals]
+        assert len(set(words)) == len(words)
+        for a in words:
+            for b in words:
+                assert a == b or not b.startswith(a)
+        assert "1" * maxlen not in words
+    assert seen == 4
+
+
+def test_annexk_codewords_from_the_standard():
+    """The oracle's canonical construction applied to the Annex K lists gives the codewords printed in T.81."""
+    img = OracleImage(encode_jpeg(np.full((8, 8), 128, np.uint8), quality=50).data)
+    code, length = img.codes(0, 0)
+    for size, word in jf.K3_DC_LUMA.items():
+        assert format(int(code[size]), "0%db" % int(length[size])) == word
+    code, length = img.codes(1, 0)
+    for (run, size), word in jf.K5_AC_LUMA.items():
+        s = (run << 4) | size
+        assert format(int(code[s]), "0%db" % int(length[s])) == word
+
+
+# --------------------------------------------------------------- independent encoder round trip
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+@pytest.mark.parametrize("optimize", [False, True])
+def test_roundtrip_with_independent_encoder(sub, optimize):
+    """The encoder in workloads/ (separate code) reports the coefficients it quantised; the oracle
+    must decode exactly those -- sizes that are not multiples of the MCU included."""
+    for seed, (h, w), q in [(1, (37, 51), 85), (2, (64, 48), 95), (3, (8, 8), 40), (4, (129, 70), 75)]:
+        px = small_image(seed, h, w, ncomp=1 if sub == "gray" else 3, sigma=9.0)
+        enc = encode_jpeg(px, quality=q, subsampling=sub, optimize=optimize)
+        img = OracleImage(enc.data)
+        assert (img.width, img.height) == (w, h)
+        assert np.array_equal(img.coefficients(), enc.coef)
+        assert img.info.scan_offset == enc.scan_offset and img.info.scan_len == enc.scan_len
+
+
+# ------------------------------------------------------------------------- Pillow black box
+
+def _pillow_jpeg(px, **kw):
+    buf = io.BytesIO()
+    Image.fromarray(px).save(buf, "JPEG", **kw)
+    return np.frombuffer(buf.getvalue(), np.uint8).copy()
+
+
+@pytest.mark.parametrize("kw", [dict(quality=75), dict(quality=92, optimize=True), dict(quality=50)])
+def test_decodes_pillow_files_gray_and_444(kw):
+    """Files the oracle's authors did not write.  libjpeg's integer IDCT and colour conversion differ
+    from the double-precision path by at most 2 levels on these images."""
+    for ncomp in (1, 3):
+        px = small_image(11, 72, 88, ncomp=ncomp, sigma=7.0)
+        data = _pillow_jpeg(px, subsampling=0, **kw) if ncomp == 3 else _pillow_jpeg(px, **kw)
+        ref = np.asarray(Image.open(io.BytesIO(data.tobytes())))
+        got = OracleImage(data).pixels()
+        assert got.shape == ref.shape
+        assert np.abs(got.astype(int) - ref.astype(int)).max() <= 2
+
+
+def test_pillow_420_geometry_with_flat_chroma():
+    """4:2:0 placement (2x2 luma units per MCU, chroma covering 16x16).  libjpeg interpolates chroma
+    where the oracle replicates it, so the comparison is made where chroma is locally constant:
+    colour patches aligned to 32 pixels with luminance-only texture, away from patch borders."""
+    rng = np.random.default_rng(7)
+    h, w = 96, 128
+    px = np.zeros((h, w, 3), np.float64)
+    for by in range(0, h, 32):
+        for bx in range(0, w, 32):
+            px[by:by + 32, bx:bx + 32] = rng.uniform(60, 190, size=3)
+    px += rng.normal(0, 10, size=(h, w, 1))          # same offset on R, G and B: Cb and Cr unchanged
+    px = np.clip(np.rint(px), 0, 255).astype(np.uint8)
+    data = _pillow_jpeg(px, quality=95, subsampling=2)
+    img = OracleImage(data)
+    assert img.units_per_mcu == 6
+    ref = np.asarray(Image.open(io.BytesIO(data.tobytes()))).astype(int)
+    got = img.pixels().astype(int)
+    inner = np.zeros((h, w), bool)
+    for by in range(0, h, 32):
+        for bx in range(0, w, 32):
+            inner[by + 6:by + 26, bx + 6:bx + 26] = True
+    assert np.abs(got - ref)[inner].max() <= 3
+    # and the luminance texture really is resolved per pixel: swapping two luma units would show
+    assert np.abs(got - px.astype(int))[inner].mean() < 4.0
+
+
+def test_pillow_tables_pin_zigzag_and_parser():
+    """A quality-50 libjpeg file carries Table K.1 unscaled, stored in zig-zag order.  Reading it with
+    the oracle's parser and undoing the oracle's zig-zag must give the matrix printed in the standard."""
+    data = _pillow_jpeg(small_image(1, 16, 16, ncomp=1), quality=50)
+    img = OracleImage(data)
+    zz = zigzag()
+    assert sorted(zz.tolist()) == list(range(64))
+    assert zz[:8].tolist() == [0, 1, 8, 16, 9, 2, 3, 10] and zz[-2:].tolist() == [62, 63]
+    natural = np.zeros(64, int)
+    natural[zz] = img.quant_table(0)
+    assert natural.tolist() == K1_LUMA
+
+
+# --------------------------------------------------------------------------------- IDCT
+
+def test_idct_matches_scipy_orthonormal_dct3():
+    """JPEG's 8x8 IDCT is the orthonormal 2-D DCT-III; scipy.fft.idctn(norm='ortho') is the library routine."""
+    rng = np.random.default_rng(3)
+    for _ in range(20):
+        F = rng.normal(0, 200, size=(8, 8))
+        assert np.allclose(idct8x8(F), scipy.fft.idctn(F, type=2, norm="ortho"), atol=1e-9)
+    F = np.zeros((8, 8))
+    F[0, 0] = 80.0
+    assert np.allclose(idct8x8(F), 10.0)
+    # Parseval: orthonormal transform preserves the sum of squares
+    F = rng.normal(0, 50, size=(8, 8))
+    assert np.isclose((idct8x8(F) ** 2).sum(), (F ** 2).sum())
+    # transposition: vertical frequency is the row index of F
+    F = np.zeros((8, 8))
+    F[1, 0] = 100.0
+    f = idct8x8(F)
+    assert np.allclose(f, f[:, :1]) and not np.allclose(f[0], f[7])
+
+
+# ---------------------------------------------------------------------------- unstuffing
+
+def test_unstuff_brute_force():
+    rng = np.random.default_rng(5)
+    for n in (0, 1, 2, 17, 1000):
+        raw = rng.choice(np.array([0x00, 0xFF, 0xFF, 0x7F, 0x01], np.uint8), size=n)
+        stuffed = np.frombuffer(jf.stuff(raw.tobytes()), np.uint8)
+        assert np.array_equal(unstuff_bytes(stuffed), raw)
+
+
+# ------------------------------------------------------------------------ boundary states
+
+@pytest.mark.parametrize("sub,L", [("gray", 128), ("444", 256), ("420", 1024), ("422", 512), ("420", 32)])
+def test_boundary_states_are_the_sequential_decoder_s_states(sub, L):
+    """s_info after synchronisation (Section 4.1) is the sequential decoder's state at each boundary:
+    decoding onward from a reported state reproduces the rest of the sequential decode, the unit and
+    slot counts add up, and slots = 64*units + z - z_prev."""
+    px = small_image(21, 80, 112, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+    enc = encode_jpeg(px, quality=88, subsampling=sub)
+    img = OracleImage(enc.data)
+    raw = img.unstuffed()
+    nbits = raw.size * 8
+    bs = img.boundary_states(L)
+    n = len(bs["p"])
+    assert n == -(-nbits // L)
+    assert int(bs["units"].sum()) == img.total_units
+    assert int(bs["slots"].sum()) == 64 * img.total_units
+    zprev = np.concatenate([[0], bs["z"][:-1]])
+    assert np.array_equal(bs["slots"], 64 * bs["units"].astype(np.int64) + bs["z"] - zprev)
+    coef, end_bit = img.coefficients(return_end_bit=True)
+    full = img.trace(raw, end_bit, 0, max_symbols=200000)
+    by_p = {s["p"]: s for s in full}
+    for i in range(0, n, max(1, n // 25)):
+        p, u, z = int(bs["p"][i]), int(bs["u"][i]), int(bs["z"][i])
+        if p >= end_bit:
+            assert p == end_bit
+            continue
+        assert (i + 1) * L <= p < (i + 1) * L + 32
+        tail = img.trace(raw, end_bit, p, u=u, z=z, max_symbols=50)
+        assert all(by_p[s["p"]] == s for s in tail) and tail[0]["p"] == p
+        # it is the FIRST symbol at or after the boundary
+        assert max(q for q in by_p if q < p) < (i + 1) * L
+    # DC sums per subsequence telescope to the last absolute DC of each component
+    upm = img.units_per_mcu
+    comp_of_unit = [0] * (upm - 2) + [1, 2] if upm > 1 else [0]
+    for c in range(img.ncomp):
+        last = [k for k in range(img.total_units) if comp_of_unit[k % upm] == c][-1]
+        assert int(bs["dcsum"][:, c].sum()) == int(coef[last, 0])
