@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole decode path on one MI355X.
+
+A step is one jpgd_decode_batch call over one synthetic workload: unstuff, synchronisation (intra and
+inter), scan, write (with DC), pixels -- inputs already resident in HBM, outputs left in HBM.
+Prints ONE JSON line (see README / DESIGN.md, "Measurement").
+
+  python bench.py                       # benchmark configs[1]: one 1920x1088 4:4:4 q90 image
+  python bench.py --config 5            # other workloads (1..5), for the notes in the design doc
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: int) -> int:
+    """Bytes the method itself must move per launch ("Kernels"): Bs stuffed bytes, B unstuffed
+    bytes, S subsequences (16-byte records), K data units (128 bytes of int16 each), out_bytes of pixels."""
+    return {
+        "unstuff_count": Bs,
+        "unstuff_scatter": Bs + B,
+        "sync_intra": B + 16 * S,
+        "sync_inter": 16 * (S // 256 + 1),
+        "scan": 16 * S,
+        "zero": 128 * K,
+        "write": B + 16 * S + 128 * K,
+        "pixels": 128 * K + out_bytes,
+    }[kernel]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 of BASELINE.json (default 2 = configs[1])")
+    ap.add_argument("--subseq-bits", type=int, default=0)
+    ap.add_argument("--overlap", type=int, default=-1)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing; 0 skips it")
+    ap.add_argument("--limit", type=int, default=0, help="images of the batch config to use (0 = all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (nothing here is distributed)" % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2111_09219_amd as J
+    from workloads import CONFIGS, config_jpeg
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the decoder has no CPU path", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    c = args.config
+    wl = CONFIGS[c]
+    enc = config_jpeg(c, limit=args.limit or None) if c == 4 else config_jpeg(c)
+    files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
+    cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap)
+    batch = J.prepare_batch(files, cfg, device="cuda:0")
+    Bs = batch.compressed_bytes
+    pixels = batch.pixels_total
+    K = int(sum(i.total_units for i in batch.infos))
+    out_bytes = int(sum(i.width * i.height * i.ncomp for i in batch.infos))
+
+    # warm-up; the first steps also time every kernel once to find the dominant one
+    cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
+                            timing_mask=0xFF)
+    split = np.zeros(len(J.KERNELS))
+    nsplit = max(1, min(5, args.warmup))
+    rep = None
+    for w in range(max(args.warmup, nsplit)):
+        if w < nsplit:
+            rep = batch.decode(cfg=cfg_all)
+            split += np.array(list(rep.kernel_ms))
+        else:
+            rep = batch.decode()
+    split /= nsplit
+    dominant = int(np.argmax(split))
+    S = rep.n_subseq
+    B = Bs  # unstuffed length is within 0.5 % of the stuffed one; the bound is used for the byte counts
+
+    cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
+                            timing_mask=1 << dominant)
+    dom_ms = 0.0
+    dom_launches = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rep = batch.decode(cfg=cfg_dom)
+        dom_ms += rep.kernel_ms[dominant]
+        dom_launches += rep.launches[dominant]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    mbps = Bs / 1e6 / (ms_per_step / 1e3)
+    mpix = pixels / 1e6 / (ms_per_step / 1e3)
+
+    dom_name = J.KERNELS[dominant]
+    dom_avg_ms = dom_ms / max(1, dom_launches)
+    alg = algorithmic_bytes(dom_name, Bs, B, S, K, out_bytes)
+    achieved = alg / 1e9 / (dom_avg_ms / 1e3) if dom_avg_ms > 0 else 0.0
+
+    kernels = {}
+    for k, name in enumerate(J.KERNELS):
+        if rep.launches[k] == 0:
+            continue
+        ab = algorithmic_bytes(name, Bs, B, S, K, out_bytes)
+        kernels[name] = {"ms": round(float(split[k]), 5), "alg_bytes": ab,
+                         "hbm_gbs": round(ab / 1e9 / (split[k] / 1e3), 2) if split[k] > 0 else None}
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        from oracle import OracleImage
+        t_start = time.perf_counter()
+        done_bytes = 0
+        done_pixels = 0
+        reps = 0
+        imgs = files if len(files) > 1 else files * 1000
+        for f in imgs:
+            o = OracleImage(f)
+            coef = o.coefficients()
+            o.pixels(coef)
+            done_bytes += int(o.info.scan_len)
+            done_pixels += o.width * o.height
+            reps += 1
+            if time.perf_counter() - t_start > args.cpu_seconds:
+                break
+        cpu_dt = time.perf_counter() - t_start
+        cpu = {"value": round(done_bytes / 1e6 / cpu_dt, 3), "unit": "MB/s", "cores": 1, "kind": "oracle",
+               "mpixel_per_s": round(done_pixels / 1e6 / cpu_dt, 3),
+               "sample": "%d full decode(s) (entropy decode + double-precision pixels) of the same file(s), %.1f s, "
+                         "single thread" % (reps, cpu_dt)}
+
+    line = {
+        "metric": "compressed MB/s per image (whole decode path, data resident in HBM)",
+        "value": round(mbps, 2),
+        "unit": "MB/s",
+        "mpixel_per_s": round(mpix, 2),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32 bit-parsing + fp32 IDCT (int16 coefficients, u8 pixels)",
+        "data": "synthetic",
+        "config": {"workload": "configs[%d] %s: %d image(s) %dx%d %s q%s%s, %d compressed bytes" % (
+            c - 1, wl["name"], len(files), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
+            " optimized Huffman" if wl["optimize"] else "", Bs),
+            "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
+            "inter_rounds": rep.inter_rounds, "redo": rep.redo},
+        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                     "avg_launch_ms": round(dom_avg_ms, 5), "alg_bytes_per_launch": alg},
+        "cpu_baseline": cpu,
+        "kernels": kernels,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

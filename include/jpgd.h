@@ -73,17 +73,32 @@ typedef struct {
 } jpgd_info;
 
 typedef struct {
-    uint32_t subseq_bits;  /* subsequence size in bits ("s*32" in Algorithm 1): 128, 256, ..., 4096;
-                              0 = choose per call from the stream sizes                            */
+    uint32_t subseq_bits;  /* subsequence size in bits ("s*32" in Algorithm 1): 128, 256, 512, 1024
+                              or 2048; 0 = choose per call from the stream sizes                   */
     uint32_t overlap;      /* subsequences by which neighbouring sequences overlap (warm-up lanes
                               in front of each sequence); 0 = the paper's disjoint sequences;
                               must be < 192; 0xFFFFFFFF = library default                          */
     uint32_t max_rounds;   /* upper bound on inter-sequence synchronisation rounds; 0 = number of
                               sequences (always enough)                                             */
     uint32_t flags;        /* JPGD_F_* */
+    uint32_t timing_mask;  /* bit k set: bracket kernel k (JPGD_K_*) with HIP events on the stream
+                              and report its duration; 0 = no events                               */
 } jpgd_config;
 
 #define JPGD_F_NO_PIXELS 1u /* stop after the coefficients even if a pixel buffer is given */
+
+/* kernels of the pipeline, in launch order */
+enum {
+    JPGD_K_UNSTUFF_COUNT = 0, /* unstuff: bytes to drop per tile, last tile scans the counts       */
+    JPGD_K_UNSTUFF_SCATTER,   /* unstuff: compaction                                               */
+    JPGD_K_SYNC_INTRA,        /* Algorithm 3, first loop                                           */
+    JPGD_K_SYNC_INTER,        /* Algorithm 3, second loop                                          */
+    JPGD_K_SCAN,              /* exclusive scan over s_info (group totals and their prefix)        */
+    JPGD_K_ZERO,              /* clears the coefficient buffer                                     */
+    JPGD_K_WRITE,             /* Algorithm 1, write pass                                           */
+    JPGD_K_PIXELS,            /* Section 4.3 plus colour                                           */
+    JPGD_N_KERNELS
+};
 
 /* What a decode call did; filled on return (host memory). */
 typedef struct {
@@ -93,6 +108,8 @@ typedef struct {
     uint32_t inter_rounds;  /* inter-sequence rounds run                                          */
     uint32_t redo;          /* times scan+write were repeated because verification failed         */
     uint32_t device_flags;  /* raw status word from the device                                    */
+    uint32_t launches[JPGD_N_KERNELS];  /* launches of each kernel in this call                          */
+    float kernel_ms[JPGD_N_KERNELS];    /* summed duration of the launches selected by timing_mask       */
 } jpgd_report;
 
 /*
@@ -122,10 +139,11 @@ size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, con
  * Decodes n images in one go (paper, Algorithm 1, "batched").
  *
  *  infos          [host]   n parsed headers
- *  d_scans        [device] the entropy-coded bytes of all images; image i occupies
- *                          scan_offsets[i] .. scan_offsets[i] + infos[i].scan_bytes
- *  scan_offsets   [host]   n byte offsets into d_scans
- *  d_coef         [device] int16 output, may not be NULL; image i gets 64*total_units
+ *  d_scans        [device] the entropy-coded bytes of all images (still byte-stuffed, without the
+ *                          EOI marker); image i occupies scan_offsets[i] .. + infos[i].scan_bytes;
+ *                          16-byte aligned
+ *  scan_offsets   [host]   n byte offsets into d_scans, each a multiple of 16
+ *  d_coef         [device] int16 output, 16-byte aligned, may not be NULL; image i gets 64*total_units
  *                          values at element offset coef_offsets[i] (must be a multiple of 64):
  *                          data units in scan (MCU-interleaved) order, zig-zag order inside a
  *                          unit, quantised (not dequantised), DC un-differenced
@@ -163,7 +181,11 @@ int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, u
 
 /*
  * Stage-level entry points (used by the tests to check single steps against the oracle).
- * jpgd_unstuff: d_out must hold `n + 64` bytes; *out_len [host] receives the unstuffed length.
+ *
+ * jpgd_unstuff: the byte-unstuffing step alone.  d_in (16-byte aligned, n bytes) is compacted into
+ * d_out (256-byte aligned, room for n + 256 bytes: the kernel clears 192 bytes after the last one);
+ * *out_len [host] receives the unstuffed length.  d_workspace: 256-byte aligned, at least
+ * 1024 + 4 * ceil(n / 4096) bytes.  Returns after the stream has drained.
  */
 int jpgd_unstuff(const uint8_t* d_in /*[device]*/, size_t n, uint8_t* d_out /*[device]*/, size_t* out_len /*[host]*/,
                  void* d_workspace, size_t workspace_bytes, void* stream);

@@ -1,0 +1,483 @@
+// Host side of the decoder: workspace layout, per-call descriptors, kernel launches, the verdict.
+// C ABI declared in include/jpgd.h.
+#include <hip/hip_runtime.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "../../include/jpgd.h"
+#include "jpgd_common.h"
+#include "jpgd_kernels.h"
+#include "jpgd_lut.h"
+
+using namespace jpgd;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x4A504744u;  // "JPGD"
+
+// first bytes of the workspace: lets jpgd_read_sync_info find its way without the caller's help
+struct WsHeader {
+    uint32_t magic, nimg, logL, overlap;
+    uint64_t off_status, off_state, off_img, off_lut, off_qt;       // uploaded region
+    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref; // device-written regions
+    uint64_t upload_bytes, total_bytes;
+};
+
+struct Plan {
+    WsHeader h;
+    std::vector<ImgDesc> img;
+    std::vector<uint32_t> lut_of_img;  // index of the table set of image i
+    uint32_t nsets = 0, lut_slots = 0;
+    uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, zerowgs = 0, nsub_total = 0;
+    uint32_t L = 0;
+};
+
+size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+uint32_t ilog2(uint32_t v) {
+    uint32_t l = 0;
+    while ((1u << l) < v) ++l;
+    return l;
+}
+
+bool same_tables(const jpgd_info& a, const jpgd_info& b) {
+    if (a.ncomp != b.ncomp) return false;
+    for (uint32_t c = 0; c < a.ncomp; ++c) {
+        if (a.td[c] != b.td[c] || a.ta[c] != b.ta[c]) return false;
+        if (memcmp(a.dht_bits[0][a.td[c]], b.dht_bits[0][b.td[c]], 16) ||
+            memcmp(a.dht_vals[0][a.td[c]], b.dht_vals[0][b.td[c]], 256) ||
+            memcmp(a.dht_bits[1][a.ta[c]], b.dht_bits[1][b.ta[c]], 16) ||
+            memcmp(a.dht_vals[1][a.ta[c]], b.dht_vals[1][b.ta[c]], 256))
+            return false;
+    }
+    return true;
+}
+
+uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
+    (void)infos; (void)n;
+    return 1024u;  // the size the paper uses for high-quality material (Section 5, Tables II and III)
+}
+
+// Validates arguments that do not need the GPU and lays the workspace out.
+int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
+    if (!infos || n < 1) return JPGD_E_ARG;
+    uint32_t L = cfg && cfg->subseq_bits ? cfg->subseq_bits : choose_subseq_bits(infos, n);
+    if (L < 128u || L > 2048u || (L & (L - 1u))) return JPGD_E_ARG;
+    uint32_t H = (!cfg || cfg->overlap == 0xFFFFFFFFu) ? 0u : cfg->overlap;
+    if (H > (uint32_t)kMaxOverlap) return JPGD_E_ARG;
+    const uint32_t seq_len = kWG - H;
+    pl.L = L;
+    pl.img.assign(n, ImgDesc());
+    pl.lut_of_img.assign(n, 0);
+    size_t stream_bytes = 0, coef_units = 0;
+    for (int i = 0; i < n; ++i) {
+        const jpgd_info& in = infos[i];
+        ImgDesc& d = pl.img[i];
+        if (in.ncomp != 1 && in.ncomp != 3) return JPGD_E_ARG;
+        if (in.units_per_mcu < 1 || in.units_per_mcu > 6 || kPixBlocks % in.units_per_mcu) return JPGD_E_ARG;
+        if (in.scan_bytes < 1 || in.scan_bytes >= (1ull << 28)) return JPGD_E_ARG;
+        if (in.total_units < 1 || in.total_units > 0x3FFFFFFu) return JPGD_E_ARG;
+        if (in.restart_interval) return JPGD_E_UNSUPPORTED;
+        d.scan_bytes = (uint32_t)in.scan_bytes;
+        d.tile0 = pl.tiles;
+        d.ntiles = (d.scan_bytes + kUnstuffTile - 1) / kUnstuffTile;
+        pl.tiles += d.ntiles;
+        d.stream_off = stream_bytes;
+        stream_bytes += up256((size_t)d.scan_bytes + L / 8 + 64 + 16);
+        d.nsub_max = (uint32_t)(((uint64_t)d.scan_bytes * 8 + L - 1) / L);
+        d.sub0 = pl.nsub_total;
+        pl.nsub_total += (d.nsub_max + 3u) & ~3u;
+        d.seq0 = pl.seqs;
+        d.nseq_max = (d.nsub_max + seq_len - 1) / seq_len;
+        pl.seqs += d.nseq_max;
+        d.grp0 = pl.grps;
+        d.ngrp_max = (d.nsub_max + kWG - 1) / kWG;
+        pl.grps += d.ngrp_max;
+        d.bnd0 = pl.bnds;
+        d.nbnd_wg = d.nseq_max > 1 ? (d.nseq_max - 1 + 63) / 64 : 0;
+        pl.bnds += d.nbnd_wg;
+        d.total_units = in.total_units;
+        d.upm = in.units_per_mcu;
+        d.width = in.width; d.height = in.height; d.ncomp = in.ncomp;
+        d.hs = in.hsamp[0]; d.vs = in.vsamp[0];
+        d.mcus_x = in.mcus_x; d.mcus_y = in.mcus_y;
+        if (d.upm != (in.ncomp == 1 ? 1u : d.hs * d.vs + 2u)) return JPGD_E_ARG;
+        if ((uint64_t)d.mcus_x * d.mcus_y * d.upm != d.total_units) return JPGD_E_ARG;
+        const uint32_t M = kPixBlocks / d.upm;
+        d.pix_runs = (d.mcus_x + M - 1) / M;
+        d.pix_wg0 = pl.pixwgs;
+        pl.pixwgs += d.pix_runs * d.mcus_y;
+        d.zero_wg0 = pl.zerowgs;
+        d.zero_nwg = (uint32_t)(((uint64_t)d.total_units * 128 + kZeroChunk - 1) / kZeroChunk);
+        pl.zerowgs += d.zero_nwg;
+        coef_units += d.total_units;
+        // table slots: distinct DC tables first, then distinct AC tables, in order of first use
+        uint32_t dc_ids[3], ac_ids[3], ndc = 0, nac = 0, comp_dc[3], comp_ac[3];
+        for (uint32_t c = 0; c < in.ncomp; ++c) {
+            if (in.td[c] > 3 || in.ta[c] > 3 || !in.dht_present[0][in.td[c]] || !in.dht_present[1][in.ta[c]] ||
+                in.tq[c] > 3 || !in.qt_present[in.tq[c]])
+                return JPGD_E_TABLE;
+            uint32_t k;
+            for (k = 0; k < ndc && dc_ids[k] != in.td[c]; ++k) {}
+            if (k == ndc) dc_ids[ndc++] = in.td[c];
+            comp_dc[c] = k;
+            for (k = 0; k < nac && ac_ids[k] != in.ta[c]; ++k) {}
+            if (k == nac) ac_ids[nac++] = in.ta[c];
+            comp_ac[c] = k;
+        }
+        d.nslots = ndc + nac;
+        d.sched_dc = d.sched_ac = d.sched_comp = 0;
+        uint32_t u = 0;
+        for (uint32_t c = 0; c < in.ncomp; ++c) {
+            uint32_t nu = c == 0 ? d.hs * d.vs : 1u;
+            if (in.ncomp == 1) nu = 1;
+            for (uint32_t k = 0; k < nu; ++k, ++u) {
+                d.sched_dc |= comp_dc[c] << (4 * u);
+                d.sched_ac |= (ndc + comp_ac[c]) << (4 * u);
+                d.sched_comp |= c << (4 * u);
+            }
+        }
+        if (u != d.upm) return JPGD_E_ARG;
+        if (i > 0 && same_tables(infos[i - 1], in)) {
+            pl.lut_of_img[i] = pl.lut_of_img[i - 1];
+        } else {
+            pl.lut_of_img[i] = pl.nsets++;
+        }
+        if (d.nslots > pl.lut_slots) pl.lut_slots = d.nslots;
+    }
+    for (int i = 0; i < n; ++i) {
+        pl.img[i].lut_off = pl.lut_of_img[i] * (uint32_t)kMaxSlots * kLutEntries;
+        pl.img[i].qt_off = (uint32_t)i * 192u;
+    }
+    if (pl.nsub_total > 0x7FFFFFF0u || pl.tiles > 0x7FFFFFF0u) return JPGD_E_ARG;
+
+    WsHeader& h = pl.h;
+    memset(&h, 0, sizeof h);
+    h.magic = kMagic; h.nimg = (uint32_t)n; h.logL = ilog2(L); h.overlap = H;
+    size_t off = up256(sizeof(WsHeader));
+    h.off_status = off; off = up256(off + sizeof(Status));
+    h.off_state = off;  off = up256(off + sizeof(ImgState) * (size_t)n);
+    h.off_img = off;    off = up256(off + sizeof(ImgDesc) * (size_t)n);
+    h.off_lut = off;    off = up256(off + (size_t)pl.nsets * kMaxSlots * kLutEntries * 2);
+    h.off_qt = off;     off = up256(off + (size_t)n * 192 * 2);
+    h.upload_bytes = off;
+    h.off_tiles = off;  off = up256(off + (size_t)pl.tiles * 4);
+    h.off_stream = off; off = up256(off + stream_bytes);
+    h.off_sinfo = off;  off = up256(off + (size_t)pl.nsub_total * sizeof(SInfo));
+    h.off_gtot = off;   off = up256(off + (size_t)pl.grps * 16);
+    h.off_gpref = off;  off = up256(off + (size_t)pl.grps * 16);
+    h.total_bytes = off;
+    return JPGD_OK;
+}
+
+// ---- pinned staging for the per-call upload ----------------------------------------------------------
+struct Staging {
+    std::mutex mu;
+    uint8_t* buf[2] = {nullptr, nullptr};
+    size_t cap[2] = {0, 0};
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    bool pending[2] = {false, false};
+    uint32_t* verdict = nullptr;  // pinned, 64 bytes
+    int turn = 0;
+    std::vector<hipEvent_t> timers;  // pairs of events for timing_mask
+};
+Staging g_stage;
+
+int stage_acquire(size_t bytes, int* slot) {
+    Staging& s = g_stage;
+    int k = s.turn;
+    s.turn ^= 1;
+    if (s.pending[k]) {
+        if (hipEventSynchronize(s.ev[k]) != hipSuccess) return JPGD_E_HIP;
+        s.pending[k] = false;
+    }
+    if (!s.ev[k] && hipEventCreateWithFlags(&s.ev[k], hipEventDisableTiming) != hipSuccess) return JPGD_E_HIP;
+    if (s.cap[k] < bytes) {
+        if (s.buf[k]) (void)hipHostFree(s.buf[k]);
+        s.buf[k] = nullptr;
+        s.cap[k] = 0;
+        size_t want = bytes + (bytes >> 2) + 4096;
+        if (hipHostMalloc((void**)&s.buf[k], want, hipHostMallocDefault) != hipSuccess) return JPGD_E_HIP;
+        s.cap[k] = want;
+    }
+    if (!s.verdict && hipHostMalloc((void**)&s.verdict, 64, hipHostMallocDefault) != hipSuccess) return JPGD_E_HIP;
+    *slot = k;
+    return JPGD_OK;
+}
+
+#define HIP_OK(expr)                                    \
+    do {                                                \
+        if ((expr) != hipSuccess) return JPGD_E_HIP;    \
+    } while (0)
+
+size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
+    uint32_t wps = L / 32, nwords = kWG * wps + 4;
+    uint32_t ps = ilog2(wps) > 5 ? ilog2(wps) : 5;
+    return (size_t)lut_slots * kLutEntries * 2 + 4 * kWG * 4 + ((size_t)nwords + (nwords >> ps) + 4) * 4;
+}
+size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
+    uint32_t wps = L / 32, nwords = kWG * wps + 4;
+    uint32_t ps = ilog2(wps) > 5 ? ilog2(wps) : 5;
+    return (size_t)lut_slots * kLutEntries * 2 + ((size_t)nwords + (nwords >> ps) + 4) * 4;
+}
+
+std::once_flag g_attr_once;
+int g_attr_rc = JPGD_OK;
+void set_kernel_attributes() {
+    const int max_lds = 160 * 1024;
+    if (hipFuncSetAttribute((const void*)k_sync_intra, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess ||
+        hipFuncSetAttribute((const void*)k_write, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess ||
+        hipFuncSetAttribute((const void*)k_sync_inter, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
+        g_attr_rc = JPGD_E_HIP;
+}
+
+}  // namespace
+
+extern "C" size_t jpgd_workspace_bytes(const jpgd_info* infos, int n_images, const jpgd_config* cfg) {
+    Plan pl;
+    if (make_plan(infos, n_images, cfg, pl) != JPGD_OK) return 0;
+    return pl.h.total_bytes;
+}
+
+extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                                 int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
+                                 const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
+                                 const jpgd_config* cfg, void* stream_v, jpgd_report* report) {
+    if (!infos || n < 1 || !d_scans || !scan_offsets || !d_coef || !coef_offsets || !d_workspace) return JPGD_E_ARG;
+    if (d_pixels && !pixel_offsets) return JPGD_E_ARG;
+    if (((uintptr_t)d_scans & 15u) || ((uintptr_t)d_coef & 15u)) return JPGD_E_ARG;
+    if ((uintptr_t)d_workspace & 255u) return JPGD_E_WORKSPACE;
+    Plan pl;
+    int rc = make_plan(infos, n, cfg, pl);
+    if (rc) return rc;
+    if (workspace_bytes < pl.h.total_bytes) return JPGD_E_WORKSPACE;
+    const bool want_pixels = d_pixels && !(cfg && (cfg->flags & JPGD_F_NO_PIXELS));
+    for (int i = 0; i < n; ++i) {
+        if (scan_offsets[i] & 15u) return JPGD_E_ARG;
+        if (coef_offsets[i] & 63u) return JPGD_E_ARG;
+        pl.img[i].scan_off = scan_offsets[i];
+        pl.img[i].coef_off = coef_offsets[i];
+        pl.img[i].pix_off = want_pixels ? pixel_offsets[i] : 0;
+    }
+    hipStream_t stream = (hipStream_t)stream_v;
+    std::call_once(g_attr_once, set_kernel_attributes);
+    if (g_attr_rc) return g_attr_rc;
+    const size_t lds_sync = lds_sync_bytes(pl.L, pl.lut_slots), lds_write = lds_write_bytes(pl.L, pl.lut_slots);
+    const size_t lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
+    if (lds_sync > 160 * 1024) return JPGD_E_ARG;
+
+    std::lock_guard<std::mutex> lock(g_stage.mu);
+    int slot;
+    rc = stage_acquire(pl.h.upload_bytes, &slot);
+    if (rc) return rc;
+    uint8_t* up = g_stage.buf[slot];
+    memset(up, 0, pl.h.upload_bytes);
+    memcpy(up, &pl.h, sizeof pl.h);
+    memcpy(up + pl.h.off_img, pl.img.data(), sizeof(ImgDesc) * (size_t)n);
+    uint16_t* luts = (uint16_t*)(up + pl.h.off_lut);
+    uint16_t* qts = (uint16_t*)(up + pl.h.off_qt);
+    for (int i = 0; i < n; ++i) {
+        const jpgd_info& in = infos[i];
+        const ImgDesc& d = pl.img[i];
+        if (i == 0 || pl.lut_of_img[i] != pl.lut_of_img[i - 1]) {
+            uint16_t* set = luts + d.lut_off;
+            for (uint32_t u = 0; u < d.upm; ++u) {
+                uint32_t c = (d.sched_comp >> (4 * u)) & 15u;
+                uint32_t sd = (d.sched_dc >> (4 * u)) & 15u, sa = (d.sched_ac >> (4 * u)) & 15u;
+                if (!build_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, set + sd * kLutEntries) ||
+                    !build_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, set + sa * kLutEntries))
+                    return JPGD_E_TABLE;
+            }
+        }
+        for (uint32_t c = 0; c < in.ncomp; ++c)
+            for (int k = 0; k < 64; ++k) qts[d.qt_off + c * 64 + k] = in.qt[in.tq[c]][k];
+    }
+    uint8_t* ws = (uint8_t*)d_workspace;
+    HIP_OK(hipMemcpyAsync(ws, up, pl.h.upload_bytes, hipMemcpyHostToDevice, stream));
+    HIP_OK(hipEventRecord(g_stage.ev[slot], stream));
+    g_stage.pending[slot] = true;
+
+    Params P;
+    P.img = (const ImgDesc*)(ws + pl.h.off_img);
+    P.st = (ImgState*)(ws + pl.h.off_state);
+    P.status = (Status*)(ws + pl.h.off_status);
+    P.scans = d_scans;
+    P.stream = ws + pl.h.off_stream;
+    P.tile_cnt = (uint32_t*)(ws + pl.h.off_tiles);
+    P.sinfo = (SInfo*)(ws + pl.h.off_sinfo);
+    P.grp_tot = (int4*)(ws + pl.h.off_gtot);
+    P.grp_pref = (int4*)(ws + pl.h.off_gpref);
+    P.luts = (const uint16_t*)(ws + pl.h.off_lut);
+    P.qts = (const uint16_t*)(ws + pl.h.off_qt);
+    P.coef = d_coef;
+    P.pixels = d_pixels;
+    P.nimg = (uint32_t)n;
+    P.logL = pl.h.logL;
+    P.overlap = pl.h.overlap;
+    P.seq_len = kWG - pl.h.overlap;
+    P.lut_slots = pl.lut_slots;
+
+    // optional bracketing of single kernels with events (jpgd_config.timing_mask)
+    const uint32_t tmask = cfg ? cfg->timing_mask : 0u;
+    struct Timed { int kernel; size_t ev; };
+    std::vector<Timed> timed;
+    uint32_t launches[JPGD_N_KERNELS] = {0};
+    auto t_begin = [&](int k) -> int {
+        launches[k]++;
+        if (!(tmask & (1u << k))) return JPGD_OK;
+        size_t need = 2 * (timed.size() + 1);
+        while (g_stage.timers.size() < need) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return JPGD_E_HIP;
+            g_stage.timers.push_back(e);
+        }
+        timed.push_back({k, 2 * timed.size()});
+        return hipEventRecord(g_stage.timers[timed.back().ev], stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
+    };
+    auto t_end = [&](int k) -> int {
+        if (!(tmask & (1u << k))) return JPGD_OK;
+        return hipEventRecord(g_stage.timers[timed.back().ev + 1], stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
+    };
+#define LAUNCH(K, kernel, grid, block, lds)                                   \
+    do {                                                                      \
+        if ((rc = t_begin(K)) != JPGD_OK) return rc;                          \
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, stream, P);  \
+        if ((rc = t_end(K)) != JPGD_OK) return rc;                            \
+    } while (0)
+
+    LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles, kWG, 0);
+    LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
+    LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra, pl.seqs, kWG, lds_sync);
+
+    uint32_t rounds = 0, redo = 0, flags = 0;
+    const uint32_t max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
+    for (;;) {
+        if (pl.bnds) {
+            LAUNCH(JPGD_K_SYNC_INTER, k_sync_inter, pl.bnds, 64, lds_inter);
+            ++rounds;
+        }
+        LAUNCH(JPGD_K_SCAN, k_group_totals, pl.grps, kWG, 0);
+        LAUNCH(JPGD_K_ZERO, k_zero_coef, pl.zerowgs, kWG, 0);
+        LAUNCH(JPGD_K_WRITE, k_write, pl.grps, kWG, lds_write);
+        HIP_OK(hipGetLastError());
+        HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + pl.h.off_status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+        HIP_OK(hipStreamSynchronize(stream));
+        flags = g_stage.verdict[0];
+        const bool chain_broken = (flags & (kStMismatch | kStUnit)) != 0;
+        // A broken chain with more than one sequence may only mean that synchronisation needs another
+        // inter-sequence round (paper: the host repeats the phase until all sequences are synchronised).
+        if (!chain_broken || !pl.bnds || rounds >= max_rounds) break;
+        ++redo;
+        HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
+    }
+    if (!flags && want_pixels) {
+        LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
+        HIP_OK(hipGetLastError());
+        HIP_OK(hipStreamSynchronize(stream));
+    }
+#undef LAUNCH
+    if (report) {
+        memset(report, 0, sizeof *report);
+        report->subseq_bits = pl.L;
+        report->n_subseq = pl.nsub_total;
+        report->n_sequences = pl.seqs;
+        report->inter_rounds = rounds;
+        report->redo = redo;
+        report->device_flags = flags;
+        for (int k = 0; k < JPGD_N_KERNELS; ++k) report->launches[k] = launches[k];
+        for (const Timed& t : timed) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, g_stage.timers[t.ev], g_stage.timers[t.ev + 1]) == hipSuccess)
+                report->kernel_ms[t.kernel] += ms;
+        }
+    }
+    return flags ? JPGD_E_CORRUPT : JPGD_OK;
+}
+
+extern "C" int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
+                           void* d_workspace, size_t workspace_bytes, const jpgd_config* cfg, void* stream,
+                           jpgd_report* report) {
+    const uint64_t zero = 0;
+    return jpgd_decode_batch(1, info, d_scan, &zero, d_coef, &zero, d_pixels, &zero, d_workspace, workspace_bytes, cfg,
+                             stream, report);
+}
+
+extern "C" int jpgd_read_sync_info(const void* d_workspace, int image, uint32_t capacity, uint32_t* n_subseq,
+                                   uint64_t* p, uint32_t* u, uint32_t* z, uint32_t* units, int32_t* dcsum,
+                                   void* stream_v) {
+    if (!d_workspace || image < 0 || !n_subseq || !p || !u || !z || !units || !dcsum) return JPGD_E_ARG;
+    hipStream_t stream = (hipStream_t)stream_v;
+    const uint8_t* ws = (const uint8_t*)d_workspace;
+    WsHeader h;
+    HIP_OK(hipMemcpyAsync(&h, ws, sizeof h, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+    if (h.magic != kMagic || (uint32_t)image >= h.nimg) return JPGD_E_ARG;
+    ImgDesc d;
+    ImgState st;
+    HIP_OK(hipMemcpyAsync(&d, ws + h.off_img + sizeof(ImgDesc) * (size_t)image, sizeof d, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(&st, ws + h.off_state + sizeof(ImgState) * (size_t)image, sizeof st, hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+    *n_subseq = st.nsub;
+    if (st.nsub > capacity) return JPGD_E_ARG;
+    std::vector<SInfo> rec(st.nsub);
+    if (st.nsub) {
+        HIP_OK(hipMemcpyAsync(rec.data(), ws + h.off_sinfo + sizeof(SInfo) * (size_t)d.sub0, sizeof(SInfo) * (size_t)st.nsub,
+                              hipMemcpyDeviceToHost, stream));
+        HIP_OK(hipStreamSynchronize(stream));
+    }
+    for (uint32_t i = 0; i < st.nsub; ++i) {
+        p[i] = ((uint64_t)(i + 1) << h.logL) + state_prel(rec[i].x);
+        z[i] = state_z(rec[i].x);
+        u[i] = state_u(rec[i].x);
+        units[i] = rec[i].y;
+        dcsum[3 * i + 0] = (int16_t)(rec[i].z & 0xFFFFu);
+        dcsum[3 * i + 1] = (int16_t)(rec[i].z >> 16);
+        dcsum[3 * i + 2] = (int16_t)(rec[i].w & 0xFFFFu);
+    }
+    return JPGD_OK;
+}
+
+extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_t* out_len, void* d_workspace,
+                            size_t workspace_bytes, void* stream_v) {
+    if (!d_in || !d_out || !out_len || !d_workspace || n < 1 || n >= (1ull << 28)) return JPGD_E_ARG;
+    if (((uintptr_t)d_in & 15u) || ((uintptr_t)d_out & 255u) || ((uintptr_t)d_workspace & 255u)) return JPGD_E_ARG;
+    const uint32_t tiles = (uint32_t)((n + kUnstuffTile - 1) / kUnstuffTile);
+    const size_t off_state = 0, off_img = 256, off_tiles = up256(256 + sizeof(ImgDesc));
+    const size_t need = up256(off_tiles + (size_t)tiles * 4);
+    if (workspace_bytes < need) return JPGD_E_WORKSPACE;
+    hipStream_t stream = (hipStream_t)stream_v;
+    std::lock_guard<std::mutex> lock(g_stage.mu);
+    int slot;
+    int rc = stage_acquire(off_tiles, &slot);
+    if (rc) return rc;
+    uint8_t* up = g_stage.buf[slot];
+    memset(up, 0, off_tiles);
+    ImgDesc d;
+    memset(&d, 0, sizeof d);
+    d.scan_bytes = (uint32_t)n;
+    d.ntiles = tiles;
+    memcpy(up + off_img, &d, sizeof d);
+    uint8_t* ws = (uint8_t*)d_workspace;
+    HIP_OK(hipMemcpyAsync(ws, up, off_tiles, hipMemcpyHostToDevice, stream));
+    HIP_OK(hipEventRecord(g_stage.ev[slot], stream));
+    g_stage.pending[slot] = true;
+    Params P;
+    memset(&P, 0, sizeof P);
+    P.img = (const ImgDesc*)(ws + off_img);
+    P.st = (ImgState*)(ws + off_state);
+    P.scans = d_in;
+    P.stream = d_out;
+    P.tile_cnt = (uint32_t*)(ws + off_tiles);
+    P.nimg = 1;
+    P.logL = 10;
+    hipLaunchKernelGGL(k_unstuff_count, dim3(tiles), dim3(kWG), 0, stream, P);
+    hipLaunchKernelGGL(k_unstuff_scatter, dim3(tiles), dim3(kWG), 0, stream, P);
+    HIP_OK(hipGetLastError());
+    HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + off_state, sizeof(ImgState), hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipStreamSynchronize(stream));
+    *out_len = g_stage.verdict[0];
+    return JPGD_OK;
+}

@@ -1,0 +1,127 @@
+// Internal definitions shared by the host code and the gfx950 kernels.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define JPGD_HD __host__ __device__ __forceinline__
+#else
+#define JPGD_HD inline
+#endif
+
+namespace jpgd {
+
+// ---- geometry of the parallel decomposition (paper, Section 4.1, Algorithm 1) ----------------
+// subsequence : L bits of the unstuffed stream, one lane
+// sequence    : the subsequences one workgroup synchronises among itself ("b" in the paper)
+constexpr int kWG = 256;          // lanes per workgroup of the sync and write kernels
+constexpr int kMaxOverlap = 191;  // warm-up lanes a sequence may borrow from its predecessor
+
+// ---- Huffman lookup tables ---------------------------------------------------------------------
+// One table = kLutL1 first-level entries indexed by the next kLutK bits, followed by up to kLutL2
+// second-level entries for codewords longer than kLutK bits.  uint16 entries:
+//   bit 15      first level : escape, (bits 0..8 = offset into the second level, bits 9..11 = number of
+//                             further bits that index it)
+//               second level: no codeword starts with these bits (consume one bit, state unchanged)
+//   bit 14      end-of-block class (AC symbol with zero size and run != 15)
+//   bits 10..13 run of zeros before the coefficient
+//   bits 5..9   number of value bits
+//   bits 0..4   codeword length
+// Bound on the second level: codes of one length are consecutive, so those of length l > kLutK touch
+// at most n_l / 2^(l-kLutK) + 2 first-level prefixes; summed over l = 11..16 with at most 256 symbols
+// this is below 512 entries.
+constexpr int kLutK = 10;
+constexpr int kLutL1 = 1 << kLutK;
+constexpr int kLutL2 = 512;
+constexpr int kLutEntries = kLutL1 + kLutL2;
+constexpr int kMaxSlots = 6;  // up to 3 DC and 3 AC tables per image (one pair per component)
+
+constexpr uint16_t kLutEscape = 0x8000;
+constexpr uint16_t kLutNop = 0x8000;
+constexpr uint16_t kLutEob = 0x4000;
+
+// ---- s_info (paper, Section 4.1): one 16-byte record per subsequence --------------------------
+//  x : decoder state after the last symbol that starts inside the subsequence
+//        bits 0..5   p - (i+1)*L  (bit position relative to the end of the subsequence, 0..31)
+//        bits 6..11  z            (zig-zag index of the next coefficient)
+//        bits 12..15 u            (data unit inside the MCU)
+//  y : data units completed by the symbols that start inside the subsequence.  The paper's count n
+//      (zig-zag slots covered) is 64*y + z_i - z_{i-1}; keeping units and z apart makes the exclusive
+//      scan deliver the output position as (unit index, z) without overflow.
+//  z : sum of DC differences of component 0 (low 16 bits) and component 1 (high 16 bits), wrapped
+//  w : the same for component 2 (low 16 bits)
+struct SInfo {
+    uint32_t x, y, z, w;
+};
+
+JPGD_HD uint32_t pack_state(uint32_t p_rel, uint32_t z, uint32_t u) { return (p_rel & 63u) | (z << 6) | (u << 12); }
+JPGD_HD uint32_t state_prel(uint32_t x) { return x & 63u; }
+JPGD_HD uint32_t state_z(uint32_t x) { return (x >> 6) & 63u; }
+JPGD_HD uint32_t state_u(uint32_t x) { return (x >> 12) & 15u; }
+
+// ---- per-image descriptor, built on the host and uploaded with every call ----------------------
+struct ImgDesc {
+    // input
+    uint64_t scan_off;     // byte offset of the stuffed scan inside d_scans (multiple of 16)
+    uint32_t scan_bytes;   // stuffed length
+    uint32_t tile0;        // first unstuff tile of this image
+    uint32_t ntiles;
+    // unstuffed stream
+    uint64_t stream_off;   // byte offset inside the workspace's stream region (multiple of 256)
+    // decomposition (upper bounds from the stuffed size; the true counts live in ImgState)
+    uint32_t sub0;         // first s_info record of this image
+    uint32_t nsub_max;
+    uint32_t seq0;         // first workgroup of the intra-sequence kernel
+    uint32_t nseq_max;
+    uint32_t grp0;         // first workgroup of the scan/write kernels (groups of kWG subsequences)
+    uint32_t ngrp_max;
+    uint32_t bnd0;         // first workgroup of the inter-sequence kernel (64 boundaries each)
+    uint32_t nbnd_wg;
+    // scan syntax
+    uint32_t total_units;
+    uint32_t upm;          // data units per MCU
+    uint32_t sched_dc;     // 4 bits per unit u: LUT slot of its DC table
+    uint32_t sched_ac;     //                     ... of its AC table
+    uint32_t sched_comp;   //                     component of unit u
+    uint32_t lut_off;      // element (uint16) offset of this image's tables inside the LUT region
+    uint32_t nslots;       // tables this image uses
+    // output
+    uint64_t coef_off;     // element offset into d_coef
+    uint64_t pix_off;      // byte offset into d_pixels
+    uint32_t width, height, ncomp;
+    uint32_t hs, vs;       // luma sampling factors
+    uint32_t mcus_x, mcus_y;
+    uint32_t pix_wg0;      // first workgroup of the pixel kernel
+    uint32_t pix_runs;     // workgroups per MCU row
+    uint32_t qt_off;       // element (uint16) offset of 3 x 64 quantisation values (per component, zig-zag)
+    uint32_t zero_wg0;     // first workgroup of the coefficient zero-fill
+    uint32_t zero_nwg;
+    uint32_t pad_;
+};
+
+// written by the unstuff kernels
+struct ImgState {
+    uint32_t nbytes;   // unstuffed length B
+    uint32_t nsub;     // ceil(8B / L)
+    uint32_t tiles_done;  // arrival counters of the last-workgroup-done reductions
+    uint32_t grps_done;
+};
+
+// status word bits (device -> host)
+constexpr uint32_t kStMismatch = 1u;   // a write lane did not end in the state recorded for its subsequence
+constexpr uint32_t kStInvalid = 2u;    // write pass met bits that are no codeword, or a run past slot 63
+constexpr uint32_t kStShort = 4u;      // stream ended before all data units were decoded
+constexpr uint32_t kStUnit = 8u;       // unit index and recorded data-unit phase disagree
+
+struct Status {
+    uint32_t flags;
+    uint32_t inter_changed;  // boundaries whose first comparison failed in the last inter-sequence round
+    uint32_t pad[2];
+};
+
+constexpr int kUnstuffTile = 4096;  // bytes per workgroup of the unstuff kernels (256 lanes x 16 bytes)
+constexpr int kPixBlocks = 48;      // data units per workgroup of the pixel kernel
+constexpr uint32_t kZeroChunk = 1u << 16;  // bytes per workgroup of the zero-fill
+
+JPGD_HD uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace jpgd

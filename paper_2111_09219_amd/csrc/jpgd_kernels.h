@@ -1,0 +1,602 @@
+// gfx950 kernels of the decoder.  Included once, by jpgd.hip.
+//
+// Launch geometry: every kernel runs kWG = 256 lanes (four wave64) per workgroup, except the
+// inter-sequence kernel (one wave64).  A workgroup finds its image by bisection over the per-image
+// first-workgroup fields of ImgDesc, so one launch covers a whole batch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "jpgd_common.h"
+#include "jpgd_idct.h"
+#include "jpgd_lane.h"
+
+namespace jpgd {
+
+struct Params {
+    const ImgDesc* img;
+    ImgState* st;
+    Status* status;
+    const uint8_t* scans;
+    uint8_t* stream;        // unstuffed streams, image i at img[i].stream_off
+    uint32_t* tile_cnt;     // per unstuff tile: bytes removed in it, then (in place) bytes removed before it
+    SInfo* sinfo;
+    int4* grp_tot;          // per group of kWG subsequences: (units, dc0, dc1, dc2) totals
+    int4* grp_pref;         // exclusive prefix of grp_tot inside the image
+    const uint16_t* luts;
+    const uint16_t* qts;
+    int16_t* coef;
+    uint8_t* pixels;
+    uint32_t nimg;
+    uint32_t logL;          // log2 of the subsequence size in bits
+    uint32_t overlap;       // H: warm-up lanes in front of each sequence
+    uint32_t seq_len;       // kWG - H: subsequences a sequence owns
+    uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
+};
+
+// ---- small helpers ------------------------------------------------------------------------------
+
+template <class F>
+__device__ __forceinline__ uint32_t find_image(const Params& P, uint32_t wg, F first_wg) {
+    uint32_t lo = 0, hi = P.nimg;  // last image whose first workgroup is <= wg
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (first_wg(P.img[mid]) <= wg) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+    const uint32_t lane = threadIdx.x & 63u;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(v, d, 64);
+        if (lane >= (uint32_t)d) v += o;
+    }
+    return v;
+}
+
+// exclusive prefix of v over the 256 lanes of the workgroup; *total gets the sum.  scratch: 8 words of LDS.
+__device__ __forceinline__ uint32_t wg_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+    uint32_t inc = wave_incl_scan(v);
+    uint32_t wave = threadIdx.x >> 6;
+    __syncthreads();  // scratch may still be read from a previous use
+    if ((threadIdx.x & 63u) == 63u) scratch[wave] = inc;
+    __syncthreads();
+    uint32_t w0 = scratch[0], w1 = scratch[1], w2 = scratch[2], w3 = scratch[3];
+    uint32_t before = wave == 0 ? 0u : wave == 1 ? w0 : wave == 2 ? w0 + w1 : w0 + w1 + w2;
+    *total = w0 + w1 + w2 + w3;
+    return before + inc - v;
+}
+
+// "last workgroup done": returns true in exactly one workgroup per counter, the one that arrives last,
+// after which all data the others wrote before calling is visible to it.  No workgroup waits.
+__device__ __forceinline__ bool last_workgroup_arrives(uint32_t* counter, uint32_t expected, uint32_t* flag_lds) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        *flag_lds = (old == expected - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    bool last = *flag_lds != 0u;
+    if (last) __threadfence();
+    return last;
+}
+
+__device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, uint16_t* lut_s) {
+    const uint32_t n16 = D.nslots * (uint32_t)kLutEntries;       // uint16 count, multiple of 8
+    const uint4* src = reinterpret_cast<const uint4*>(P.luts + D.lut_off);
+    uint4* dst = reinterpret_cast<uint4*>(lut_s);
+    for (uint32_t k = threadIdx.x; k < n16 / 8u; k += blockDim.x) dst[k] = src[k];
+}
+
+__device__ __forceinline__ Syntax syntax_of(const ImgDesc& D) {
+    Syntax sx;
+    sx.sched_dc = D.sched_dc;
+    sx.sched_ac = D.sched_ac;
+    sx.sched_comp = D.sched_comp;
+    sx.upm4 = D.upm * 4u;
+    return sx;
+}
+
+// LDS copy of a stretch of the stream as big-endian 32-bit words, one pad word after every 2^pad_shift
+// words so that lanes whose subsequences are a power of two apart hit different banks.
+__device__ __forceinline__ uint32_t padded(uint32_t r, uint32_t pad_shift) { return r + (r >> pad_shift); }
+
+__device__ __forceinline__ void stage_stream(const uint8_t* stream_img, uint32_t first_word, uint32_t nwords,
+                                             uint32_t pad_shift, uint32_t* strm) {
+    // nwords is a multiple of 4 and first_word*4 a multiple of 16
+    const uint4* src = reinterpret_cast<const uint4*>(stream_img + (size_t)first_word * 4u);
+    for (uint32_t k = threadIdx.x; k < nwords / 4u; k += blockDim.x) {
+        uint4 v = src[k];
+        uint32_t r = k * 4u;
+        strm[padded(r + 0u, pad_shift)] = __builtin_bswap32(v.x);
+        strm[padded(r + 1u, pad_shift)] = __builtin_bswap32(v.y);
+        strm[padded(r + 2u, pad_shift)] = __builtin_bswap32(v.z);
+        strm[padded(r + 3u, pad_shift)] = __builtin_bswap32(v.w);
+    }
+}
+
+__device__ __forceinline__ uint32_t pad_shift_for(uint32_t logL) {
+    uint32_t words_log = logL - 5u;  // log2(words per subsequence)
+    return words_log > 5u ? words_log : 5u;
+}
+
+// ---- unstuffing (byte compaction) -----------------------------------------------------------------
+// A 0x00 is dropped iff the byte before it is 0xFF: inside entropy-coded data without restart markers a
+// 0xFF is always followed by its stuffed 0x00, so the decision is local.
+
+struct UnstuffLane {
+    uint32_t bytes[4];  // 16 input bytes
+    uint32_t keep_mask; // bit j set = byte j is kept
+    uint32_t nvalid;    // bytes of this lane that exist
+};
+
+__device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_t n, uint32_t pos) {
+    UnstuffLane r;
+    r.nvalid = pos >= n ? 0u : (n - pos < 16u ? n - pos : 16u);
+    if (r.nvalid == 16u) {
+        uint4 v = *reinterpret_cast<const uint4*>(scan + pos);
+        r.bytes[0] = v.x; r.bytes[1] = v.y; r.bytes[2] = v.z; r.bytes[3] = v.w;
+    } else {
+        r.bytes[0] = r.bytes[1] = r.bytes[2] = r.bytes[3] = 0u;
+        for (uint32_t j = 0; j < r.nvalid; ++j) r.bytes[j >> 2] |= (uint32_t)scan[pos + j] << (8u * (j & 3u));
+    }
+    uint32_t prev = (pos > 0u && r.nvalid) ? scan[pos - 1u] : 0u;
+    uint32_t mask = 0u;
+#pragma unroll
+    for (uint32_t j = 0; j < 16u; ++j) {
+        uint32_t b = (r.bytes[j >> 2] >> (8u * (j & 3u))) & 255u;
+        bool drop = (b == 0u) && (prev == 255u);
+        if (j < r.nvalid && !drop) mask |= 1u << j;
+        prev = b;
+    }
+    r.keep_mask = mask;
+    return r;
+}
+
+__global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
+    __shared__ uint32_t scratch[8];
+    __shared__ uint32_t flag;
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t lt = wg - D.tile0;
+    const uint8_t* scan = P.scans + D.scan_off;
+    const uint32_t pos = lt * (uint32_t)kUnstuffTile + threadIdx.x * 16u;
+    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos);
+    uint32_t removed = u.nvalid - (uint32_t)__popc(u.keep_mask);
+    uint32_t total;
+    wg_excl_scan(removed, scratch, &total);
+    if (threadIdx.x == 0) P.tile_cnt[wg] = total;
+
+    if (!last_workgroup_arrives(&P.st[ii].tiles_done, D.ntiles, &flag)) return;
+    // this workgroup arrived last for image ii: turn the per-tile counts into exclusive prefixes
+    uint32_t carry = 0u;
+    for (uint32_t base = 0; base < D.ntiles; base += kWG) {
+        uint32_t k = base + threadIdx.x;
+        uint32_t v = k < D.ntiles ? P.tile_cnt[D.tile0 + k] : 0u;
+        uint32_t chunk_total;
+        uint32_t ex = wg_excl_scan(v, scratch, &chunk_total);
+        if (k < D.ntiles) P.tile_cnt[D.tile0 + k] = carry + ex;
+        carry += chunk_total;
+    }
+    if (threadIdx.x == 0) {
+        uint32_t nbytes = D.scan_bytes - carry;
+        P.st[ii].nbytes = nbytes;
+        uint32_t L = 1u << P.logL;
+        P.st[ii].nsub = (uint32_t)(((uint64_t)nbytes * 8u + L - 1u) >> P.logL);
+        P.st[ii].tiles_done = 0u;
+    }
+}
+
+__global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
+    __shared__ uint32_t scratch[8];
+    __shared__ __attribute__((aligned(16))) uint8_t buf[kUnstuffTile + 16];
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t lt = wg - D.tile0;
+    const uint8_t* scan = P.scans + D.scan_off;
+    uint8_t* out = P.stream + D.stream_off;
+    const uint32_t pos = lt * (uint32_t)kUnstuffTile + threadIdx.x * 16u;
+    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos);
+    uint32_t kept = (uint32_t)__popc(u.keep_mask);
+    uint32_t T;
+    uint32_t off = wg_excl_scan(kept, scratch, &T);
+#pragma unroll
+    for (uint32_t j = 0; j < 16u; ++j)
+        if (u.keep_mask & (1u << j)) buf[off++] = (uint8_t)(u.bytes[j >> 2] >> (8u * (j & 3u)));
+    __syncthreads();
+    // output position of this tile's first kept byte
+    const uint32_t o = lt * (uint32_t)kUnstuffTile - P.tile_cnt[wg];
+    const uint32_t a = o & 3u;
+    const uint32_t nd = (a + T + 3u) >> 2;
+    uint32_t* out32 = reinterpret_cast<uint32_t*>(out + (o - a));
+    for (uint32_t d = threadIdx.x; d < nd; d += kWG) {
+        int32_t s0 = (int32_t)(4u * d) - (int32_t)a;
+        if (s0 >= 0 && (uint32_t)s0 + 4u <= T) {
+            uint32_t v = (uint32_t)buf[s0] | ((uint32_t)buf[s0 + 1] << 8) | ((uint32_t)buf[s0 + 2] << 16) |
+                         ((uint32_t)buf[s0 + 3] << 24);
+            out32[d] = v;
+        } else {
+            for (int32_t b = 0; b < 4; ++b) {
+                int32_t s = s0 + b;
+                if (s >= 0 && (uint32_t)s < T) out[o - a + 4u * d + (uint32_t)b] = buf[s];
+            }
+        }
+    }
+    // the last tile clears what lanes may read past the end: one subsequence plus 64 bytes
+    if (lt == D.ntiles - 1u) {
+        const uint32_t nbytes = P.st[ii].nbytes;
+        const uint32_t clear = (1u << (P.logL - 3u)) + 64u;
+        for (uint32_t k = threadIdx.x; k < clear; k += kWG) out[nbytes + k] = 0u;
+    }
+}
+
+// ---- synchronisation, intra-sequence (paper, Algorithm 3, first loop) --------------------------------
+// Workgroup w of an image covers the kWG subsequences base .. base+kWG-1, base = w*seq_len - overlap, and
+// publishes the records of the last seq_len of them; the first `overlap` lanes only warm the chain up.
+
+__global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t nsub = P.st[ii].nsub;
+    const int32_t base = (int32_t)((wg - D.seq0) * P.seq_len) - (int32_t)P.overlap;
+    if (base >= (int32_t)nsub || (int32_t)((wg - D.seq0) * P.seq_len) >= (int32_t)nsub) return;  // nothing owned
+
+    uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
+    uint32_t* sw = reinterpret_cast<uint32_t*>(lut_s + P.lut_slots * (uint32_t)kLutEntries);
+    uint32_t* pnb = sw + kWG;
+    uint32_t* pdc01 = pnb + kWG;
+    uint32_t* pdc2 = pdc01 + kWG;
+    uint32_t* strm = pdc2 + kWG;
+
+    const uint32_t L = 1u << P.logL, wps = L >> 5;  // words per subsequence
+    const uint32_t first = base < 0 ? 0u : (uint32_t)base;
+    const uint32_t t0 = (uint32_t)((int32_t)first - base);                  // first lane with a subsequence
+    const uint32_t t1 = min((uint32_t)kWG, (uint32_t)((int32_t)nsub - base));  // one past the last such lane
+    const uint32_t first_word = first * wps;
+    const uint32_t nwords = (t1 - t0) * wps + 4u;
+    const uint32_t ps = pad_shift_for(P.logL);
+    stage_luts(P, D, lut_s);
+    stage_stream(P.stream + D.stream_off, first_word, nwords, ps, strm);
+    __syncthreads();
+
+    const Syntax sx = syntax_of(D);
+    auto fetch = [&](uint32_t w) { return strm[padded(w - first_word, ps)]; };
+    const uint32_t t = threadIdx.x;
+    const bool valid = t >= t0 && t < t1;
+    Lane l;
+    BitWin w;
+    if (valid) {
+        const uint32_t i = (uint32_t)(base + (int32_t)t);
+        l.p = i << P.logL; l.u4 = 0u; l.z = 0u; l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
+        win_init(w, l.p, fetch);
+        const uint32_t limit = (i + 1u) << P.logL;
+        decode_span_sync(l, w, limit, sx, fetch, lut_s);
+        sw[t] = pack_state(l.p - limit, l.z, l.u4 >> 2);
+        pnb[t] = l.nb;
+        pdc01[t] = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
+        pdc2[t] = (uint32_t)l.dc2 & 0xFFFFu;
+    }
+    // overflow rounds: in round r lane t decodes subsequence t+r from its own state and compares with the
+    // record the lane before it in the chain (t+1) left there one round earlier
+    bool active = valid && (t + 1u < t1);
+    uint32_t tt = t + 1u;
+    for (;;) {
+        if (!__syncthreads_or(active ? 1 : 0)) break;
+        if (active) {
+            l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
+            const uint32_t limit = ((uint32_t)(base + (int32_t)tt) + 1u) << P.logL;
+            decode_span_sync(l, w, limit, sx, fetch, lut_s);
+            const uint32_t x = pack_state(l.p - limit, l.z, l.u4 >> 2);
+            const bool synced = x == sw[tt];
+            sw[tt] = x;
+            pnb[tt] = l.nb;
+            pdc01[tt] = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
+            pdc2[tt] = (uint32_t)l.dc2 & 0xFFFFu;
+            ++tt;
+            active = !synced && tt < t1;
+        }
+    }
+    if (valid && t >= P.overlap) {
+        SInfo r;
+        r.x = sw[t]; r.y = pnb[t]; r.z = pdc01[t]; r.w = pdc2[t];
+        P.sinfo[D.sub0 + (uint32_t)(base + (int32_t)t)] = r;
+    }
+}
+
+// ---- synchronisation, inter-sequence (paper, Algorithm 3, second loop) ------------------------------
+// One lane per sequence boundary: continue from the last record of sequence b into sequence b+1 until
+// the state equals the recorded one or the sequence ends.  One wave64 per workgroup.
+
+__global__ __launch_bounds__(64) void k_sync_inter(Params P) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.bnd0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t nsub = P.st[ii].nsub;
+    uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
+    stage_luts(P, D, lut_s);
+    __syncthreads();
+    const uint32_t b = (wg - D.bnd0) * 64u + threadIdx.x;
+    const uint64_t gfirst = (uint64_t)(b + 1u) * P.seq_len;
+    if (gfirst >= nsub) return;
+    uint32_t g = (uint32_t)gfirst;
+    const uint32_t gend = min(nsub, g + P.seq_len);
+    const Syntax sx = syntax_of(D);
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off);
+    auto fetch = [&](uint32_t w) { return __builtin_bswap32(words[w]); };
+    SInfo* rec = P.sinfo + D.sub0;
+    const uint32_t x0 = rec[g - 1u].x;
+    Lane l;
+    BitWin w;
+    l.p = (g << P.logL) + state_prel(x0);
+    l.z = state_z(x0);
+    l.u4 = state_u(x0) * 4u;
+    win_init(w, l.p, fetch);
+    bool first = true;
+    for (;;) {
+        l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
+        const uint32_t limit = (g + 1u) << P.logL;
+        decode_span_sync(l, w, limit, sx, fetch, lut_s);
+        SInfo r;
+        r.x = pack_state(l.p - limit, l.z, l.u4 >> 2);
+        r.y = l.nb;
+        r.z = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
+        r.w = (uint32_t)l.dc2 & 0xFFFFu;
+        const bool synced = r.x == rec[g].x;
+        if (first && !synced) atomicAdd(&P.status->inter_changed, 1u);
+        first = false;
+        rec[g] = r;
+        ++g;
+        if (synced || g >= gend) break;
+    }
+}
+
+// ---- exclusive scan over s_info (paper, Algorithm 1: prefix sum on s_info.n) ---------------------------
+// Level 1: totals of each group of kWG records.  Level 2: the workgroup that finishes last for an image
+// scans the image's group totals.  Level 3 (inside the write kernel): scan within the group.
+
+__device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
+
+__global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
+    __shared__ uint32_t scratch[8];
+    __shared__ uint32_t flag;
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t nsub = P.st[ii].nsub;
+    const uint32_t ngrp = (nsub + kWG - 1u) / kWG;
+    const uint32_t lg = wg - D.grp0;
+    if (lg >= ngrp) return;  // groups past the true stream length take no part in the count below
+    const uint32_t i = lg * kWG + threadIdx.x;
+    SInfo r = {0u, 0u, 0u, 0u};
+    if (i < nsub) r = P.sinfo[D.sub0 + i];
+    uint32_t tot[4], dummy;
+    wg_excl_scan(r.y, scratch, &tot[0]);
+    dummy = wg_excl_scan((uint32_t)sx16(r.z), scratch, &tot[1]);
+    dummy = wg_excl_scan((uint32_t)sx16(r.z >> 16), scratch, &tot[2]);
+    dummy = wg_excl_scan((uint32_t)sx16(r.w), scratch, &tot[3]);
+    (void)dummy;
+    if (threadIdx.x == 0) P.grp_tot[wg] = make_int4((int)tot[0], (int)tot[1], (int)tot[2], (int)tot[3]);
+
+    if (!last_workgroup_arrives(&P.st[ii].grps_done, ngrp, &flag)) return;
+    uint32_t carry[4] = {0u, 0u, 0u, 0u};
+    for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
+        uint32_t k = b0 + threadIdx.x;
+        int4 v = k < ngrp ? P.grp_tot[D.grp0 + k] : make_int4(0, 0, 0, 0);
+        uint32_t ct[4];
+        uint32_t e0 = wg_excl_scan((uint32_t)v.x, scratch, &ct[0]);
+        uint32_t e1 = wg_excl_scan((uint32_t)v.y, scratch, &ct[1]);
+        uint32_t e2 = wg_excl_scan((uint32_t)v.z, scratch, &ct[2]);
+        uint32_t e3 = wg_excl_scan((uint32_t)v.w, scratch, &ct[3]);
+        if (k < ngrp)
+            P.grp_pref[D.grp0 + k] = make_int4((int)(carry[0] + e0), (int)(carry[1] + e1), (int)(carry[2] + e2),
+                                               (int)(carry[3] + e3));
+        for (int c = 0; c < 4; ++c) carry[c] += ct[c];
+    }
+    if (threadIdx.x == 0) P.st[ii].grps_done = 0u;
+}
+
+// ---- coefficient buffer clear -------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kWG) void k_zero_coef(Params P) {
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.zero_wg0; });
+    const ImgDesc& D = P.img[ii];
+    const uint64_t bytes = (uint64_t)D.total_units * 128u;
+    const uint64_t begin = (uint64_t)(wg - D.zero_wg0) * kZeroChunk;
+    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(P.coef + D.coef_off) + begin);
+    const uint64_t left = bytes - begin;
+    const uint64_t n16 = (left < (uint64_t)kZeroChunk ? left : (uint64_t)kZeroChunk) / 16u;  // 128 bytes per unit
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    for (uint64_t k = threadIdx.x; k < n16; k += kWG) dst[k] = zero;
+}
+
+// ---- write pass (paper, Algorithm 1 last loop; Algorithm 2 with write = true) ---------------------------
+
+__global__ __launch_bounds__(kWG) void k_write(Params P) {
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
+    __shared__ uint32_t scratch[8];
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t nsub = P.st[ii].nsub;
+    const uint32_t lg = wg - D.grp0;
+    const uint32_t i0 = lg * kWG;
+    if (i0 >= nsub) return;
+    uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
+    uint32_t* strm = reinterpret_cast<uint32_t*>(lut_s + P.lut_slots * (uint32_t)kLutEntries);
+
+    const uint32_t L = 1u << P.logL, wps = L >> 5;
+    const uint32_t nloc = min((uint32_t)kWG, nsub - i0);
+    const uint32_t first_word = i0 * wps;
+    const uint32_t nwords = nloc * wps + 4u;
+    const uint32_t ps = pad_shift_for(P.logL);
+    stage_luts(P, D, lut_s);
+    stage_stream(P.stream + D.stream_off, first_word, nwords, ps, strm);
+
+    const uint32_t t = threadIdx.x;
+    const uint32_t i = i0 + t;
+    const bool valid = t < nloc;
+    const SInfo* rec = P.sinfo + D.sub0;
+    SInfo mine = {0u, 0u, 0u, 0u};
+    uint32_t xprev = 0u;
+    if (valid) {
+        mine = rec[i];
+        if (i > 0u) xprev = rec[i - 1u].x;
+    }
+    // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
+    // plus the group's prefix
+    const int4 gp = P.grp_pref[wg];
+    uint32_t tot;
+    uint32_t unit = (uint32_t)gp.x + wg_excl_scan(mine.y, scratch, &tot);
+    int32_t pred0 = gp.y + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z), scratch, &tot);
+    int32_t pred1 = gp.z + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z >> 16), scratch, &tot);
+    int32_t pred2 = gp.w + (int32_t)wg_excl_scan((uint32_t)sx16(mine.w), scratch, &tot);
+    __syncthreads();  // staged tables and stream are complete
+    if (!valid) return;
+
+    const Syntax sx = syntax_of(D);
+    auto fetch = [&](uint32_t w) { return strm[padded(w - first_word, ps)]; };
+    int16_t* coef = P.coef + D.coef_off;
+    auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)k * 64u + at] = v; };
+    Lane l;
+    BitWin w;
+    l.p = (i << P.logL) + state_prel(xprev);
+    l.z = state_z(xprev);
+    l.u4 = state_u(xprev) * 4u;
+    l.nb = 0u;
+    l.dc0 = (int32_t)(int16_t)pred0; l.dc1 = (int32_t)(int16_t)pred1; l.dc2 = (int32_t)(int16_t)pred2;
+    uint32_t flags = 0u;
+    const uint32_t total = D.total_units;
+    if (unit < total && (unit % D.upm) * 4u != l.u4) flags |= kStUnit;
+    const uint32_t limit = (i + 1u) << P.logL;
+    if (unit < total) {
+        win_init(w, l.p, fetch);
+        decode_span_write(l, w, limit, unit, total, sx, fetch, lut_s, store, flags);
+    }
+    // every lane checks the chain: unless the image is complete it must end in the recorded state
+    if (unit < total) {
+        if (l.p < limit || pack_state(l.p - limit, l.z, l.u4 >> 2) != mine.x) flags |= kStMismatch;
+        if (i == nsub - 1u) flags |= kStShort;
+    }
+    if (flags) atomicOr(&P.status->flags, flags);
+}
+
+// ---- pixels: de-zigzag, dequantise, 8x8 IDCT, level shift, chroma replication, YCbCr -> RGB -------------
+// (paper, Section 4.3; the colour steps are not in the paper).  A workgroup takes a run of consecutive
+// MCUs of one MCU row, kPixBlocks data units at most, transforms them in LDS and writes the pixel
+// rectangle they cover with row-contiguous stores.
+
+constexpr int kBlkStride = 72;  // floats per data unit in LDS: 8 rows of 9 (one pad per row)
+__device__ __constant__ uint8_t c_zigzag[64] = JPGD_ZIGZAG_LITERAL;
+
+__global__ __launch_bounds__(kWG) void k_pixels(Params P) {
+    __shared__ float blk[kPixBlocks * kBlkStride];
+    __shared__ float qf[3 * 64];
+    __shared__ uint8_t zoff[64];
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.pix_wg0; });
+    const ImgDesc& D = P.img[ii];
+    const uint32_t lw = wg - D.pix_wg0;
+    const uint32_t mrow = lw / D.pix_runs, run = lw % D.pix_runs;
+    const uint32_t upm = D.upm;
+    const uint32_t M = (uint32_t)kPixBlocks / upm;
+    const uint32_t m0 = run * M;
+    const uint32_t nm = min(M, D.mcus_x - m0);
+    const uint32_t nblk = nm * upm;
+    const uint32_t t = threadIdx.x;
+    if (t < 64u) zoff[t] = (uint8_t)((c_zigzag[t] >> 3) * 9u + (c_zigzag[t] & 7u));
+    if (t < 3u * 64u) qf[t] = (float)P.qts[D.qt_off + t];
+    __syncthreads();
+
+    // load + dequantise + de-zigzag: 8 coefficients (16 bytes) per lane and step
+    const int16_t* coef = P.coef + D.coef_off + (size_t)((size_t)mrow * D.mcus_x + m0) * upm * 64u;
+    for (uint32_t j = t; j < nblk * 8u; j += kWG) {
+        const uint32_t k = j >> 3, part = j & 7u;
+        const uint32_t comp = (D.sched_comp >> ((k % upm) * 4u)) & 15u;
+        uint4 raw = *reinterpret_cast<const uint4*>(coef + (size_t)j * 8u);
+        const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (uint32_t e = 0; e < 8u; ++e) {
+            const int32_t c = (int32_t)(int16_t)(v[e >> 1] >> (16u * (e & 1u)));
+            const uint32_t zi = part * 8u + e;
+            blk[k * kBlkStride + zoff[zi]] = (float)c * qf[comp * 64u + zi];
+        }
+    }
+    __syncthreads();
+    // columns, then rows
+    for (uint32_t j = t; j < nblk * 8u; j += kWG) {
+        float* b = blk + (j >> 3) * kBlkStride + (j & 7u);
+        float v0 = b[0], v1 = b[9], v2 = b[18], v3 = b[27], v4 = b[36], v5 = b[45], v6 = b[54], v7 = b[63];
+        idct8(v0, v1, v2, v3, v4, v5, v6, v7);
+        b[0] = v0; b[9] = v1; b[18] = v2; b[27] = v3; b[36] = v4; b[45] = v5; b[54] = v6; b[63] = v7;
+    }
+    __syncthreads();
+    for (uint32_t j = t; j < nblk * 8u; j += kWG) {
+        float* b = blk + (j >> 3) * kBlkStride + (j & 7u) * 9u;
+        float v0 = b[0], v1 = b[1], v2 = b[2], v3 = b[3], v4 = b[4], v5 = b[5], v6 = b[6], v7 = b[7];
+        idct8(v0, v1, v2, v3, v4, v5, v6, v7);
+        b[0] = v0 + 128.0f; b[1] = v1 + 128.0f; b[2] = v2 + 128.0f; b[3] = v3 + 128.0f;
+        b[4] = v4 + 128.0f; b[5] = v5 + 128.0f; b[6] = v6 + 128.0f; b[7] = v7 + 128.0f;
+    }
+    __syncthreads();
+
+    // output: groups of 4 horizontally adjacent pixels
+    const uint32_t hs = D.hs, vs = D.vs, ncomp = D.ncomp;
+    const uint32_t mcu_w = 8u * hs, mcu_h = 8u * vs;
+    const uint32_t region_w = nm * mcu_w;
+    const uint32_t groups_per_row = region_w >> 2;
+    uint8_t* pix = P.pixels + D.pix_off;
+    const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
+    const uint32_t x_base = m0 * mcu_w, y_base = mrow * mcu_h;
+    for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
+        const uint32_t py = j / groups_per_row, px0 = (j % groups_per_row) * 4u;
+        const uint32_t gy = y_base + py, gx0 = x_base + px0;
+        if (gy >= D.height || gx0 >= D.width) continue;
+        const uint32_t m = px0 / mcu_w, xin = px0 % mcu_w;  // the 4 pixels share MCU and luma unit
+        const float* yb = blk + (m * upm + (py >> 3) * hs + (xin >> 3)) * kBlkStride + (py & 7u) * 9u + (xin & 7u);
+        uint32_t out[4];
+        if (ncomp == 1u) {
+#pragma unroll
+            for (uint32_t e = 0; e < 4u; ++e) out[e] = to_u8(yb[e]);
+        } else {
+            const float* cbb = blk + (m * upm + hs * vs) * kBlkStride + (py / vs) * 9u;
+            const float* crb = cbb + kBlkStride;
+#pragma unroll
+            for (uint32_t e = 0; e < 4u; ++e) {
+                const uint32_t cx = (xin + e) / hs;
+                out[e] = ycc_to_rgb(yb[e], cbb[cx], crb[cx]);
+            }
+        }
+        uint8_t* dst = pix + ((size_t)gy * D.width + gx0) * ncomp;
+        const bool full = gx0 + 4u <= D.width;
+        if (ncomp == 1u) {
+            if (full && aligned) {
+                *reinterpret_cast<uint32_t*>(dst) = out[0] | (out[1] << 8) | (out[2] << 16) | (out[3] << 24);
+            } else {
+                for (uint32_t e = 0; e < 4u && gx0 + e < D.width; ++e) dst[e] = (uint8_t)out[e];
+            }
+        } else {
+            if (full && aligned) {
+                uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+                d32[0] = out[0] | (out[1] << 24);
+                d32[1] = (out[1] >> 8) | (out[2] << 16);
+                d32[2] = (out[2] >> 16) | (out[3] << 8);
+            } else {
+                for (uint32_t e = 0; e < 4u && gx0 + e < D.width; ++e) {
+                    dst[3u * e + 0u] = (uint8_t)(out[e]);
+                    dst[3u * e + 1u] = (uint8_t)(out[e] >> 8);
+                    dst[3u * e + 2u] = (uint8_t)(out[e] >> 16);
+                }
+            }
+        }
+    }
+}
+
+}  // namespace jpgd

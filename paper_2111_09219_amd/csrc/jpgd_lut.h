@@ -1,0 +1,84 @@
+// Host-side construction of the two-level Huffman lookup tables the kernels keep in LDS.
+// Layout and entry format: jpgd_common.h.
+#pragma once
+#include <string.h>
+
+#include "jpgd_common.h"
+
+namespace jpgd {
+
+// bits[l-1] = number of codes of length l, vals = symbols in code order (as stored in a DHT segment).
+// Codewords are assigned canonically: shortest first, in list order, counting upward, the running
+// code doubled whenever the length grows.  Returns false if the lists cannot be a prefix code.
+inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_t* out) {
+    uint32_t first[17], count[17], valptr[17];
+    uint32_t code = 0, k = 0;
+    for (int len = 1; len <= 16; ++len) {
+        first[len] = code;
+        count[len] = bits[len - 1];
+        valptr[len] = k;
+        code += count[len];
+        k += count[len];
+        if (code > (1u << len)) return false;
+        code <<= 1;
+    }
+    if (k > 256) return false;
+
+    auto entry_for = [&](uint32_t sym, int len) -> uint16_t {
+        if (is_dc) {
+            uint32_t size = sym > 16 ? 16 : sym;
+            return (uint16_t)(len | (size << 5));
+        }
+        uint32_t run = sym >> 4, size = sym & 15;
+        if (size == 0) return run == 15 ? (uint16_t)(len | (15u << 10)) : (uint16_t)(len | kLutEob);
+        return (uint16_t)(len | (size << 5) | (run << 10));
+    };
+
+    const uint16_t kUnset = 0xFFFF;
+    for (int i = 0; i < kLutL1; ++i) out[i] = kUnset;
+    uint8_t maxlen[kLutL1];
+    memset(maxlen, 0, sizeof maxlen);
+    for (int len = 1; len <= 16; ++len)
+        for (uint32_t i = 0; i < count[len]; ++i) {
+            uint32_t c = first[len] + i;
+            if (len <= kLutK) {
+                uint16_t e = entry_for(vals[valptr[len] + i], len);
+                uint32_t lo = c << (kLutK - len), n = 1u << (kLutK - len);
+                for (uint32_t j = 0; j < n; ++j) out[lo + j] = e;
+            } else {
+                uint32_t prefix = c >> (len - kLutK);
+                if (maxlen[prefix] < len) maxlen[prefix] = (uint8_t)len;
+            }
+        }
+    // second level: entry 0 is the shared "no codeword" record, then one subtable per escaping prefix
+    uint16_t* l2 = out + kLutL1;
+    const uint16_t invalid = (uint16_t)(kLutNop | 1u);
+    for (int i = 0; i < kLutL2; ++i) l2[i] = invalid;
+    uint32_t used = 1;
+    uint32_t suboff[kLutL1];
+    for (int p = 0; p < kLutL1; ++p) {
+        if (maxlen[p]) {
+            if (out[p] != kUnset) return false;  // a short code is a prefix of a long one
+            uint32_t nb2 = maxlen[p] - kLutK, n = 1u << nb2;
+            if (used + n > (uint32_t)kLutL2) return false;
+            suboff[p] = used;
+            out[p] = (uint16_t)(kLutEscape | (nb2 << 9) | used);
+            used += n;
+        } else if (out[p] == kUnset) {
+            out[p] = (uint16_t)(kLutEscape | 0u);  // zero further bits, offset 0: the invalid record
+        }
+    }
+    for (int len = kLutK + 1; len <= 16; ++len)
+        for (uint32_t i = 0; i < count[len]; ++i) {
+            uint32_t c = first[len] + i;
+            uint32_t prefix = c >> (len - kLutK);
+            uint32_t ml = maxlen[prefix];
+            uint32_t low = c & ((1u << (len - kLutK)) - 1u);
+            uint32_t lo = low << (ml - len), n = 1u << (ml - len);
+            uint16_t e = entry_for(vals[valptr[len] + i], len);
+            for (uint32_t j = 0; j < n; ++j) l2[suboff[prefix] + lo + j] = e;
+        }
+    return true;
+}
+
+}  // namespace jpgd

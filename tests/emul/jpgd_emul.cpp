@@ -1,0 +1,349 @@
+// Host walk-through of the decoder's kernels: the same lane code (jpgd_lane.h, jpgd_lut.h, jpgd_idct.h)
+// and the same index arithmetic as jpgd_kernels.h, with workgroups and lanes run one after another.
+// It exists so that the CPU-only test run can check the host logic (tables, lane decoder, record
+// packing, padded staging layout, scan, write, pixel arithmetic) before anything reaches a GPU.
+// It is test code: the library never calls it and it is not a fallback for the GPU path.
+//
+// Build: g++ -O2 -std=c++17 -shared -fPIC -o libjpgd_emul.so jpgd_emul.cpp ../../paper_2111_09219_amd/csrc/jpgd_parse.cpp
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "../../include/jpgd.h"
+#include "../../paper_2111_09219_amd/csrc/jpgd_common.h"
+#include "../../paper_2111_09219_amd/csrc/jpgd_idct.h"
+#include "../../paper_2111_09219_amd/csrc/jpgd_lane.h"
+#include "../../paper_2111_09219_amd/csrc/jpgd_lut.h"
+
+using namespace jpgd;
+
+namespace {
+
+uint32_t bswap(uint32_t v) { return __builtin_bswap32(v); }
+uint32_t padded(uint32_t r, uint32_t ps) { return r + (r >> ps); }
+uint32_t pad_shift_for(uint32_t logL) { uint32_t w = logL - 5; return w > 5 ? w : 5; }
+int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
+
+struct Image {
+    jpgd_info in;
+    uint32_t sched_dc = 0, sched_ac = 0, sched_comp = 0, nslots = 0;
+    std::vector<uint16_t> lut;
+    std::vector<uint8_t> stream;  // unstuffed + zero slack
+    uint32_t nbytes = 0, nsub = 0;
+};
+
+int prepare(const uint8_t* file, size_t len, Image& im) {
+    int rc = jpgd_parse(file, len, &im.in);
+    if (rc) return rc;
+    const jpgd_info& in = im.in;
+    uint32_t dc_ids[3], ac_ids[3], ndc = 0, nac = 0, cdc[3], cac[3];
+    for (uint32_t c = 0; c < in.ncomp; ++c) {
+        uint32_t k;
+        for (k = 0; k < ndc && dc_ids[k] != in.td[c]; ++k) {}
+        if (k == ndc) dc_ids[ndc++] = in.td[c];
+        cdc[c] = k;
+        for (k = 0; k < nac && ac_ids[k] != in.ta[c]; ++k) {}
+        if (k == nac) ac_ids[nac++] = in.ta[c];
+        cac[c] = k;
+    }
+    im.nslots = ndc + nac;
+    im.lut.assign((size_t)im.nslots * kLutEntries, 0);
+    uint32_t u = 0;
+    for (uint32_t c = 0; c < in.ncomp; ++c) {
+        uint32_t nu = (in.ncomp == 1) ? 1u : (c == 0 ? (uint32_t)in.hsamp[0] * in.vsamp[0] : 1u);
+        for (uint32_t k = 0; k < nu; ++k, ++u) {
+            im.sched_dc |= cdc[c] << (4 * u);
+            im.sched_ac |= (ndc + cac[c]) << (4 * u);
+            im.sched_comp |= c << (4 * u);
+        }
+        if (!build_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, &im.lut[(size_t)cdc[c] * kLutEntries]) ||
+            !build_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, &im.lut[(size_t)(ndc + cac[c]) * kLutEntries]))
+            return JPGD_E_TABLE;
+    }
+    return JPGD_OK;
+}
+
+// the two unstuff kernels, tile by tile and lane by lane
+void unstuff(const uint8_t* scan, uint32_t n, uint32_t logL, Image& im) {
+    const uint32_t tiles = (n + kUnstuffTile - 1) / kUnstuffTile;
+    std::vector<uint32_t> removed(tiles, 0), before(tiles, 0);
+    auto keep_mask = [&](uint32_t pos, uint32_t& nvalid) {
+        nvalid = pos >= n ? 0u : std::min(16u, n - pos);
+        uint32_t prev = (pos > 0 && nvalid) ? scan[pos - 1] : 0u, mask = 0;
+        for (uint32_t j = 0; j < nvalid; ++j) {
+            uint32_t b = scan[pos + j];
+            if (!(b == 0 && prev == 255)) mask |= 1u << j;
+            prev = b;
+        }
+        return mask;
+    };
+    for (uint32_t t = 0; t < tiles; ++t)
+        for (uint32_t lane = 0; lane < (uint32_t)kWG; ++lane) {
+            uint32_t nv, m = keep_mask(t * kUnstuffTile + lane * 16, nv);
+            removed[t] += nv - (uint32_t)__builtin_popcount(m);
+        }
+    uint32_t carry = 0;
+    for (uint32_t t = 0; t < tiles; ++t) { before[t] = carry; carry += removed[t]; }
+    im.nbytes = n - carry;
+    const uint32_t L = 1u << logL;
+    im.nsub = (uint32_t)(((uint64_t)im.nbytes * 8 + L - 1) >> logL);
+    im.stream.assign((size_t)n + L / 8 + 64 + 16 + 256, 0xAA);  // poison: the kernels must define what they read
+    for (uint32_t t = 0; t < tiles; ++t) {
+        uint32_t o = t * kUnstuffTile - before[t];
+        for (uint32_t lane = 0; lane < (uint32_t)kWG; ++lane) {
+            uint32_t pos = t * kUnstuffTile + lane * 16, nv, m = keep_mask(pos, nv);
+            for (uint32_t j = 0; j < nv; ++j)
+                if (m & (1u << j)) im.stream[o++] = scan[pos + j];
+        }
+    }
+    for (uint32_t k = 0; k < L / 8 + 64; ++k) im.stream[im.nbytes + k] = 0;
+}
+
+struct Emul {
+    Image im;
+    uint32_t logL, H, seq_len;
+    std::vector<SInfo> sinfo;
+    Syntax sx;
+    uint32_t inter_changed = 0, rounds_max = 0, flags = 0;
+};
+
+void sync_intra(Emul& E) {
+    const Image& im = E.im;
+    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5, ps = pad_shift_for(logL);
+    const uint32_t nseq = (nsub + E.seq_len - 1) / E.seq_len;
+    const uint32_t* words = (const uint32_t*)im.stream.data();
+    std::vector<uint32_t> strm;
+    for (uint32_t wg = 0; wg < nseq; ++wg) {
+        const int32_t base = (int32_t)(wg * E.seq_len) - (int32_t)E.H;
+        const uint32_t first = base < 0 ? 0u : (uint32_t)base;
+        const uint32_t t0 = (uint32_t)((int32_t)first - base);
+        const uint32_t t1 = std::min<uint32_t>(kWG, (uint32_t)((int32_t)nsub - base));
+        const uint32_t first_word = first * wps, nwords = (t1 - t0) * wps + 4;
+        strm.assign(padded(nwords, ps) + 4, 0xDEADBEEF);
+        for (uint32_t r = 0; r < nwords; ++r) strm[padded(r, ps)] = bswap(words[first_word + r]);
+        auto fetch = [&](uint32_t w) {
+            uint32_t a = padded(w - first_word, ps);
+            if (w < first_word || w - first_word >= nwords) abort();  // a lane read outside the staged window
+            return strm[a];
+        };
+        uint32_t sw[kWG], pnb[kWG], pdc01[kWG], pdc2[kWG];
+        Lane l[kWG];
+        BitWin bw[kWG];
+        bool active[kWG];
+        uint32_t tt[kWG];
+        for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
+            active[t] = false;
+            if (t < t0 || t >= t1) continue;
+            uint32_t i = (uint32_t)(base + (int32_t)t);
+            l[t].p = i << logL; l[t].u4 = 0; l[t].z = 0; l[t].nb = 0; l[t].dc0 = l[t].dc1 = l[t].dc2 = 0;
+            win_init(bw[t], l[t].p, fetch);
+            uint32_t limit = (i + 1) << logL;
+            decode_span_sync(l[t], bw[t], limit, E.sx, fetch, im.lut.data());
+            sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
+            pnb[t] = l[t].nb;
+            pdc01[t] = ((uint32_t)l[t].dc0 & 0xFFFFu) | ((uint32_t)l[t].dc1 << 16);
+            pdc2[t] = (uint32_t)l[t].dc2 & 0xFFFFu;
+            active[t] = t + 1 < t1;
+            tt[t] = t + 1;
+        }
+        uint32_t rounds = 0;
+        for (;;) {
+            bool any = false;
+            for (uint32_t t = 0; t < (uint32_t)kWG; ++t) any = any || active[t];
+            if (!any) break;
+            ++rounds;
+            for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
+                if (!active[t]) continue;
+                l[t].nb = 0; l[t].dc0 = l[t].dc1 = l[t].dc2 = 0;
+                uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
+                decode_span_sync(l[t], bw[t], limit, E.sx, fetch, im.lut.data());
+                uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
+                bool synced = x == sw[tt[t]];
+                sw[tt[t]] = x; pnb[tt[t]] = l[t].nb;
+                pdc01[tt[t]] = ((uint32_t)l[t].dc0 & 0xFFFFu) | ((uint32_t)l[t].dc1 << 16);
+                pdc2[tt[t]] = (uint32_t)l[t].dc2 & 0xFFFFu;
+                ++tt[t];
+                active[t] = !synced && tt[t] < t1;
+            }
+        }
+        E.rounds_max = std::max(E.rounds_max, rounds);
+        for (uint32_t t = std::max(t0, E.H); t < t1; ++t) {
+            SInfo r = {sw[t], pnb[t], pdc01[t], pdc2[t]};
+            E.sinfo[(uint32_t)(base + (int32_t)t)] = r;
+        }
+    }
+}
+
+void sync_inter(Emul& E) {
+    const Image& im = E.im;
+    const uint32_t nsub = im.nsub, logL = E.logL;
+    const uint32_t* words = (const uint32_t*)im.stream.data();
+    auto fetch = [&](uint32_t w) { return bswap(words[w]); };
+    E.inter_changed = 0;
+    for (uint32_t b = 0;; ++b) {
+        uint64_t gfirst = (uint64_t)(b + 1) * E.seq_len;
+        if (gfirst >= nsub) break;
+        uint32_t g = (uint32_t)gfirst, gend = std::min(nsub, g + E.seq_len);
+        uint32_t x0 = E.sinfo[g - 1].x;
+        Lane l;
+        BitWin w;
+        l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u4 = state_u(x0) * 4;
+        win_init(w, l.p, fetch);
+        bool first = true;
+        for (;;) {
+            l.nb = 0; l.dc0 = l.dc1 = l.dc2 = 0;
+            uint32_t limit = (g + 1) << logL;
+            decode_span_sync(l, w, limit, E.sx, fetch, im.lut.data());
+            SInfo r = {pack_state(l.p - limit, l.z, l.u4 >> 2), l.nb,
+                       ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16), (uint32_t)l.dc2 & 0xFFFFu};
+            bool synced = r.x == E.sinfo[g].x;
+            if (first && !synced) E.inter_changed++;
+            first = false;
+            E.sinfo[g] = r;
+            ++g;
+            if (synced || g >= gend) break;
+        }
+    }
+}
+
+void scan_and_write(Emul& E, int16_t* coef) {
+    const Image& im = E.im;
+    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5, ps = pad_shift_for(logL);
+    const uint32_t total = im.in.total_units;
+    memset(coef, 0, (size_t)total * 128);
+    const uint32_t* words = (const uint32_t*)im.stream.data();
+    uint32_t unit0 = 0;
+    int32_t pred[3] = {0, 0, 0};
+    std::vector<uint32_t> strm;
+    E.flags = 0;
+    for (uint32_t i0 = 0; i0 < nsub; i0 += kWG) {
+        const uint32_t nloc = std::min<uint32_t>(kWG, nsub - i0);
+        const uint32_t first_word = i0 * wps, nwords = nloc * wps + 4;
+        strm.assign(padded(nwords, ps) + 4, 0xDEADBEEF);
+        for (uint32_t r = 0; r < nwords; ++r) strm[padded(r, ps)] = bswap(words[first_word + r]);
+        auto fetch = [&](uint32_t w) {
+            if (w < first_word || w - first_word >= nwords) abort();
+            return strm[padded(w - first_word, ps)];
+        };
+        auto store = [&](uint32_t k, uint32_t at, int16_t v) {
+            if (k >= total || at > 63) abort();
+            coef[(size_t)k * 64 + at] = v;
+        };
+        for (uint32_t t = 0; t < nloc; ++t) {
+            const uint32_t i = i0 + t;
+            const SInfo mine = E.sinfo[i];
+            const uint32_t xprev = i ? E.sinfo[i - 1].x : 0u;
+            Lane l;
+            BitWin w;
+            l.p = (i << logL) + state_prel(xprev); l.z = state_z(xprev); l.u4 = state_u(xprev) * 4; l.nb = 0;
+            l.dc0 = (int16_t)pred[0]; l.dc1 = (int16_t)pred[1]; l.dc2 = (int16_t)pred[2];
+            uint32_t unit = unit0, flags = 0;
+            if (unit < total && (unit % im.in.units_per_mcu) * 4 != l.u4) flags |= kStUnit;
+            const uint32_t limit = (i + 1) << logL;
+            if (unit < total) {
+                win_init(w, l.p, fetch);
+                decode_span_write(l, w, limit, unit, total, E.sx, fetch, im.lut.data(), store, flags);
+            }
+            if (unit < total) {
+                if (l.p < limit || pack_state(l.p - limit, l.z, l.u4 >> 2) != mine.x) flags |= kStMismatch;
+                if (i == nsub - 1) flags |= kStShort;
+            }
+            E.flags |= flags;
+            // exclusive scan, lane by lane
+            unit0 += mine.y;
+            pred[0] += sx16(mine.z); pred[1] += sx16(mine.z >> 16); pred[2] += sx16(mine.w);
+        }
+    }
+}
+
+void pixels(const Emul& E, const int16_t* coef_all, uint8_t* pix) {
+    const jpgd_info& in = E.im.in;
+    const uint8_t zz[64] = JPGD_ZIGZAG_LITERAL;
+    const uint32_t upm = in.units_per_mcu, hs = in.hsamp[0], vs = in.vsamp[0], ncomp = in.ncomp;
+    const uint32_t M = kPixBlocks / upm, runs = (in.mcus_x + M - 1) / M;
+    const uint32_t mcu_w = 8 * hs, mcu_h = 8 * vs;
+    std::vector<float> blk(kPixBlocks * 72);
+    for (uint32_t mrow = 0; mrow < in.mcus_y; ++mrow)
+        for (uint32_t run = 0; run < runs; ++run) {
+            const uint32_t m0 = run * M, nm = std::min(M, in.mcus_x - m0), nblk = nm * upm;
+            const int16_t* coef = coef_all + ((size_t)mrow * in.mcus_x + m0) * upm * 64;
+            for (uint32_t k = 0; k < nblk; ++k) {
+                uint32_t comp = (E.im.sched_comp >> ((k % upm) * 4)) & 15u;
+                for (uint32_t zi = 0; zi < 64; ++zi)
+                    blk[k * 72 + (zz[zi] >> 3) * 9 + (zz[zi] & 7)] = (float)coef[k * 64 + zi] * (float)in.qt[in.tq[comp]][zi];
+            }
+            for (uint32_t j = 0; j < nblk * 8; ++j) {
+                float* b = &blk[(j >> 3) * 72 + (j & 7)];
+                idct8(b[0], b[9], b[18], b[27], b[36], b[45], b[54], b[63]);
+            }
+            for (uint32_t j = 0; j < nblk * 8; ++j) {
+                float* b = &blk[(j >> 3) * 72 + (j & 7) * 9];
+                idct8(b[0], b[1], b[2], b[3], b[4], b[5], b[6], b[7]);
+                for (int e = 0; e < 8; ++e) b[e] += 128.0f;
+            }
+            for (uint32_t py = 0; py < mcu_h; ++py)
+                for (uint32_t px = 0; px < nm * mcu_w; ++px) {
+                    uint32_t gy = mrow * mcu_h + py, gx = m0 * mcu_w + px;
+                    if (gy >= in.height || gx >= in.width) continue;
+                    uint32_t m = px / mcu_w, xin = px % mcu_w;
+                    float y = blk[(m * upm + (py >> 3) * hs + (xin >> 3)) * 72 + (py & 7) * 9 + (xin & 7)];
+                    uint8_t* dst = pix + ((size_t)gy * in.width + gx) * ncomp;
+                    if (ncomp == 1) { dst[0] = (uint8_t)to_u8(y); continue; }
+                    const float* cbb = &blk[(m * upm + hs * vs) * 72 + (py / vs) * 9];
+                    uint32_t rgb = ycc_to_rgb(y, cbb[xin / hs], cbb[72 + xin / hs]);
+                    dst[0] = (uint8_t)rgb; dst[1] = (uint8_t)(rgb >> 8); dst[2] = (uint8_t)(rgb >> 16);
+                }
+        }
+}
+
+}  // namespace
+
+// Runs the whole pipeline on the host.  stats: [0] inter-sequence rounds used, [1] boundaries whose first
+// comparison failed in the last round, [2] longest intra-sequence overflow (rounds), [3] final flags,
+// [4] number of subsequences, [5] unstuffed bytes.  sinfo_out (may be NULL): 4 words per subsequence.
+extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t H, uint32_t max_rounds, int16_t* coef,
+                           uint8_t* pix, uint32_t* sinfo_out, uint32_t sinfo_cap, uint8_t* stream_out,
+                           uint32_t* stats) {
+    Emul E;
+    int rc = prepare(file, len, E.im);
+    if (rc) return rc;
+    E.logL = 0;
+    while ((1u << E.logL) < L) ++E.logL;
+    E.H = H;
+    E.seq_len = kWG - H;
+    E.sx.sched_dc = E.im.sched_dc; E.sx.sched_ac = E.im.sched_ac; E.sx.sched_comp = E.im.sched_comp;
+    E.sx.upm4 = E.im.in.units_per_mcu * 4;
+    unstuff(file + E.im.in.scan_offset, (uint32_t)E.im.in.scan_bytes, E.logL, E.im);
+    E.sinfo.assign(E.im.nsub, SInfo{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu});
+    sync_intra(E);
+    uint32_t rounds = 0;
+    const uint32_t nseq = (E.im.nsub + E.seq_len - 1) / E.seq_len;
+    for (;;) {
+        if (nseq > 1) { sync_inter(E); ++rounds; }
+        scan_and_write(E, coef);
+        bool broken = (E.flags & (kStMismatch | kStUnit)) != 0;
+        if (!broken || nseq <= 1 || rounds >= max_rounds) break;
+    }
+    if (stats) {
+        stats[0] = rounds; stats[1] = E.inter_changed; stats[2] = E.rounds_max; stats[3] = E.flags;
+        stats[4] = E.im.nsub; stats[5] = E.im.nbytes;
+    }
+    if (sinfo_out && sinfo_cap >= E.im.nsub) memcpy(sinfo_out, E.sinfo.data(), (size_t)E.im.nsub * 16);
+    if (stream_out) memcpy(stream_out, E.im.stream.data(), E.im.nbytes);
+    if (E.flags) return JPGD_E_CORRUPT;
+    if (pix) pixels(E, coef, pix);
+    return JPGD_OK;
+}
+
+// the literal zig-zag table of jpgd_idct.h, for comparison with a generated one
+extern "C" void emul_zigzag(uint8_t out[64]) {
+    const uint8_t zz[64] = JPGD_ZIGZAG_LITERAL;
+    memcpy(out, zz, 64);
+}
+
+// one table built by jpgd_lut.h
+extern "C" int emul_build_lut(const uint8_t* bits, const uint8_t* vals, int is_dc, uint16_t* out) {
+    return build_lut(bits, vals, is_dc != 0, out) ? 0 : JPGD_E_TABLE;
+}

@@ -1,0 +1,184 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, on a real MI355X.
+
+Coefficients must be bit-exact (integer work).  Pixels must be within 1 level of the oracle's
+double-precision path: the kernels compute the IDCT and colour conversion in fp32 with the same order
+of operations (no intermediate rounding), so the two can differ only where the exact value lies within
+fp32 error (about 1e-3 for 8-bit data) of a rounding boundary -- one level at most.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import paper_2111_09219_amd as J
+from oracle import OracleImage, unstuff_bytes
+from workloads import CONFIGS, config_jpeg, encode_jpeg, small_image
+
+pytestmark = pytest.mark.gpu
+
+PIXEL_TOL = 1
+
+
+def _decode(files, **cfg):
+    batch = J.prepare_batch(files, J.Config.make(**cfg))
+    rep = batch.decode()
+    return batch, rep
+
+
+def _check_image(batch, i, data, pixel_rects=None):
+    o = OracleImage(data)
+    ref = o.coefficients()
+    got = batch.coefficients(i).cpu().numpy()
+    assert got.shape == ref.shape
+    bad = np.flatnonzero((got != ref).any(axis=1))
+    assert bad.size == 0, "first differing data unit %d of %d" % (bad[0], ref.shape[0])
+    pix = batch.pixels(i).cpu().numpy()
+    if pixel_rects is None:
+        want = o.pixels(ref)
+        assert pix.shape == want.shape
+        assert np.abs(pix.astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL
+    else:
+        mw, mh = o.info.hmax * 8, o.info.vmax * 8
+        for (mx0, mx1, my0, my1) in pixel_rects:
+            want = o.pixels(ref, mcu_rect=(mx0, mx1, my0, my1))
+            ys, xs = slice(my0 * mh, min(my1 * mh, o.height)), slice(mx0 * mw, min(mx1 * mw, o.width))
+            d = np.abs(pix[ys, xs].astype(np.int16) - want[ys, xs].astype(np.int16))
+            assert d.max() <= PIXEL_TOL
+    return o
+
+
+def test_config1_gray_256():
+    data = config_jpeg(1).data
+    for L in (128, 1024):
+        batch, rep = _decode([data], subseq_bits=L)
+        assert rep.redo == 0
+        _check_image(batch, 0, data)
+
+
+def test_config2_hd_444():
+    data = config_jpeg(2).data
+    batch, rep = _decode([data])
+    assert rep.redo == 0 and rep.n_sequences > 16
+    _check_image(batch, 0, data)
+
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+@pytest.mark.parametrize("opt", [False, True])
+def test_small_shapes_all_layouts(sub, opt):
+    """Sizes that are not multiples of the MCU, streams that span several workgroups and a ragged tail,
+    every subsequence size, disjoint and overlapping sequences."""
+    for seed, (h, w), q in [(1, (37, 51), 85), (2, (200, 333), 94), (3, (8, 8), 40), (4, (129, 70), 75)]:
+        px = small_image(seed, h, w, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+        data = encode_jpeg(px, q, sub, opt).data
+        for L, H in [(128, 0), (128, 64), (256, 0), (512, 16), (1024, 0), (2048, 0)]:
+            batch, rep = _decode([data], subseq_bits=L, overlap=H)
+            assert rep.subseq_bits == L
+            _check_image(batch, 0, data)
+
+
+def test_sync_records_are_the_sequential_decoder_states():
+    """After synchronisation s_info holds, for every subsequence, the sequential decoder's state at the
+    first symbol past its end, the data units completed in it and the DC-difference sums (oracle:
+    boundary_states)."""
+    px = small_image(31, 480, 640, sigma=12.0)
+    data = encode_jpeg(px, 93, "420", False).data
+    for L in (128, 1024):
+        batch, rep = _decode([data], subseq_bits=L)
+        rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
+        o = OracleImage(data)
+        bs = o.boundary_states(L)
+        n = len(bs["p"])
+        assert len(rec["p"]) == n
+        live = np.cumsum(bs["units"]) < o.total_units
+        assert np.array_equal(rec["p"][live].astype(np.int64), bs["p"][live])
+        assert np.array_equal(rec["u"][live], bs["u"][live]) and np.array_equal(rec["z"][live], bs["z"][live])
+        assert np.array_equal(rec["units"][live], bs["units"][live])
+        assert np.array_equal(rec["dcsum"][live].astype(np.int16), bs["dcsum"][live].astype(np.int16))
+
+
+def test_unstuff_kernel_alone():
+    import torch
+    rng = np.random.default_rng(9)
+    for n in (1, 15, 16, 17, 4095, 4096, 4097, 100003):
+        raw = rng.choice(np.array([0, 255, 255, 17, 200], np.uint8), size=n)
+        stuffed = bytearray()
+        for v in raw.tolist():
+            stuffed.append(v)
+            if v == 255:
+                stuffed.append(0)
+        stuffed = np.frombuffer(bytes(stuffed), np.uint8)
+        want = unstuff_bytes(stuffed)
+        assert np.array_equal(want, raw)
+        d_in = torch.from_numpy(stuffed.copy()).cuda()
+        d_out = torch.full((stuffed.size + 512,), 0xAA, dtype=torch.uint8, device="cuda")
+        ws = torch.empty(4096 + 4 * (stuffed.size // 4096 + 2), dtype=torch.uint8, device="cuda")
+        k = J.jpgd_unstuff(d_in, d_out, ws)
+        assert k == want.size
+        got = d_out.cpu().numpy()
+        assert np.array_equal(got[:k], want)
+        assert not got[k:k + 192].any()                 # cleared slack that lanes may read
+        assert (got[k + 192:] == 0xAA).all()            # nothing written beyond it
+
+
+def test_batch_of_different_images():
+    """Images with different sizes, layouts, qualities and Huffman tables in one call (Algorithm 1, batched)."""
+    files = [encode_jpeg(small_image(1, 96, 128), 80, "420").data,
+             encode_jpeg(small_image(2, 40, 40, ncomp=1), 95).data,
+             encode_jpeg(small_image(3, 64, 200), 90, "444", True).data,
+             encode_jpeg(small_image(4, 130, 90), 70, "422").data,
+             encode_jpeg(small_image(5, 256, 256, sigma=20), 97, "420", True).data]
+    for L in (256, 1024):
+        batch, rep = _decode(files, subseq_bits=L)
+        for i, f in enumerate(files):
+            _check_image(batch, i, f)
+
+
+def test_config4_batch_slice():
+    files = [e.data for e in config_jpeg(4, limit=24)]
+    batch, rep = _decode(files)
+    for i, f in enumerate(files):
+        _check_image(batch, i, f)
+
+
+def test_corrupt_streams_are_reported_not_written_out_of_bounds():
+    import torch
+    enc = encode_jpeg(small_image(5, 128, 128), 85, "420")
+    data = enc.data
+    # truncated entropy segment
+    short = np.concatenate([data[:enc.scan_offset + enc.scan_len // 2], np.array([0xFF, 0xD9], np.uint8)])
+    with pytest.raises(J.JpgdError) as e:
+        _decode([short])
+    assert e.value.name == "CORRUPT"
+    # flipped bits in the middle of the stream: either still decodable garbage or CORRUPT, never a fault,
+    # and guard bytes around the outputs stay intact
+    rng = np.random.default_rng(3)
+    for trial in range(4):
+        bad = data.copy()
+        pos = enc.scan_offset + int(rng.integers(8, enc.scan_len - 8))
+        if bad[pos] in (0xFF, 0x00) or bad[pos - 1] == 0xFF:
+            continue
+        bad[pos] ^= 1 << int(rng.integers(0, 8))
+        if bad[pos] == 0xFF:
+            continue
+        batch = J.prepare_batch([bad])
+        try:
+            batch.decode()
+        except J.JpgdError as err:
+            assert err.name == "CORRUPT"
+    torch.cuda.synchronize()
+
+
+@pytest.mark.slow
+def test_config3_4096_optimized_tables():
+    data = config_jpeg(3).data
+    batch, rep = _decode([data])
+    _check_image(batch, 0, data, pixel_rects=[(0, 16, 0, 8), (120, 136, 100, 104), (240, 256, 250, 256)])
+
+
+@pytest.mark.slow
+def test_config5_flat_and_random_halves():
+    """Full size: 15360x8640.  All coefficients are compared (the oracle's entropy decode takes seconds);
+    pixels on sampled MCU rectangles from both halves, the seam and the last rows."""
+    data = config_jpeg(5).data
+    batch, rep = _decode([data])
+    _check_image(batch, 0, data, pixel_rects=[(0, 24, 0, 4), (470, 490, 270, 273), (940, 960, 536, 540)])

@@ -1,0 +1,280 @@
+"""CPU-only checks of the product's host side: the C ABI loads and exports what include/jpgd.h declares,
+jpgd_parse agrees with the oracle's independent parser and rejects what it must, the lookup tables decode
+every codeword, and a host walk-through of the kernels' lane code reproduces the oracle.  No GPU call."""
+import ctypes
+import io
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+from PIL import Image
+
+import jpegfile as jf
+import paper_2111_09219_amd as J
+from oracle import OracleError, OracleImage, zigzag
+from workloads import config_jpeg, encode_jpeg, small_image
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EMUL_DIR = os.path.join(ROOT, "tests", "emul")
+
+
+# ------------------------------------------------------------------------------------------ ABI
+
+def test_library_loads_and_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "jpgd.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(jpgd_[a-z_]+)\s*\(", header))
+    assert declared == set(J.EXPORTS)
+    lib = ctypes.CDLL(J.library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.jpgd_abi_version() == 1
+    lib.jpgd_strerror.restype = ctypes.c_char_p
+    assert b"corrupt" not in lib.jpgd_strerror(0) and lib.jpgd_strerror(-6)
+    # the product must not link the oracle or the input encoder
+    deps = subprocess.run(["ldd", J.library_path()], stdout=subprocess.PIPE, text=True).stdout
+    assert "orc_jpeg" not in deps and "wl_jpeg" not in deps
+
+
+def test_struct_layout_matches_the_header():
+    """sizeof(jpgd_info) as the C compiler sees it equals the ctypes mirror."""
+    src = '#include "jpgd.h"\n#include <stdio.h>\nint main(){printf("%zu %zu %zu", sizeof(jpgd_info), sizeof(jpgd_config), sizeof(jpgd_report));}'
+    exe = os.path.join(EMUL_DIR, "sizeof_probe")
+    subprocess.run(["gcc", "-x", "c", "-I", os.path.join(ROOT, "include"), "-o", exe, "-"], input=src.encode(), check=True)
+    a, b, c = map(int, subprocess.check_output([exe]).split())
+    os.remove(exe)
+    assert (a, b, c) == (ctypes.sizeof(J.Info), ctypes.sizeof(J.Config), ctypes.sizeof(J.Report))
+
+
+# ---------------------------------------------------------------------------------------- parse
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_parse_agrees_with_oracle_parser(sub):
+    px = small_image(4, 45, 77, ncomp=1 if sub == "gray" else 3)
+    for opt in (False, True):
+        data = encode_jpeg(px, quality=80, subsampling=sub, optimize=opt).data
+        info, o = J.jpgd_parse(data), OracleImage(data).info
+        assert (info.width, info.height, info.ncomp) == (o.width, o.height, o.ncomp)
+        assert (info.mcus_x, info.mcus_y, info.units_per_mcu, info.total_units) == (
+            o.mcus_x, o.mcus_y, o.units_per_mcu, o.total_units)
+        assert (info.scan_offset, info.scan_bytes) == (o.scan_offset, o.scan_len)
+        for c in range(info.ncomp):
+            assert (info.hsamp[c], info.vsamp[c], info.tq[c], info.td[c], info.ta[c]) == (
+                o.hs[c], o.vs[c], o.tq[c], o.td[c], o.ta[c])
+            assert list(info.qt[info.tq[c]]) == list(o.qt[o.tq[c]])
+
+
+def test_parse_pillow_file_and_trailing_bytes():
+    buf = io.BytesIO()
+    Image.fromarray(small_image(2, 40, 56)).save(buf, "JPEG", quality=85, subsampling=2, optimize=True)
+    data = np.frombuffer(buf.getvalue(), np.uint8)
+    info = J.jpgd_parse(data)
+    o = OracleImage(data).info
+    assert (info.scan_offset, info.scan_bytes, info.units_per_mcu) == (o.scan_offset, o.scan_len, 6)
+    padded = np.concatenate([data, np.zeros(5, np.uint8)])          # junk after EOI
+    assert J.jpgd_parse(padded).scan_bytes == info.scan_bytes
+
+
+def _expect(data, name):
+    with pytest.raises(J.JpgdError) as e:
+        J.jpgd_parse(np.asarray(data, np.uint8))
+    assert e.value.name == name
+
+
+def test_parse_rejections():
+    good = encode_jpeg(small_image(3, 24, 24), quality=80, subsampling="420").data
+    _expect(good[:3], "TRUNCATED")
+    _expect(good[:200], "TRUNCATED")                 # cut inside a table segment
+    _expect(good[:-2], "TRUNCATED")                  # no EOI
+    bad = good.copy(); bad[1] = 0xD9
+    _expect(bad, "MARKER")
+    prog = io.BytesIO()
+    Image.fromarray(small_image(3, 24, 24)).save(prog, "JPEG", progressive=True)
+    _expect(np.frombuffer(prog.getvalue(), np.uint8), "UNSUPPORTED")
+    rst = encode_jpeg(small_image(3, 24, 24), quality=80, subsampling="420", restart_interval=2).data
+    _expect(rst, "UNSUPPORTED")
+    q = [1] * 64
+    std_dc = ([0, 1, 5, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0], list(range(12)))
+    ac = ([0, 2] + [0] * 14, [0, 1])
+    ok = jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q}, [(0, 0, *std_dc), (1, 0, *ac)], b"\x00")
+    assert J.jpgd_parse(ok).total_units == 1
+    # 12-bit precision
+    twelve = ok.copy(); i = bytes(ok).index(b"\xFF\xC0"); twelve[i + 4] = 12
+    _expect(twelve, "UNSUPPORTED")
+    # a DHT whose lengths cannot form a prefix code: three codes of length 1
+    _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q}, [(0, 0, [3] + [0] * 15, [0, 1, 2]), (1, 0, *ac)],
+                        b"\x00"), "TABLE")
+    # scan refers to an AC table that was never defined
+    _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 1)], {0: q}, [(0, 0, *std_dc), (1, 0, *ac)], b"\x00"), "TABLE")
+    # 4 components, and chroma sampled 2x2
+    _expect(jf.assemble(8, 8, [(i, 1, 1, 0) for i in range(1, 5)], [(i, 0, 0) for i in range(1, 5)], {0: q},
+                        [(0, 0, *std_dc), (1, 0, *ac)], b"\x00"), "UNSUPPORTED")
+    _expect(jf.assemble(16, 16, [(1, 1, 1, 0), (2, 2, 2, 0), (3, 1, 1, 0)], [(1, 0, 0), (2, 0, 0), (3, 0, 0)], {0: q},
+                        [(0, 0, *std_dc), (1, 0, *ac)], b"\x00"), "UNSUPPORTED")
+
+
+def test_workspace_bytes_and_config_validation():
+    info = J.jpgd_parse(config_jpeg(1).data)
+    base = J.jpgd_workspace_bytes([info])
+    assert base > info.scan_bytes and base % 256 == 0
+    assert J.jpgd_workspace_bytes([info, info]) > base
+    for bad in (J.Config.make(subseq_bits=100), J.Config.make(subseq_bits=4096), J.Config.make(overlap=200)):
+        with pytest.raises(J.JpgdError):
+            J.jpgd_workspace_bytes([info], bad)
+    assert J.jpgd_workspace_bytes([info], J.Config.make(subseq_bits=128, overlap=32)) > 0
+
+
+def test_product_refuses_to_run_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(RuntimeError):
+        J.prepare_batch([config_jpeg(1).data])
+
+
+# ------------------------------------------------------------------------- host walk-through
+
+@pytest.fixture(scope="module")
+def emul():
+    lib_path = os.path.join(EMUL_DIR, "libjpgd_emul.so")
+    src = os.path.join(EMUL_DIR, "jpgd_emul.cpp")
+    csrc = os.path.join(ROOT, "paper_2111_09219_amd", "csrc")
+    deps = [src] + [os.path.join(csrc, f) for f in os.listdir(csrc)]
+    if not os.path.exists(lib_path) or any(os.path.getmtime(d) > os.path.getmtime(lib_path) for d in deps):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-o", lib_path, src,
+                               os.path.join(csrc, "jpgd_parse.cpp")])
+    lib = ctypes.CDLL(lib_path)
+    vp, u32 = ctypes.c_void_p, ctypes.c_uint32
+    lib.emul_decode.argtypes = [vp, ctypes.c_size_t, u32, u32, u32, vp, vp, vp, u32, vp, vp]
+    lib.emul_zigzag.argtypes = [vp]
+    lib.emul_build_lut.argtypes = [vp, vp, ctypes.c_int, vp]
+    return lib
+
+
+def _emul_run(lib, data, L, H, max_rounds=64):
+    o = OracleImage(data)
+    coef = np.zeros((o.total_units, 64), np.int16)
+    pix = np.zeros((o.height, o.width, o.ncomp), np.uint8)
+    stats = np.zeros(8, np.uint32)
+    cap = int(o.info.scan_len * 8 // L + 2)
+    sinfo = np.zeros((cap, 4), np.uint32)
+    stream = np.zeros(int(o.info.scan_len) + 8, np.uint8)
+    rc = lib.emul_decode(data.ctypes.data, data.size, L, H, max_rounds, coef.ctypes.data, pix.ctypes.data,
+                         sinfo.ctypes.data, cap, stream.ctypes.data, stats.ctypes.data)
+    return rc, coef, pix, sinfo[:stats[4]], stream[:stats[5]], stats, o
+
+
+def test_zigzag_literal_is_the_diagonal_walk(emul):
+    lit = np.zeros(64, np.uint8)
+    emul.emul_zigzag(lit.ctypes.data)
+    walk, r, c = [], 0, 0
+    for _ in range(64):                       # generated here, independently of both tables
+        walk.append(r * 8 + c)
+        if (r + c) % 2 == 0:
+            if c == 7: r += 1
+            elif r == 0: c += 1
+            else: r, c = r - 1, c + 1
+        else:
+            if r == 7: c += 1
+            elif c == 0: r += 1
+            else: r, c = r + 1, c - 1
+    assert lit.tolist() == walk == zigzag().tolist()
+
+
+@pytest.mark.parametrize("optimize", [False, True])
+def test_lookup_tables_decode_every_codeword(emul, optimize):
+    """For each codeword of each table (as the oracle derives them) followed by any continuation bits, the
+    two-level table yields that symbol's length, run and size; bit patterns that start no codeword yield the
+    skip-one-bit record."""
+    px2 = np.full((256, 256, 3), 128, np.uint8)
+    px2[::37, ::41] = (255, 0, 90)
+    files = [encode_jpeg(small_image(8, 160, 160, sigma=30), 97, "420", optimize).data]
+    if optimize:
+        files.append(encode_jpeg(px2, 100, "444", True).data)       # skewed counts: long codes
+    K, L1 = 10, 1024
+    for data in files:
+        img = OracleImage(data)
+        for cls in (0, 1):
+            for tid in (0, 1):
+                bits, vals = img.huffman(cls, tid)
+                code, length = img.codes(cls, tid)
+                vbuf = np.zeros(256, np.uint8); vbuf[:len(vals)] = vals
+                lut = np.zeros(1536, np.uint16)
+                assert emul.emul_build_lut(bits.ctypes.data, vbuf.ctypes.data, int(cls == 0), lut.ctypes.data) == 0
+
+                def look(peek16):
+                    e = int(lut[peek16 >> (16 - K)])
+                    if e & 0x8000:
+                        nb2, off = (e >> 9) & 7, e & 511
+                        j = (peek16 >> (16 - K - nb2)) & ((1 << nb2) - 1)
+                        e = int(lut[L1 + off + j])
+                        if e & 0x8000:
+                            return None
+                    return e & 31, (e >> 5) & 31, (e >> 10) & 15, bool(e & 0x4000)
+                covered = np.zeros(1 << 16, bool)
+                for s in vals:
+                    ln = int(length[s])
+                    lo = int(code[s]) << (16 - ln)
+                    covered[lo:lo + (1 << (16 - ln))] = True
+                    want_size = min(int(s), 16) if cls == 0 else int(s) & 15
+                    want_run = 0 if cls == 0 else int(s) >> 4
+                    eob = cls == 1 and (int(s) & 15) == 0 and (int(s) >> 4) != 15
+                    for tail in {0, (1 << (16 - ln)) - 1, 0x5555 & ((1 << (16 - ln)) - 1)}:
+                        got = look(lo | tail)
+                        assert got is not None and got[0] == ln and got[3] == eob
+                        if not eob:
+                            assert got[1] == want_size and got[2] == want_run
+                for peek in np.flatnonzero(~covered)[::97]:
+                    assert look(int(peek)) is None
+
+
+CASES = [("gray", False, 75, (64, 64)), ("444", False, 90, (40, 104)), ("420", True, 95, (96, 80)),
+         ("422", False, 85, (37, 51)), ("420", False, 92, (137, 251)), ("gray", True, 50, (9, 300))]
+
+
+@pytest.mark.parametrize("sub,opt,q,shape", CASES)
+@pytest.mark.parametrize("L,H", [(128, 0), (128, 48), (256, 0), (1024, 0)])
+def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H):
+    px = small_image(17, *shape, ncomp=1 if sub == "gray" else 3, sigma=11.0)
+    data = encode_jpeg(px, q, sub, opt).data
+    rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
+    assert rc == 0 and stats[3] == 0
+    assert np.array_equal(stream, o.unstuffed())
+    ref = o.coefficients()
+    assert np.array_equal(coef, ref)
+    refpix = o.pixels(ref).reshape(pix.shape).astype(int)
+    assert np.abs(pix.astype(int) - refpix).max() <= 1
+    # converged records are the sequential decoder's boundary states
+    bs = o.boundary_states(L)
+    n = len(bs["p"])
+    assert n == len(sinfo)
+    done = np.cumsum(bs["units"]) >= o.total_units          # boundaries after the last symbol carry no state
+    x = sinfo[:, 0]
+    keep = ~done
+    assert np.array_equal(((np.arange(n) + 1) * L + (x & 63))[keep], bs["p"][keep])
+    assert np.array_equal(((x >> 6) & 63)[keep], bs["z"][keep]) and np.array_equal((x >> 12)[keep], bs["u"][keep])
+    assert np.array_equal(sinfo[keep, 1], bs["units"][keep])
+    dc0 = (sinfo[:, 2] & 0xFFFF).astype(np.uint16).view(np.int16)
+    assert np.array_equal(dc0[keep], bs["dcsum"][keep, 0].astype(np.int16))
+
+
+def test_host_walkthrough_dense_ff_and_tiny_streams(emul):
+    rng = np.random.default_rng(1)
+    px = (rng.integers(0, 2, size=(64, 64)) * 255).astype(np.uint8)
+    data = encode_jpeg(px, 100).data                             # many 0xFF bytes
+    rc, coef, pix, _, stream, stats, o = _emul_run(emul, data, 128, 0)
+    assert rc == 0 and np.array_equal(stream, o.unstuffed()) and np.array_equal(coef, o.coefficients())
+    tiny = encode_jpeg(np.full((8, 8), 128, np.uint8), 75).data  # one block, a one-byte stream
+    rc, coef, pix, _, stream, stats, o = _emul_run(emul, tiny, 1024, 0)
+    assert rc == 0 and stats[4] == 1 and (pix == 128).all()
+
+
+def test_host_walkthrough_flags_corrupt_streams(emul):
+    enc = encode_jpeg(small_image(5, 64, 64), 85, "420")
+    short = np.concatenate([enc.data[:enc.scan_offset + enc.scan_len // 2], np.array([0xFF, 0xD9], np.uint8)])
+    rc, *_ = _emul_run(emul, short, 256, 0)
+    assert rc == -6
+    with pytest.raises(OracleError):
+        OracleImage(short).coefficients()
