@@ -208,9 +208,14 @@ int stage_acquire(size_t bytes, int* slot) {
     return JPGD_OK;
 }
 
-#define HIP_OK(expr)                                    \
-    do {                                                \
-        if ((expr) != hipSuccess) return JPGD_E_HIP;    \
+int hip_failed(const char* what, hipError_t e) {
+    fprintf(stderr, "jpgd: %s failed: %s\n", what, hipGetErrorString(e));
+    return JPGD_E_HIP;
+}
+#define HIP_OK(expr)                                                \
+    do {                                                            \
+        hipError_t e_ = (expr);                                     \
+        if (e_ != hipSuccess) return hip_failed(#expr, e_);         \
     } while (0)
 
 size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
@@ -224,14 +229,13 @@ size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
     return (size_t)lut_slots * kLutEntries * 2 + ((size_t)nwords + (nwords >> ps) + 4) * 4;
 }
 
-std::once_flag g_attr_once;
-int g_attr_rc = JPGD_OK;
-void set_kernel_attributes() {
-    const int max_lds = 160 * 1024;
-    if (hipFuncSetAttribute((const void*)k_sync_intra, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess ||
-        hipFuncSetAttribute((const void*)k_write, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess ||
-        hipFuncSetAttribute((const void*)k_sync_inter, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
-        g_attr_rc = JPGD_E_HIP;
+// dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
+size_t g_lds_granted[3] = {0, 0, 0};
+int grant_lds(int which, const void* kernel, size_t bytes) {
+    if (bytes <= g_lds_granted[which]) return JPGD_OK;
+    HIP_OK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    g_lds_granted[which] = bytes;
+    return JPGD_OK;
 }
 
 }  // namespace
@@ -263,13 +267,14 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         pl.img[i].pix_off = want_pixels ? pixel_offsets[i] : 0;
     }
     hipStream_t stream = (hipStream_t)stream_v;
-    std::call_once(g_attr_once, set_kernel_attributes);
-    if (g_attr_rc) return g_attr_rc;
     const size_t lds_sync = lds_sync_bytes(pl.L, pl.lut_slots), lds_write = lds_write_bytes(pl.L, pl.lut_slots);
     const size_t lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
-    if (lds_sync > 160 * 1024) return JPGD_E_ARG;
+    if (lds_sync > 150 * 1024) return JPGD_E_ARG;
 
     std::lock_guard<std::mutex> lock(g_stage.mu);
+    if ((rc = grant_lds(0, (const void*)k_sync_intra, lds_sync)) || (rc = grant_lds(1, (const void*)k_write, lds_write)) ||
+        (rc = grant_lds(2, (const void*)k_sync_inter, lds_inter)))
+        return rc;
     int slot;
     rc = stage_acquire(pl.h.upload_bytes, &slot);
     if (rc) return rc;
