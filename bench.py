@@ -29,10 +29,12 @@ def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: i
     bytes, S subsequences (16-byte records), K data units (128 bytes of int16 each), out_bytes of pixels."""
     return {
         "unstuff_count": Bs,
+        "unstuff_scan": 8 * (Bs // 4096 + 1),
         "unstuff_scatter": Bs + B,
         "sync_intra": B + 16 * S,
         "sync_inter": 16 * (S // 256 + 1),
-        "scan": 16 * S,
+        "scan_totals": 16 * S,
+        "scan_prefix": 32 * (S // 256 + 1),
         "zero": 128 * K,
         "write": B + 16 * S + 128 * K,
         "pixels": 128 * K + out_bytes,
@@ -76,7 +78,7 @@ def main() -> int:
 
     # warm-up; the first steps also time every kernel once to find the dominant one
     cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            timing_mask=0xFF)
+                            timing_mask=0x3FF)
     split = np.zeros(len(J.KERNELS))
     nsplit = max(1, min(5, args.warmup))
     rep = None

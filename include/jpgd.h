@@ -89,11 +89,13 @@ typedef struct {
 
 /* kernels of the pipeline, in launch order */
 enum {
-    JPGD_K_UNSTUFF_COUNT = 0, /* unstuff: bytes to drop per tile, last tile scans the counts       */
+    JPGD_K_UNSTUFF_COUNT = 0, /* unstuff: bytes to drop per tile                                   */
+    JPGD_K_UNSTUFF_SCAN,      /* unstuff: exclusive scan of the tile counts, unstuffed length      */
     JPGD_K_UNSTUFF_SCATTER,   /* unstuff: compaction                                               */
     JPGD_K_SYNC_INTRA,        /* Algorithm 3, first loop                                           */
     JPGD_K_SYNC_INTER,        /* Algorithm 3, second loop                                          */
-    JPGD_K_SCAN,              /* exclusive scan over s_info (group totals and their prefix)        */
+    JPGD_K_SCAN_TOTALS,       /* exclusive scan over s_info: totals per group of 256 records       */
+    JPGD_K_SCAN_PREFIX,       /* exclusive scan over s_info: prefix of the group totals            */
     JPGD_K_ZERO,              /* clears the coefficient buffer                                     */
     JPGD_K_WRITE,             /* Algorithm 1, write pass                                           */
     JPGD_K_PIXELS,            /* Section 4.3 plus colour                                           */

@@ -57,14 +57,15 @@ class Config(ctypes.Structure):
         return Config(subseq_bits, 0xFFFFFFFF if overlap is None else overlap, max_rounds, flags, timing_mask)
 
 
-KERNELS = ["unstuff_count", "unstuff_scatter", "sync_intra", "sync_inter", "scan", "zero", "write", "pixels"]
+KERNELS = ["unstuff_count", "unstuff_scan", "unstuff_scatter", "sync_intra", "sync_inter", "scan_totals",
+           "scan_prefix", "zero", "write", "pixels"]
 
 
 class Report(ctypes.Structure):
     """jpgd_report"""
     _fields_ = [("subseq_bits", ctypes.c_uint32), ("n_subseq", ctypes.c_uint32), ("n_sequences", ctypes.c_uint32),
                 ("inter_rounds", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("device_flags", ctypes.c_uint32),
-                ("launches", ctypes.c_uint32 * 8), ("kernel_ms", ctypes.c_float * 8)]
+                ("launches", ctypes.c_uint32 * 10), ("kernel_ms", ctypes.c_float * 10)]
 
     def as_dict(self):
         d = {k: int(getattr(self, k)) for k, _ in self._fields_[:6]}

@@ -219,14 +219,12 @@ int hip_failed(const char* what, hipError_t e) {
     } while (0)
 
 size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
-    uint32_t wps = L / 32, nwords = kWG * wps + 4;
-    uint32_t ps = ilog2(wps) > 5 ? ilog2(wps) : 5;
-    return (size_t)lut_slots * kLutEntries * 2 + 4 * kWG * 4 + ((size_t)nwords + (nwords >> ps) + 4) * 4;
+    uint32_t nwords = kWG * (L / 32) + 4;
+    return (size_t)lut_slots * kLutEntries * 2 + 4 * kWG * 4 + (size_t)nwords * 4;
 }
 size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
-    uint32_t wps = L / 32, nwords = kWG * wps + 4;
-    uint32_t ps = ilog2(wps) > 5 ? ilog2(wps) : 5;
-    return (size_t)lut_slots * kLutEntries * 2 + ((size_t)nwords + (nwords >> ps) + 4) * 4;
+    uint32_t nwords = kWG * (L / 32) + 4;
+    return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4;
 }
 
 // dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
@@ -354,6 +352,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     } while (0)
 
     LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles, kWG, 0);
+    LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
     LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra, pl.seqs, kWG, lds_sync);
 
@@ -364,7 +363,8 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
             LAUNCH(JPGD_K_SYNC_INTER, k_sync_inter, pl.bnds, 64, lds_inter);
             ++rounds;
         }
-        LAUNCH(JPGD_K_SCAN, k_group_totals, pl.grps, kWG, 0);
+        LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, pl.grps, kWG, 0);
+        LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
         LAUNCH(JPGD_K_ZERO, k_zero_coef, pl.zerowgs, kWG, 0);
         LAUNCH(JPGD_K_WRITE, k_write, pl.grps, kWG, lds_write);
         HIP_OK(hipGetLastError());
@@ -479,6 +479,7 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     P.nimg = 1;
     P.logL = 10;
     hipLaunchKernelGGL(k_unstuff_count, dim3(tiles), dim3(kWG), 0, stream, P);
+    hipLaunchKernelGGL(k_unstuff_scan, dim3(1), dim3(kWG), 0, stream, P);
     hipLaunchKernelGGL(k_unstuff_scatter, dim3(tiles), dim3(kWG), 0, stream, P);
     HIP_OK(hipGetLastError());
     HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + off_state, sizeof(ImgState), hipMemcpyDeviceToHost, stream));

@@ -19,25 +19,26 @@ constexpr int kMaxOverlap = 191;  // warm-up lanes a sequence may borrow from it
 // ---- Huffman lookup tables ---------------------------------------------------------------------
 // One table = kLutL1 first-level entries indexed by the next kLutK bits, followed by up to kLutL2
 // second-level entries for codewords longer than kLutK bits.  uint16 entries:
-//   bit 15      first level : escape, (bits 0..8 = offset into the second level, bits 9..11 = number of
-//                             further bits that index it)
-//               second level: no codeword starts with these bits (consume one bit, state unchanged)
-//   bit 14      end-of-block class (AC symbol with zero size and run != 15)
-//   bits 10..13 run of zeros before the coefficient
-//   bits 5..9   number of value bits
-//   bits 0..4   codeword length
+//   bits 0..4   codeword length, 1..16; 0 marks a first-level escape (see below)
+//   bits 5..9   number of value bits that follow the codeword, 0..16
+//   bits 10..15 zig-zag slots the symbol covers: run+1 for a coefficient, 1 for a DC symbol, 16 for
+//               ZRL, 63 for end-of-block (any z >= 1 plus 63 reaches 64 = unit complete), and 0 for
+//               "no codeword starts with these bits" (length 1: skip one bit, state unchanged)
+//   escape (first level only): bits 5..7 = number of further bits that index the second level,
+//               bits 8..15 = half the offset of the subtable inside the second level
 // Bound on the second level: codes of one length are consecutive, so those of length l > kLutK touch
 // at most n_l / 2^(l-kLutK) + 2 first-level prefixes; summed over l = 11..16 with at most 256 symbols
-// this is below 512 entries.
+// this is below 510 entries; two more hold the shared "no codeword" record.
 constexpr int kLutK = 10;
 constexpr int kLutL1 = 1 << kLutK;
 constexpr int kLutL2 = 512;
 constexpr int kLutEntries = kLutL1 + kLutL2;
 constexpr int kMaxSlots = 6;  // up to 3 DC and 3 AC tables per image (one pair per component)
+constexpr uint32_t kAdvEob = 63u;
 
-constexpr uint16_t kLutEscape = 0x8000;
-constexpr uint16_t kLutNop = 0x8000;
-constexpr uint16_t kLutEob = 0x4000;
+JPGD_HD uint32_t lut_len(uint32_t e) { return e & 31u; }
+JPGD_HD uint32_t lut_size(uint32_t e) { return (e >> 5) & 31u; }
+JPGD_HD uint32_t lut_adv(uint32_t e) { return e >> 10; }
 
 // ---- s_info (paper, Section 4.1): one 16-byte record per subsequence --------------------------
 //  x : decoder state after the last symbol that starts inside the subsequence
@@ -102,8 +103,7 @@ struct ImgDesc {
 struct ImgState {
     uint32_t nbytes;   // unstuffed length B
     uint32_t nsub;     // ceil(8B / L)
-    uint32_t tiles_done;  // arrival counters of the last-workgroup-done reductions
-    uint32_t grps_done;
+    uint32_t pad_[2];
 };
 
 // status word bits (device -> host)

@@ -68,21 +68,6 @@ __device__ __forceinline__ uint32_t wg_excl_scan(uint32_t v, uint32_t* scratch, 
     return before + inc - v;
 }
 
-// "last workgroup done": returns true in exactly one workgroup per counter, the one that arrives last,
-// after which all data the others wrote before calling is visible to it.  No workgroup waits.
-__device__ __forceinline__ bool last_workgroup_arrives(uint32_t* counter, uint32_t expected, uint32_t* flag_lds) {
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        *flag_lds = (old == expected - 1u) ? 1u : 0u;
-    }
-    __syncthreads();
-    bool last = *flag_lds != 0u;
-    if (last) __threadfence();
-    return last;
-}
-
 __device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, uint16_t* lut_s) {
     const uint32_t n16 = D.nslots * (uint32_t)kLutEntries;       // uint16 count, multiple of 8
     const uint4* src = reinterpret_cast<const uint4*>(P.luts + D.lut_off);
@@ -99,27 +84,30 @@ __device__ __forceinline__ Syntax syntax_of(const ImgDesc& D) {
     return sx;
 }
 
-// LDS copy of a stretch of the stream as big-endian 32-bit words, one pad word after every 2^pad_shift
-// words so that lanes whose subsequences are a power of two apart hit different banks.
-__device__ __forceinline__ uint32_t padded(uint32_t r, uint32_t pad_shift) { return r + (r >> pad_shift); }
-
+// LDS copy of a stretch of the stream as big-endian 32-bit words.  No padding: lanes start a power of two
+// apart and collide on a bank for their first reads only; after that they advance at their own pace.
 __device__ __forceinline__ void stage_stream(const uint8_t* stream_img, uint32_t first_word, uint32_t nwords,
-                                             uint32_t pad_shift, uint32_t* strm) {
+                                             uint32_t* strm) {
     // nwords is a multiple of 4 and first_word*4 a multiple of 16
     const uint4* src = reinterpret_cast<const uint4*>(stream_img + (size_t)first_word * 4u);
+    uint4* dst = reinterpret_cast<uint4*>(strm);
     for (uint32_t k = threadIdx.x; k < nwords / 4u; k += blockDim.x) {
         uint4 v = src[k];
-        uint32_t r = k * 4u;
-        strm[padded(r + 0u, pad_shift)] = __builtin_bswap32(v.x);
-        strm[padded(r + 1u, pad_shift)] = __builtin_bswap32(v.y);
-        strm[padded(r + 2u, pad_shift)] = __builtin_bswap32(v.z);
-        strm[padded(r + 3u, pad_shift)] = __builtin_bswap32(v.w);
+        v.x = __builtin_bswap32(v.x); v.y = __builtin_bswap32(v.y);
+        v.z = __builtin_bswap32(v.z); v.w = __builtin_bswap32(v.w);
+        dst[k] = v;
     }
 }
 
-__device__ __forceinline__ uint32_t pad_shift_for(uint32_t logL) {
-    uint32_t words_log = logL - 5u;  // log2(words per subsequence)
-    return words_log > 5u ? words_log : 5u;
+__device__ __forceinline__ uint32_t pack_dc01(int64_t acc) {
+    int32_t d0, d1, d2;
+    dc_unpack(acc, d0, d1, d2);
+    return ((uint32_t)d0 & 0xFFFFu) | ((uint32_t)d1 << 16);
+}
+__device__ __forceinline__ uint32_t pack_dc2(int64_t acc) {
+    int32_t d0, d1, d2;
+    dc_unpack(acc, d0, d1, d2);
+    return (uint32_t)d2 & 0xFFFFu;
 }
 
 // ---- unstuffing (byte compaction) -----------------------------------------------------------------
@@ -157,7 +145,6 @@ __device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_
 
 __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     __shared__ uint32_t scratch[8];
-    __shared__ uint32_t flag;
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
     const ImgDesc& D = P.img[ii];
@@ -169,9 +156,14 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     uint32_t total;
     wg_excl_scan(removed, scratch, &total);
     if (threadIdx.x == 0) P.tile_cnt[wg] = total;
+}
 
-    if (!last_workgroup_arrives(&P.st[ii].tiles_done, D.ntiles, &flag)) return;
-    // this workgroup arrived last for image ii: turn the per-tile counts into exclusive prefixes
+// one workgroup per image: per-tile counts -> bytes removed before each tile; unstuffed length and
+// number of subsequences of the image
+__global__ __launch_bounds__(kWG) void k_unstuff_scan(Params P) {
+    __shared__ uint32_t scratch[8];
+    const uint32_t ii = blockIdx.x;
+    const ImgDesc& D = P.img[ii];
     uint32_t carry = 0u;
     for (uint32_t base = 0; base < D.ntiles; base += kWG) {
         uint32_t k = base + threadIdx.x;
@@ -186,7 +178,6 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
         P.st[ii].nbytes = nbytes;
         uint32_t L = 1u << P.logL;
         P.st[ii].nsub = (uint32_t)(((uint64_t)nbytes * 8u + L - 1u) >> P.logL);
-        P.st[ii].tiles_done = 0u;
     }
 }
 
@@ -260,27 +251,27 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     const uint32_t t1 = min((uint32_t)kWG, (uint32_t)((int32_t)nsub - base));  // one past the last such lane
     const uint32_t first_word = first * wps;
     const uint32_t nwords = (t1 - t0) * wps + 4u;
-    const uint32_t ps = pad_shift_for(P.logL);
     stage_luts(P, D, lut_s);
-    stage_stream(P.stream + D.stream_off, first_word, nwords, ps, strm);
+    stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
     __syncthreads();
 
     const Syntax sx = syntax_of(D);
-    auto fetch = [&](uint32_t w) { return strm[padded(w - first_word, ps)]; };
+    auto fetch = [&](uint32_t c) { return strm[c]; };  // cursor = word index inside the staged window
     const uint32_t t = threadIdx.x;
     const bool valid = t >= t0 && t < t1;
     Lane l;
     BitWin w;
+    int64_t dcacc = 0;
     if (valid) {
         const uint32_t i = (uint32_t)(base + (int32_t)t);
-        l.p = i << P.logL; l.u4 = 0u; l.z = 0u; l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
-        win_init(w, l.p, fetch);
+        l.p = i << P.logL; l.u4 = 0u; l.z = 0u; l.nb = 0u;
+        win_init(w, l.p, (l.p >> 5) - first_word, fetch);
         const uint32_t limit = (i + 1u) << P.logL;
-        decode_span_sync(l, w, limit, sx, fetch, lut_s);
+        decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         sw[t] = pack_state(l.p - limit, l.z, l.u4 >> 2);
         pnb[t] = l.nb;
-        pdc01[t] = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
-        pdc2[t] = (uint32_t)l.dc2 & 0xFFFFu;
+        pdc01[t] = pack_dc01(dcacc);
+        pdc2[t] = pack_dc2(dcacc);
     }
     // overflow rounds: in round r lane t decodes subsequence t+r from its own state and compares with the
     // record the lane before it in the chain (t+1) left there one round earlier
@@ -289,15 +280,16 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     for (;;) {
         if (!__syncthreads_or(active ? 1 : 0)) break;
         if (active) {
-            l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
+            l.nb = 0u;
+            dcacc = 0;
             const uint32_t limit = ((uint32_t)(base + (int32_t)tt) + 1u) << P.logL;
-            decode_span_sync(l, w, limit, sx, fetch, lut_s);
+            decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
             const uint32_t x = pack_state(l.p - limit, l.z, l.u4 >> 2);
             const bool synced = x == sw[tt];
             sw[tt] = x;
             pnb[tt] = l.nb;
-            pdc01[tt] = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
-            pdc2[tt] = (uint32_t)l.dc2 & 0xFFFFu;
+            pdc01[tt] = pack_dc01(dcacc);
+            pdc2[tt] = pack_dc2(dcacc);
             ++tt;
             active = !synced && tt < t1;
         }
@@ -337,17 +329,18 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     l.p = (g << P.logL) + state_prel(x0);
     l.z = state_z(x0);
     l.u4 = state_u(x0) * 4u;
-    win_init(w, l.p, fetch);
+    win_init(w, l.p, l.p >> 5, fetch);  // cursor = word index in the image's stream
     bool first = true;
     for (;;) {
-        l.nb = 0u; l.dc0 = l.dc1 = l.dc2 = 0;
+        l.nb = 0u;
+        int64_t dcacc = 0;
         const uint32_t limit = (g + 1u) << P.logL;
-        decode_span_sync(l, w, limit, sx, fetch, lut_s);
+        decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         SInfo r;
         r.x = pack_state(l.p - limit, l.z, l.u4 >> 2);
         r.y = l.nb;
-        r.z = ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16);
-        r.w = (uint32_t)l.dc2 & 0xFFFFu;
+        r.z = pack_dc01(dcacc);
+        r.w = pack_dc2(dcacc);
         const bool synced = r.x == rec[g].x;
         if (first && !synced) atomicAdd(&P.status->inter_changed, 1u);
         first = false;
@@ -358,33 +351,34 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
 }
 
 // ---- exclusive scan over s_info (paper, Algorithm 1: prefix sum on s_info.n) ---------------------------
-// Level 1: totals of each group of kWG records.  Level 2: the workgroup that finishes last for an image
-// scans the image's group totals.  Level 3 (inside the write kernel): scan within the group.
+// Level 1: totals of each group of kWG records.  Level 2: one workgroup per image scans the image's
+// group totals.  Level 3 (inside the write kernel): scan within the group.
 
 __device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
 
 __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
     __shared__ uint32_t scratch[8];
-    __shared__ uint32_t flag;
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
     const ImgDesc& D = P.img[ii];
     const uint32_t nsub = P.st[ii].nsub;
-    const uint32_t ngrp = (nsub + kWG - 1u) / kWG;
-    const uint32_t lg = wg - D.grp0;
-    if (lg >= ngrp) return;  // groups past the true stream length take no part in the count below
-    const uint32_t i = lg * kWG + threadIdx.x;
+    const uint32_t i = (wg - D.grp0) * kWG + threadIdx.x;
     SInfo r = {0u, 0u, 0u, 0u};
     if (i < nsub) r = P.sinfo[D.sub0 + i];
-    uint32_t tot[4], dummy;
+    uint32_t tot[4];
     wg_excl_scan(r.y, scratch, &tot[0]);
-    dummy = wg_excl_scan((uint32_t)sx16(r.z), scratch, &tot[1]);
-    dummy = wg_excl_scan((uint32_t)sx16(r.z >> 16), scratch, &tot[2]);
-    dummy = wg_excl_scan((uint32_t)sx16(r.w), scratch, &tot[3]);
-    (void)dummy;
+    wg_excl_scan((uint32_t)sx16(r.z), scratch, &tot[1]);
+    wg_excl_scan((uint32_t)sx16(r.z >> 16), scratch, &tot[2]);
+    wg_excl_scan((uint32_t)sx16(r.w), scratch, &tot[3]);
     if (threadIdx.x == 0) P.grp_tot[wg] = make_int4((int)tot[0], (int)tot[1], (int)tot[2], (int)tot[3]);
+}
 
-    if (!last_workgroup_arrives(&P.st[ii].grps_done, ngrp, &flag)) return;
+// one workgroup per image: exclusive prefix of the group totals
+__global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
+    __shared__ uint32_t scratch[8];
+    const uint32_t ii = blockIdx.x;
+    const ImgDesc& D = P.img[ii];
+    const uint32_t ngrp = (P.st[ii].nsub + kWG - 1u) / kWG;
     uint32_t carry[4] = {0u, 0u, 0u, 0u};
     for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
         uint32_t k = b0 + threadIdx.x;
@@ -399,7 +393,6 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
                                                (int)(carry[3] + e3));
         for (int c = 0; c < 4; ++c) carry[c] += ct[c];
     }
-    if (threadIdx.x == 0) P.st[ii].grps_done = 0u;
 }
 
 // ---- coefficient buffer clear -------------------------------------------------------------------------
@@ -436,9 +429,8 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t nloc = min((uint32_t)kWG, nsub - i0);
     const uint32_t first_word = i0 * wps;
     const uint32_t nwords = nloc * wps + 4u;
-    const uint32_t ps = pad_shift_for(P.logL);
     stage_luts(P, D, lut_s);
-    stage_stream(P.stream + D.stream_off, first_word, nwords, ps, strm);
+    stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
 
     const uint32_t t = threadIdx.x;
     const uint32_t i = i0 + t;
@@ -462,7 +454,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     if (!valid) return;
 
     const Syntax sx = syntax_of(D);
-    auto fetch = [&](uint32_t w) { return strm[padded(w - first_word, ps)]; };
+    auto fetch = [&](uint32_t c) { return strm[c]; };
     int16_t* coef = P.coef + D.coef_off;
     auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)k * 64u + at] = v; };
     Lane l;
@@ -471,14 +463,14 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     l.z = state_z(xprev);
     l.u4 = state_u(xprev) * 4u;
     l.nb = 0u;
-    l.dc0 = (int32_t)(int16_t)pred0; l.dc1 = (int32_t)(int16_t)pred1; l.dc2 = (int32_t)(int16_t)pred2;
+    pred0 = (int32_t)(int16_t)pred0; pred1 = (int32_t)(int16_t)pred1; pred2 = (int32_t)(int16_t)pred2;
     uint32_t flags = 0u;
     const uint32_t total = D.total_units;
     if (unit < total && (unit % D.upm) * 4u != l.u4) flags |= kStUnit;
     const uint32_t limit = (i + 1u) << P.logL;
     if (unit < total) {
-        win_init(w, l.p, fetch);
-        decode_span_write(l, w, limit, unit, total, sx, fetch, lut_s, store, flags);
+        win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+        decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
     // every lane checks the chain: unless the image is complete it must end in the recorded state
     if (unit < total) {

@@ -25,13 +25,16 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
     if (k > 256) return false;
 
     auto entry_for = [&](uint32_t sym, int len) -> uint16_t {
+        uint32_t size, adv;
         if (is_dc) {
-            uint32_t size = sym > 16 ? 16 : sym;
-            return (uint16_t)(len | (size << 5));
+            size = sym > 16 ? 16 : sym;
+            adv = 1;
+        } else {
+            uint32_t run = sym >> 4;
+            size = sym & 15;
+            adv = size ? run + 1 : (run == 15 ? 16u : kAdvEob);
         }
-        uint32_t run = sym >> 4, size = sym & 15;
-        if (size == 0) return run == 15 ? (uint16_t)(len | (15u << 10)) : (uint16_t)(len | kLutEob);
-        return (uint16_t)(len | (size << 5) | (run << 10));
+        return (uint16_t)((uint32_t)len | (size << 5) | (adv << 10));
     };
 
     const uint16_t kUnset = 0xFFFF;
@@ -50,11 +53,12 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
                 if (maxlen[prefix] < len) maxlen[prefix] = (uint8_t)len;
             }
         }
-    // second level: entry 0 is the shared "no codeword" record, then one subtable per escaping prefix
+    // second level: entries 0 and 1 are the shared "no codeword" record (length 1, nothing else), then one
+    // subtable per escaping prefix; subtables hold 2, 4, .. 64 entries, so every offset is even
     uint16_t* l2 = out + kLutL1;
-    const uint16_t invalid = (uint16_t)(kLutNop | 1u);
+    const uint16_t invalid = 1u;
     for (int i = 0; i < kLutL2; ++i) l2[i] = invalid;
-    uint32_t used = 1;
+    uint32_t used = 2;
     uint32_t suboff[kLutL1];
     for (int p = 0; p < kLutL1; ++p) {
         if (maxlen[p]) {
@@ -62,10 +66,10 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
             uint32_t nb2 = maxlen[p] - kLutK, n = 1u << nb2;
             if (used + n > (uint32_t)kLutL2) return false;
             suboff[p] = used;
-            out[p] = (uint16_t)(kLutEscape | (nb2 << 9) | used);
+            out[p] = (uint16_t)((nb2 << 5) | ((used >> 1) << 8));
             used += n;
         } else if (out[p] == kUnset) {
-            out[p] = (uint16_t)(kLutEscape | 0u);  // zero further bits, offset 0: the invalid record
+            out[p] = 0u;  // escape with zero further bits and offset 0: the invalid record
         }
     }
     for (int len = kLutK + 1; len <= 16; ++len)

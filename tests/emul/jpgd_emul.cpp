@@ -22,9 +22,9 @@ using namespace jpgd;
 namespace {
 
 uint32_t bswap(uint32_t v) { return __builtin_bswap32(v); }
-uint32_t padded(uint32_t r, uint32_t ps) { return r + (r >> ps); }
-uint32_t pad_shift_for(uint32_t logL) { uint32_t w = logL - 5; return w > 5 ? w : 5; }
 int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
+uint32_t pack_dc01(int64_t acc) { int32_t a, b, c; dc_unpack(acc, a, b, c); return ((uint32_t)a & 0xFFFFu) | ((uint32_t)b << 16); }
+uint32_t pack_dc2(int64_t acc) { int32_t a, b, c; dc_unpack(acc, a, b, c); return (uint32_t)c & 0xFFFFu; }
 
 struct Image {
     jpgd_info in;
@@ -111,7 +111,7 @@ struct Emul {
 
 void sync_intra(Emul& E) {
     const Image& im = E.im;
-    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5, ps = pad_shift_for(logL);
+    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5;
     const uint32_t nseq = (nsub + E.seq_len - 1) / E.seq_len;
     const uint32_t* words = (const uint32_t*)im.stream.data();
     std::vector<uint32_t> strm;
@@ -121,30 +121,31 @@ void sync_intra(Emul& E) {
         const uint32_t t0 = (uint32_t)((int32_t)first - base);
         const uint32_t t1 = std::min<uint32_t>(kWG, (uint32_t)((int32_t)nsub - base));
         const uint32_t first_word = first * wps, nwords = (t1 - t0) * wps + 4;
-        strm.assign(padded(nwords, ps) + 4, 0xDEADBEEF);
-        for (uint32_t r = 0; r < nwords; ++r) strm[padded(r, ps)] = bswap(words[first_word + r]);
-        auto fetch = [&](uint32_t w) {
-            uint32_t a = padded(w - first_word, ps);
-            if (w < first_word || w - first_word >= nwords) abort();  // a lane read outside the staged window
-            return strm[a];
+        strm.assign(nwords, 0xDEADBEEF);
+        for (uint32_t r = 0; r < nwords; ++r) strm[r] = bswap(words[first_word + r]);
+        auto fetch = [&](uint32_t c) {
+            if (c >= nwords) abort();  // a lane read outside the staged window
+            return strm[c];
         };
         uint32_t sw[kWG], pnb[kWG], pdc01[kWG], pdc2[kWG];
         Lane l[kWG];
         BitWin bw[kWG];
+        int64_t dcacc[kWG];
         bool active[kWG];
         uint32_t tt[kWG];
         for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
             active[t] = false;
             if (t < t0 || t >= t1) continue;
             uint32_t i = (uint32_t)(base + (int32_t)t);
-            l[t].p = i << logL; l[t].u4 = 0; l[t].z = 0; l[t].nb = 0; l[t].dc0 = l[t].dc1 = l[t].dc2 = 0;
-            win_init(bw[t], l[t].p, fetch);
+            l[t].p = i << logL; l[t].u4 = 0; l[t].z = 0; l[t].nb = 0;
+            dcacc[t] = 0;
+            win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);
             uint32_t limit = (i + 1) << logL;
-            decode_span_sync(l[t], bw[t], limit, E.sx, fetch, im.lut.data());
+            decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
             sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
             pnb[t] = l[t].nb;
-            pdc01[t] = ((uint32_t)l[t].dc0 & 0xFFFFu) | ((uint32_t)l[t].dc1 << 16);
-            pdc2[t] = (uint32_t)l[t].dc2 & 0xFFFFu;
+            pdc01[t] = pack_dc01(dcacc[t]);
+            pdc2[t] = pack_dc2(dcacc[t]);
             active[t] = t + 1 < t1;
             tt[t] = t + 1;
         }
@@ -156,14 +157,15 @@ void sync_intra(Emul& E) {
             ++rounds;
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
                 if (!active[t]) continue;
-                l[t].nb = 0; l[t].dc0 = l[t].dc1 = l[t].dc2 = 0;
+                l[t].nb = 0;
+                dcacc[t] = 0;
                 uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
-                decode_span_sync(l[t], bw[t], limit, E.sx, fetch, im.lut.data());
+                decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
                 uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
                 bool synced = x == sw[tt[t]];
                 sw[tt[t]] = x; pnb[tt[t]] = l[t].nb;
-                pdc01[tt[t]] = ((uint32_t)l[t].dc0 & 0xFFFFu) | ((uint32_t)l[t].dc1 << 16);
-                pdc2[tt[t]] = (uint32_t)l[t].dc2 & 0xFFFFu;
+                pdc01[tt[t]] = pack_dc01(dcacc[t]);
+                pdc2[tt[t]] = pack_dc2(dcacc[t]);
                 ++tt[t];
                 active[t] = !synced && tt[t] < t1;
             }
@@ -190,14 +192,14 @@ void sync_inter(Emul& E) {
         Lane l;
         BitWin w;
         l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u4 = state_u(x0) * 4;
-        win_init(w, l.p, fetch);
+        win_init(w, l.p, l.p >> 5, fetch);
         bool first = true;
         for (;;) {
-            l.nb = 0; l.dc0 = l.dc1 = l.dc2 = 0;
+            l.nb = 0;
+            int64_t dcacc = 0;
             uint32_t limit = (g + 1) << logL;
-            decode_span_sync(l, w, limit, E.sx, fetch, im.lut.data());
-            SInfo r = {pack_state(l.p - limit, l.z, l.u4 >> 2), l.nb,
-                       ((uint32_t)l.dc0 & 0xFFFFu) | ((uint32_t)l.dc1 << 16), (uint32_t)l.dc2 & 0xFFFFu};
+            decode_span_sync(l, w, limit, dcacc, E.sx, fetch, im.lut.data());
+            SInfo r = {pack_state(l.p - limit, l.z, l.u4 >> 2), l.nb, pack_dc01(dcacc), pack_dc2(dcacc)};
             bool synced = r.x == E.sinfo[g].x;
             if (first && !synced) E.inter_changed++;
             first = false;
@@ -210,7 +212,7 @@ void sync_inter(Emul& E) {
 
 void scan_and_write(Emul& E, int16_t* coef) {
     const Image& im = E.im;
-    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5, ps = pad_shift_for(logL);
+    const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5;
     const uint32_t total = im.in.total_units;
     memset(coef, 0, (size_t)total * 128);
     const uint32_t* words = (const uint32_t*)im.stream.data();
@@ -221,11 +223,11 @@ void scan_and_write(Emul& E, int16_t* coef) {
     for (uint32_t i0 = 0; i0 < nsub; i0 += kWG) {
         const uint32_t nloc = std::min<uint32_t>(kWG, nsub - i0);
         const uint32_t first_word = i0 * wps, nwords = nloc * wps + 4;
-        strm.assign(padded(nwords, ps) + 4, 0xDEADBEEF);
-        for (uint32_t r = 0; r < nwords; ++r) strm[padded(r, ps)] = bswap(words[first_word + r]);
-        auto fetch = [&](uint32_t w) {
-            if (w < first_word || w - first_word >= nwords) abort();
-            return strm[padded(w - first_word, ps)];
+        strm.assign(nwords, 0xDEADBEEF);
+        for (uint32_t r = 0; r < nwords; ++r) strm[r] = bswap(words[first_word + r]);
+        auto fetch = [&](uint32_t c) {
+            if (c >= nwords) abort();
+            return strm[c];
         };
         auto store = [&](uint32_t k, uint32_t at, int16_t v) {
             if (k >= total || at > 63) abort();
@@ -238,13 +240,13 @@ void scan_and_write(Emul& E, int16_t* coef) {
             Lane l;
             BitWin w;
             l.p = (i << logL) + state_prel(xprev); l.z = state_z(xprev); l.u4 = state_u(xprev) * 4; l.nb = 0;
-            l.dc0 = (int16_t)pred[0]; l.dc1 = (int16_t)pred[1]; l.dc2 = (int16_t)pred[2];
+            int32_t p0 = (int16_t)pred[0], p1 = (int16_t)pred[1], p2 = (int16_t)pred[2];
             uint32_t unit = unit0, flags = 0;
             if (unit < total && (unit % im.in.units_per_mcu) * 4 != l.u4) flags |= kStUnit;
             const uint32_t limit = (i + 1) << logL;
             if (unit < total) {
-                win_init(w, l.p, fetch);
-                decode_span_write(l, w, limit, unit, total, E.sx, fetch, im.lut.data(), store, flags);
+                win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+                decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
             }
             if (unit < total) {
                 if (l.p < limit || pack_state(l.p - limit, l.z, l.u4 >> 2) != mine.x) flags |= kStMismatch;

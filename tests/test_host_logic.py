@@ -206,26 +206,26 @@ def test_lookup_tables_decode_every_codeword(emul, optimize):
 
                 def look(peek16):
                     e = int(lut[peek16 >> (16 - K)])
-                    if e & 0x8000:
-                        nb2, off = (e >> 9) & 7, e & 511
+                    if e & 31 == 0:                         # escape to the second level
+                        nb2, off = (e >> 5) & 7, (e >> 8) << 1
                         j = (peek16 >> (16 - K - nb2)) & ((1 << nb2) - 1)
                         e = int(lut[L1 + off + j])
-                        if e & 0x8000:
-                            return None
-                    return e & 31, (e >> 5) & 31, (e >> 10) & 15, bool(e & 0x4000)
+                    ln, size, adv = e & 31, (e >> 5) & 31, e >> 10
+                    if adv == 0:
+                        assert (ln, size) == (1, 0)         # "no codeword": skip one bit
+                        return None
+                    return ln, size, adv
                 covered = np.zeros(1 << 16, bool)
                 for s in vals:
                     ln = int(length[s])
                     lo = int(code[s]) << (16 - ln)
                     covered[lo:lo + (1 << (16 - ln))] = True
                     want_size = min(int(s), 16) if cls == 0 else int(s) & 15
-                    want_run = 0 if cls == 0 else int(s) >> 4
-                    eob = cls == 1 and (int(s) & 15) == 0 and (int(s) >> 4) != 15
+                    run = int(s) >> 4
+                    # slots covered: DC 1; coefficient run+1; ZRL 16; end of block 63 (completes any unit from z >= 1)
+                    want_adv = 1 if cls == 0 else (run + 1 if want_size else (16 if run == 15 else 63))
                     for tail in {0, (1 << (16 - ln)) - 1, 0x5555 & ((1 << (16 - ln)) - 1)}:
-                        got = look(lo | tail)
-                        assert got is not None and got[0] == ln and got[3] == eob
-                        if not eob:
-                            assert got[1] == want_size and got[2] == want_run
+                        assert look(lo | tail) == (ln, want_size, want_adv)
                 for peek in np.flatnonzero(~covered)[::97]:
                     assert look(int(peek)) is None
 
