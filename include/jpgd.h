@@ -77,7 +77,7 @@ typedef struct {
                               or 2048; 0 = choose per call from the stream sizes                   */
     uint32_t overlap;      /* subsequences by which neighbouring sequences overlap (warm-up lanes
                               in front of each sequence); 0 = the paper's disjoint sequences;
-                              must be < 192; 0xFFFFFFFF = library default                          */
+                              must be < 192; 0xFFFFFFFF = library default (16 or 32)               */
     uint32_t max_rounds;   /* upper bound on inter-sequence synchronisation rounds; 0 = number of
                               sequences (always enough)                                             */
     uint32_t flags;        /* JPGD_F_* */

@@ -56,9 +56,15 @@ bool same_tables(const jpgd_info& a, const jpgd_info& b) {
     return true;
 }
 
+// Subsequence size when the caller leaves it open.  The paper picks 1024 bits for high-quality material and
+// 128 for short streams (Section 5, Tables II and III).  Here: as large as possible (fewer overflow rounds,
+// fewer records) while the call still has about 64k subsequences to spread over the chip's 1024 SIMDs.
 uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
-    (void)infos; (void)n;
-    return 1024u;  // the size the paper uses for high-quality material (Section 5, Tables II and III)
+    uint64_t bits = 0;
+    for (int i = 0; i < n; ++i) bits += infos[i].scan_bytes * 8u;
+    uint32_t L = 128u;
+    while (L < 1024u && bits / (2u * L) >= 65536u) L *= 2u;
+    return L;
 }
 
 // Validates arguments that do not need the GPU and lays the workspace out.
@@ -66,7 +72,9 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     if (!infos || n < 1) return JPGD_E_ARG;
     uint32_t L = cfg && cfg->subseq_bits ? cfg->subseq_bits : choose_subseq_bits(infos, n);
     if (L < 128u || L > 2048u || (L & (L - 1u))) return JPGD_E_ARG;
-    uint32_t H = (!cfg || cfg->overlap == 0xFFFFFFFFu) ? 0u : cfg->overlap;
+    // default overlap: enough warm-up lanes that the chain entering a sequence is almost always synchronised,
+    // which leaves the inter-sequence kernel one subsequence per boundary
+    uint32_t H = (!cfg || cfg->overlap == 0xFFFFFFFFu) ? (L <= 256u ? 16u : 32u) : cfg->overlap;
     if (H > (uint32_t)kMaxOverlap) return JPGD_E_ARG;
     const uint32_t seq_len = kWG - H;
     pl.L = L;
@@ -220,7 +228,7 @@ int hip_failed(const char* what, hipError_t e) {
 
 size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
     uint32_t nwords = kWG * (L / 32) + 4;
-    return (size_t)lut_slots * kLutEntries * 2 + 4 * kWG * 4 + (size_t)nwords * 4;
+    return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4;
 }
 size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
     uint32_t nwords = kWG * (L / 32) + 4;

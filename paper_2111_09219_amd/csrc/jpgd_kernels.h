@@ -243,7 +243,11 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     uint32_t* pnb = sw + kWG;
     uint32_t* pdc01 = pnb + kWG;
     uint32_t* pdc2 = pdc01 + kWG;
-    uint32_t* strm = pdc2 + kWG;
+    uint32_t* mv_p = pdc2 + kWG;     // staging for packing the running chains
+    uint32_t* mv_uz = mv_p + kWG;
+    uint32_t* mv_tt = mv_uz + kWG;
+    uint32_t* strm = mv_tt + kWG;
+    __shared__ uint32_t scratch[8];
 
     const uint32_t L = 1u << P.logL, wps = L >> 5;  // words per subsequence
     const uint32_t first = base < 0 ? 0u : (uint32_t)base;
@@ -266,6 +270,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         const uint32_t i = (uint32_t)(base + (int32_t)t);
         l.p = i << P.logL; l.u4 = 0u; l.z = 0u; l.nb = 0u;
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+        prime(l, w, sx, lut_s);
         const uint32_t limit = (i + 1u) << P.logL;
         decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         sw[t] = pack_state(l.p - limit, l.z, l.u4 >> 2);
@@ -273,12 +278,37 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         pdc01[t] = pack_dc01(dcacc);
         pdc2[t] = pack_dc2(dcacc);
     }
-    // overflow rounds: in round r lane t decodes subsequence t+r from its own state and compares with the
-    // record the lane before it in the chain (t+1) left there one round earlier
+    // Overflow rounds: in round r the chain that started at subsequence c decodes subsequence c+r from its own
+    // state and compares with the record left there one round earlier by the chain that started at c+1.
+    // Chains drop out as they synchronise.  To keep the wavefronts full, the chains still running are packed
+    // into the lowest lanes whenever their number has changed: a chain is (p, u, z, target), everything else is
+    // rebuilt from the staged stream, so moving one costs three LDS words.
     bool active = valid && (t + 1u < t1);
     uint32_t tt = t + 1u;
+    uint32_t running = kWG + 1u;  // chains running after the previous round (more than any count: first round packs)
     for (;;) {
-        if (!__syncthreads_or(active ? 1 : 0)) break;
+        uint32_t now;
+        const uint32_t rank = wg_excl_scan(active ? 1u : 0u, scratch, &now);
+        if (now == 0u) break;
+        if (now != running) {
+            if (active) {
+                mv_p[rank] = l.p;
+                mv_uz[rank] = (l.u4 << 8) | l.z;
+                mv_tt[rank] = tt;
+            }
+            __syncthreads();
+            active = t < now;
+            if (active) {
+                l.p = mv_p[t];
+                const uint32_t uz = mv_uz[t];
+                l.u4 = uz >> 8;
+                l.z = uz & 255u;
+                tt = mv_tt[t];
+                win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+                prime(l, w, sx, lut_s);
+            }
+            running = now;
+        }
         if (active) {
             l.nb = 0u;
             dcacc = 0;
@@ -330,6 +360,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     l.z = state_z(x0);
     l.u4 = state_u(x0) * 4u;
     win_init(w, l.p, l.p >> 5, fetch);  // cursor = word index in the image's stream
+    prime(l, w, sx, lut_s);
     bool first = true;
     for (;;) {
         l.nb = 0u;
@@ -470,6 +501,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t limit = (i + 1u) << P.logL;
     if (unit < total) {
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+        prime(l, w, sx, lut_s);
         decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
     // every lane checks the chain: unless the image is complete it must end in the recorded state

@@ -140,6 +140,7 @@ void sync_intra(Emul& E) {
             l[t].p = i << logL; l[t].u4 = 0; l[t].z = 0; l[t].nb = 0;
             dcacc[t] = 0;
             win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);
+            prime(l[t], bw[t], E.sx, im.lut.data());
             uint32_t limit = (i + 1) << logL;
             decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
             sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
@@ -159,6 +160,8 @@ void sync_intra(Emul& E) {
                 if (!active[t]) continue;
                 l[t].nb = 0;
                 dcacc[t] = 0;
+                win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);  // a chain moved to another lane restarts its window
+                prime(l[t], bw[t], E.sx, im.lut.data());
                 uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
                 decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
                 uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
@@ -193,6 +196,7 @@ void sync_inter(Emul& E) {
         BitWin w;
         l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u4 = state_u(x0) * 4;
         win_init(w, l.p, l.p >> 5, fetch);
+        prime(l, w, E.sx, im.lut.data());
         bool first = true;
         for (;;) {
             l.nb = 0;
@@ -246,6 +250,7 @@ void scan_and_write(Emul& E, int16_t* coef) {
             const uint32_t limit = (i + 1) << logL;
             if (unit < total) {
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+                prime(l, w, E.sx, im.lut.data());
                 decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
             }
             if (unit < total) {
