@@ -23,6 +23,17 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain copy of known size; taken from the summaries in profiles/ (same commands).
+MEASURED_TRAFFIC = {
+    ("hd1088_444_q90", "sync_intra"): 1.71e6,
+    ("hd1088_444_q90", "write"): 8.09e6,
+    ("hd1088_444_q90", "pixels"): 18.91e6,
+    ("uhd16k_420_q92_flat_random", "sync_intra"): 84.64e6,
+    ("uhd16k_420_q92_flat_random", "write"): 1543.65e6,
+    ("uhd16k_420_q92_flat_random", "pixels"): 796.34e6,
+}
+
 
 def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: int) -> int:
     """Bytes the method itself must move per launch ("Kernels"): Bs stuffed bytes, B unstuffed
@@ -51,6 +62,8 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=-1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing; 0 skips it")
     ap.add_argument("--limit", type=int, default=0, help="images of the batch config to use (0 = all)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of decoding, run plain device copies of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (nothing here is distributed)" % args.gpus,
@@ -64,6 +77,19 @@ def main() -> int:
         print("bench.py: no GPU visible; the decoder has no CPU path", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 5, "gbs": round(2 * n / 1e9 / dt, 1)}))
+        return 0
 
     c = args.config
     wl = CONFIGS[c]
@@ -165,7 +191,8 @@ def main() -> int:
             "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
             "inter_rounds": rep.inter_rounds, "redo": rep.redo},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not args.subseq_bits else None,
                      "avg_launch_ms": round(dom_avg_ms, 5), "alg_bytes_per_launch": alg},
         "cpu_baseline": cpu,
         "kernels": kernels,
