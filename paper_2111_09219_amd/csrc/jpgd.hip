@@ -2,6 +2,7 @@
 // C ABI declared in include/jpgd.h.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -226,19 +227,30 @@ int hip_failed(const char* what, hipError_t e) {
         if (e_ != hipSuccess) return hip_failed(#expr, e_);         \
     } while (0)
 
+// subsequences of up to this many bits are staged in LDS by the sync and write kernels
+// (JPGD_STAGED_MAX_BITS overrides it for tuning runs)
+uint32_t staged_max_bits() {
+    static const uint32_t v = [] {
+        const char* e = getenv("JPGD_STAGED_MAX_BITS");
+        return e ? (uint32_t)atoi(e) : 2048u;
+    }();
+    return v;
+}
+#define kStagedMaxL staged_max_bits()
+
 size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
-    uint32_t nwords = kWG * (L / 32) + 4;
+    uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
     return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4;
 }
 size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
-    uint32_t nwords = kWG * (L / 32) + 4;
+    uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
     return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4;
 }
 
 // dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
-size_t g_lds_granted[3] = {0, 0, 0};
+size_t g_lds_granted[6] = {0, 0, 0, 0, 0, 0};
 int grant_lds(int which, const void* kernel, size_t bytes) {
-    if (bytes <= g_lds_granted[which]) return JPGD_OK;
+    if (bytes <= 48 * 1024 || bytes <= g_lds_granted[which]) return JPGD_OK;
     HIP_OK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
     g_lds_granted[which] = bytes;
     return JPGD_OK;
@@ -278,7 +290,9 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     if (lds_sync > 150 * 1024) return JPGD_E_ARG;
 
     std::lock_guard<std::mutex> lock(g_stage.mu);
-    if ((rc = grant_lds(0, (const void*)k_sync_intra, lds_sync)) || (rc = grant_lds(1, (const void*)k_write, lds_write)) ||
+    const bool staged = pl.L <= kStagedMaxL;
+    if ((rc = grant_lds(staged ? 0 : 3, staged ? (const void*)k_sync_intra<true> : (const void*)k_sync_intra<false>, lds_sync)) ||
+        (rc = grant_lds(staged ? 1 : 4, staged ? (const void*)k_write<true> : (const void*)k_write<false>, lds_write)) ||
         (rc = grant_lds(2, (const void*)k_sync_inter, lds_inter)))
         return rc;
     int slot;
@@ -360,9 +374,15 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     } while (0)
 
     LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles, kWG, 0);
-    LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
+    bool big_tiles = false, big_groups = false;  // the two image-level scans are only needed beyond 256 tiles / groups
+    for (int i = 0; i < n; ++i) {
+        big_tiles = big_tiles || pl.img[i].ntiles > (uint32_t)kWG;
+        big_groups = big_groups || pl.img[i].ngrp_max > (uint32_t)kWG;
+    }
+    if (big_tiles) LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
-    LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra, pl.seqs, kWG, lds_sync);
+    if (staged) LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra<true>, pl.seqs, kWG, lds_sync);
+    else LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra<false>, pl.seqs, kWG, lds_sync);
 
     uint32_t rounds = 0, redo = 0, flags = 0;
     const uint32_t max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
@@ -372,11 +392,16 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
             ++rounds;
         }
         LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, pl.grps, kWG, 0);
-        LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
+        if (big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
         LAUNCH(JPGD_K_ZERO, k_zero_coef, pl.zerowgs, kWG, 0);
-        LAUNCH(JPGD_K_WRITE, k_write, pl.grps, kWG, lds_write);
-        HIP_OK(hipGetLastError());
+        if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
+        else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
         HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + pl.h.off_status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+        // The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the
+        // verdict is bad its output is either redone below or reported as unspecified.  This keeps one host
+        // round trip out of the critical path.
+        if (want_pixels) LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
+        HIP_OK(hipGetLastError());
         HIP_OK(hipStreamSynchronize(stream));
         flags = g_stage.verdict[0];
         const bool chain_broken = (flags & (kStMismatch | kStUnit)) != 0;
@@ -385,11 +410,6 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         if (!chain_broken || !pl.bnds || rounds >= max_rounds) break;
         ++redo;
         HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
-    }
-    if (!flags && want_pixels) {
-        LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
-        HIP_OK(hipGetLastError());
-        HIP_OK(hipStreamSynchronize(stream));
     }
 #undef LAUNCH
     if (report) {
@@ -487,7 +507,7 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     P.nimg = 1;
     P.logL = 10;
     hipLaunchKernelGGL(k_unstuff_count, dim3(tiles), dim3(kWG), 0, stream, P);
-    hipLaunchKernelGGL(k_unstuff_scan, dim3(1), dim3(kWG), 0, stream, P);
+    if (tiles > (uint32_t)kWG) hipLaunchKernelGGL(k_unstuff_scan, dim3(1), dim3(kWG), 0, stream, P);
     hipLaunchKernelGGL(k_unstuff_scatter, dim3(tiles), dim3(kWG), 0, stream, P);
     HIP_OK(hipGetLastError());
     HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + off_state, sizeof(ImgState), hipMemcpyDeviceToHost, stream));

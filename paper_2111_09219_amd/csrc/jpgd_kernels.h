@@ -164,6 +164,7 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scan(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t ii = blockIdx.x;
     const ImgDesc& D = P.img[ii];
+    if (D.ntiles <= (uint32_t)kWG) return;  // images of up to 256 tiles: the scatter kernel sums the counts itself
     uint32_t carry = 0u;
     for (uint32_t base = 0; base < D.ntiles; base += kWG) {
         uint32_t k = base + threadIdx.x;
@@ -199,8 +200,24 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     for (uint32_t j = 0; j < 16u; ++j)
         if (u.keep_mask & (1u << j)) buf[off++] = (uint8_t)(u.bytes[j >> 2] >> (8u * (j & 3u)));
     __syncthreads();
+    // bytes removed before this tile: from the scan kernel, or, for images of up to 256 tiles, summed here
+    uint32_t before, nbytes;
+    if (D.ntiles <= (uint32_t)kWG) {
+        const uint32_t v = threadIdx.x < D.ntiles ? P.tile_cnt[D.tile0 + threadIdx.x] : 0u;
+        uint32_t all;
+        wg_excl_scan(v, scratch, &all);
+        wg_excl_scan(threadIdx.x < lt ? v : 0u, scratch, &before);
+        nbytes = D.scan_bytes - all;
+        if (lt == 0u && threadIdx.x == 0u) {
+            P.st[ii].nbytes = nbytes;
+            P.st[ii].nsub = (uint32_t)(((uint64_t)nbytes * 8u + (1u << P.logL) - 1u) >> P.logL);
+        }
+    } else {
+        before = P.tile_cnt[wg];
+        nbytes = P.st[ii].nbytes;
+    }
     // output position of this tile's first kept byte
-    const uint32_t o = lt * (uint32_t)kUnstuffTile - P.tile_cnt[wg];
+    const uint32_t o = lt * (uint32_t)kUnstuffTile - before;
     const uint32_t a = o & 3u;
     const uint32_t nd = (a + T + 3u) >> 2;
     uint32_t* out32 = reinterpret_cast<uint32_t*>(out + (o - a));
@@ -219,7 +236,6 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     }
     // the last tile clears what lanes may read past the end: one subsequence plus 64 bytes
     if (lt == D.ntiles - 1u) {
-        const uint32_t nbytes = P.st[ii].nbytes;
         const uint32_t clear = (1u << (P.logL - 3u)) + 64u;
         for (uint32_t k = threadIdx.x; k < clear; k += kWG) out[nbytes + k] = 0u;
     }
@@ -229,6 +245,10 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
 // Workgroup w of an image covers the kWG subsequences base .. base+kWG-1, base = w*seq_len - overlap, and
 // publishes the records of the last seq_len of them; the first `overlap` lanes only warm the chain up.
 
+// STAGED: the workgroup's stretch of the stream is copied to LDS first (small subsequences); otherwise lanes
+// read their words from global memory, one refill ahead, which leaves LDS to the tables and lets more
+// workgroups share a CU (large subsequences).
+template <bool STAGED>
 __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
@@ -256,11 +276,13 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     const uint32_t first_word = first * wps;
     const uint32_t nwords = (t1 - t0) * wps + 4u;
     stage_luts(P, D, lut_s);
-    stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
+    if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
     __syncthreads();
 
     const Syntax sx = syntax_of(D);
-    auto fetch = [&](uint32_t c) { return strm[c]; };  // cursor = word index inside the staged window
+    const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
+    // cursor = word index inside the workgroup's window
+    auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
     const uint32_t t = threadIdx.x;
     const bool valid = t >= t0 && t < t1;
     Lane l;
@@ -409,6 +431,7 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t ii = blockIdx.x;
     const ImgDesc& D = P.img[ii];
+    if (D.ngrp_max <= (uint32_t)kWG) return;  // images of up to 256 groups: the write kernel sums the totals itself
     const uint32_t ngrp = (P.st[ii].nsub + kWG - 1u) / kWG;
     uint32_t carry[4] = {0u, 0u, 0u, 0u};
     for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
@@ -443,6 +466,7 @@ __global__ __launch_bounds__(kWG) void k_zero_coef(Params P) {
 
 // ---- write pass (paper, Algorithm 1 last loop; Algorithm 2 with write = true) ---------------------------
 
+template <bool STAGED>
 __global__ __launch_bounds__(kWG) void k_write(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t scratch[8];
@@ -461,7 +485,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t first_word = i0 * wps;
     const uint32_t nwords = nloc * wps + 4u;
     stage_luts(P, D, lut_s);
-    stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
+    if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
 
     const uint32_t t = threadIdx.x;
     const uint32_t i = i0 + t;
@@ -475,8 +499,19 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     }
     // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
     // plus the group's prefix
-    const int4 gp = P.grp_pref[wg];
+    int4 gp;
     uint32_t tot;
+    if (D.ngrp_max <= (uint32_t)kWG) {
+        const int4 v = (t < lg) ? P.grp_tot[D.grp0 + t] : make_int4(0, 0, 0, 0);
+        uint32_t g0, g1, g2, g3;
+        wg_excl_scan((uint32_t)v.x, scratch, &g0);
+        wg_excl_scan((uint32_t)v.y, scratch, &g1);
+        wg_excl_scan((uint32_t)v.z, scratch, &g2);
+        wg_excl_scan((uint32_t)v.w, scratch, &g3);
+        gp = make_int4((int)g0, (int)g1, (int)g2, (int)g3);
+    } else {
+        gp = P.grp_pref[wg];
+    }
     uint32_t unit = (uint32_t)gp.x + wg_excl_scan(mine.y, scratch, &tot);
     int32_t pred0 = gp.y + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z), scratch, &tot);
     int32_t pred1 = gp.z + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z >> 16), scratch, &tot);
@@ -485,7 +520,8 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     if (!valid) return;
 
     const Syntax sx = syntax_of(D);
-    auto fetch = [&](uint32_t c) { return strm[c]; };
+    const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
+    auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
     int16_t* coef = P.coef + D.coef_off;
     auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)k * 64u + at] = v; };
     Lane l;
