@@ -46,7 +46,6 @@ def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: i
         "sync_inter": 16 * (S // 256 + 1),
         "scan_totals": 16 * S,
         "scan_prefix": 32 * (S // 256 + 1),
-        "zero": 128 * K,
         "write": B + 16 * S + 128 * K,
         "pixels": 128 * K + out_bytes,
     }[kernel]
@@ -102,14 +101,15 @@ def main() -> int:
     K = int(sum(i.total_units for i in batch.infos))
     out_bytes = int(sum(i.width * i.height * i.ncomp for i in batch.infos))
 
-    # warm-up; the first steps also time every kernel once to find the dominant one
+    # warm-up; its last steps time every kernel to find the dominant one
     cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            timing_mask=0x3FF)
+                            timing_mask=(1 << len(J.KERNELS)) - 1)
     split = np.zeros(len(J.KERNELS))
     nsplit = max(1, min(5, args.warmup))
     rep = None
-    for w in range(max(args.warmup, nsplit)):
-        if w < nsplit:
+    nwarm = max(args.warmup, nsplit + 1)
+    for w in range(nwarm):
+        if w >= nwarm - nsplit:   # the last warm-up steps: clocks and caches are settled by then
             rep = batch.decode(cfg=cfg_all)
             split += np.array(list(rep.kernel_ms))
         else:

@@ -96,7 +96,6 @@ enum {
     JPGD_K_SYNC_INTER,        /* Algorithm 3, second loop                                          */
     JPGD_K_SCAN_TOTALS,       /* exclusive scan over s_info: totals per group of 256 records       */
     JPGD_K_SCAN_PREFIX,       /* exclusive scan over s_info: prefix of the group totals            */
-    JPGD_K_ZERO,              /* clears the coefficient buffer                                     */
     JPGD_K_WRITE,             /* Algorithm 1, write pass                                           */
     JPGD_K_PIXELS,            /* Section 4.3 plus colour                                           */
     JPGD_N_KERNELS

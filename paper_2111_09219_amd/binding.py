@@ -58,14 +58,14 @@ class Config(ctypes.Structure):
 
 
 KERNELS = ["unstuff_count", "unstuff_scan", "unstuff_scatter", "sync_intra", "sync_inter", "scan_totals",
-           "scan_prefix", "zero", "write", "pixels"]
+           "scan_prefix", "write", "pixels"]
 
 
 class Report(ctypes.Structure):
     """jpgd_report"""
     _fields_ = [("subseq_bits", ctypes.c_uint32), ("n_subseq", ctypes.c_uint32), ("n_sequences", ctypes.c_uint32),
                 ("inter_rounds", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("device_flags", ctypes.c_uint32),
-                ("launches", ctypes.c_uint32 * 10), ("kernel_ms", ctypes.c_float * 10)]
+                ("launches", ctypes.c_uint32 * 9), ("kernel_ms", ctypes.c_float * 9)]
 
     def as_dict(self):
         d = {k: int(getattr(self, k)) for k, _ in self._fields_[:6]}

@@ -32,7 +32,7 @@ struct Plan {
     std::vector<ImgDesc> img;
     std::vector<uint32_t> lut_of_img;  // index of the table set of image i
     uint32_t nsets = 0, lut_slots = 0;
-    uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, zerowgs = 0, nsub_total = 0;
+    uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, nsub_total = 0;
     uint32_t L = 0;
 };
 
@@ -119,9 +119,6 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         d.pix_runs = (d.mcus_x + M - 1) / M;
         d.pix_wg0 = pl.pixwgs;
         pl.pixwgs += d.pix_runs * d.mcus_y;
-        d.zero_wg0 = pl.zerowgs;
-        d.zero_nwg = (uint32_t)(((uint64_t)d.total_units * 128 + kZeroChunk - 1) / kZeroChunk);
-        pl.zerowgs += d.zero_nwg;
         coef_units += d.total_units;
         // table slots: distinct DC tables first, then distinct AC tables, in order of first use
         uint32_t dc_ids[3], ac_ids[3], ndc = 0, nac = 0, comp_dc[3], comp_ac[3];
@@ -393,7 +390,6 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         }
         LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, pl.grps, kWG, 0);
         if (big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
-        LAUNCH(JPGD_K_ZERO, k_zero_coef, pl.zerowgs, kWG, 0);
         if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
         else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
         HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + pl.h.off_status, sizeof(Status), hipMemcpyDeviceToHost, stream));

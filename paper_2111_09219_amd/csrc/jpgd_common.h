@@ -94,8 +94,6 @@ struct ImgDesc {
     uint32_t pix_wg0;      // first workgroup of the pixel kernel
     uint32_t pix_runs;     // workgroups per MCU row
     uint32_t qt_off;       // element (uint16) offset of 3 x 64 quantisation values (per component, zig-zag)
-    uint32_t zero_wg0;     // first workgroup of the coefficient zero-fill
-    uint32_t zero_nwg;
     uint32_t pad_;
 };
 
@@ -120,7 +118,6 @@ struct Status {
 
 constexpr int kUnstuffTile = 4096;  // bytes per workgroup of the unstuff kernels (256 lanes x 16 bytes)
 constexpr int kPixBlocks = 48;      // data units per workgroup of the pixel kernel
-constexpr uint32_t kZeroChunk = 1u << 16;  // bytes per workgroup of the zero-fill
 
 JPGD_HD uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 

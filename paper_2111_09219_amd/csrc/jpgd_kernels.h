@@ -75,12 +75,12 @@ __device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, ui
     for (uint32_t k = threadIdx.x; k < n16 / 8u; k += blockDim.x) dst[k] = src[k];
 }
 
-__device__ __forceinline__ Syntax syntax_of(const ImgDesc& D) {
+// rows: 8 entries of LDS, complete after the next barrier
+__device__ __forceinline__ Syntax stage_syntax(const ImgDesc& D, UnitRow* rows) {
+    if (threadIdx.x < D.upm) rows[threadIdx.x] = make_unit_row(threadIdx.x, D.upm, D.sched_dc, D.sched_ac, D.sched_comp);
     Syntax sx;
-    sx.sched_dc = D.sched_dc;
-    sx.sched_ac = D.sched_ac;
-    sx.sched_comp = D.sched_comp;
-    sx.upm4 = D.upm * 4u;
+    sx.rows = rows;
+    sx.upm = D.upm;
     return sx;
 }
 
@@ -275,11 +275,12 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     const uint32_t t1 = min((uint32_t)kWG, (uint32_t)((int32_t)nsub - base));  // one past the last such lane
     const uint32_t first_word = first * wps;
     const uint32_t nwords = (t1 - t0) * wps + 4u;
+    __shared__ UnitRow rows[8];
     stage_luts(P, D, lut_s);
+    const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
     __syncthreads();
 
-    const Syntax sx = syntax_of(D);
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     // cursor = word index inside the workgroup's window
     auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
@@ -290,12 +291,12 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     int64_t dcacc = 0;
     if (valid) {
         const uint32_t i = (uint32_t)(base + (int32_t)t);
-        l.p = i << P.logL; l.u4 = 0u; l.z = 0u; l.nb = 0u;
+        l.p = i << P.logL; l.u = 0u; l.z = 0u; l.nb = 0u;
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
         prime(l, w, sx, lut_s);
         const uint32_t limit = (i + 1u) << P.logL;
         decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
-        sw[t] = pack_state(l.p - limit, l.z, l.u4 >> 2);
+        sw[t] = pack_state(l.p - limit, l.z, l.u);
         pnb[t] = l.nb;
         pdc01[t] = pack_dc01(dcacc);
         pdc2[t] = pack_dc2(dcacc);
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         if (now != running) {
             if (active) {
                 mv_p[rank] = l.p;
-                mv_uz[rank] = (l.u4 << 8) | l.z;
+                mv_uz[rank] = (l.u << 8) | l.z;
                 mv_tt[rank] = tt;
             }
             __syncthreads();
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
             if (active) {
                 l.p = mv_p[t];
                 const uint32_t uz = mv_uz[t];
-                l.u4 = uz >> 8;
+                l.u = uz >> 8;
                 l.z = uz & 255u;
                 tt = mv_tt[t];
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
             dcacc = 0;
             const uint32_t limit = ((uint32_t)(base + (int32_t)tt) + 1u) << P.logL;
             decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
-            const uint32_t x = pack_state(l.p - limit, l.z, l.u4 >> 2);
+            const uint32_t x = pack_state(l.p - limit, l.z, l.u);
             const bool synced = x == sw[tt];
             sw[tt] = x;
             pnb[tt] = l.nb;
@@ -364,14 +365,15 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     const ImgDesc& D = P.img[ii];
     const uint32_t nsub = P.st[ii].nsub;
     uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
+    __shared__ UnitRow rows[8];
     stage_luts(P, D, lut_s);
+    const Syntax sx = stage_syntax(D, rows);
     __syncthreads();
     const uint32_t b = (wg - D.bnd0) * 64u + threadIdx.x;
     const uint64_t gfirst = (uint64_t)(b + 1u) * P.seq_len;
     if (gfirst >= nsub) return;
     uint32_t g = (uint32_t)gfirst;
     const uint32_t gend = min(nsub, g + P.seq_len);
-    const Syntax sx = syntax_of(D);
     const uint32_t* words = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off);
     auto fetch = [&](uint32_t w) { return __builtin_bswap32(words[w]); };
     SInfo* rec = P.sinfo + D.sub0;
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     BitWin w;
     l.p = (g << P.logL) + state_prel(x0);
     l.z = state_z(x0);
-    l.u4 = state_u(x0) * 4u;
+    l.u = state_u(x0);
     win_init(w, l.p, l.p >> 5, fetch);  // cursor = word index in the image's stream
     prime(l, w, sx, lut_s);
     bool first = true;
@@ -390,7 +392,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
         const uint32_t limit = (g + 1u) << P.logL;
         decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         SInfo r;
-        r.x = pack_state(l.p - limit, l.z, l.u4 >> 2);
+        r.x = pack_state(l.p - limit, l.z, l.u);
         r.y = l.nb;
         r.z = pack_dc01(dcacc);
         r.w = pack_dc2(dcacc);
@@ -449,21 +451,6 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
     }
 }
 
-// ---- coefficient buffer clear -------------------------------------------------------------------------
-
-__global__ __launch_bounds__(kWG) void k_zero_coef(Params P) {
-    const uint32_t wg = blockIdx.x;
-    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.zero_wg0; });
-    const ImgDesc& D = P.img[ii];
-    const uint64_t bytes = (uint64_t)D.total_units * 128u;
-    const uint64_t begin = (uint64_t)(wg - D.zero_wg0) * kZeroChunk;
-    uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint8_t*>(P.coef + D.coef_off) + begin);
-    const uint64_t left = bytes - begin;
-    const uint64_t n16 = (left < (uint64_t)kZeroChunk ? left : (uint64_t)kZeroChunk) / 16u;  // 128 bytes per unit
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    for (uint64_t k = threadIdx.x; k < n16; k += kWG) dst[k] = zero;
-}
-
 // ---- write pass (paper, Algorithm 1 last loop; Algorithm 2 with write = true) ---------------------------
 
 template <bool STAGED>
@@ -484,7 +471,9 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t nloc = min((uint32_t)kWG, nsub - i0);
     const uint32_t first_word = i0 * wps;
     const uint32_t nwords = nloc * wps + 4u;
+    __shared__ UnitRow rows[8];
     stage_luts(P, D, lut_s);
+    const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
 
     const uint32_t t = threadIdx.x;
@@ -512,14 +501,39 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     } else {
         gp = P.grp_pref[wg];
     }
-    uint32_t unit = (uint32_t)gp.x + wg_excl_scan(mine.y, scratch, &tot);
+    uint32_t grp_units;
+    uint32_t unit = (uint32_t)gp.x + wg_excl_scan(mine.y, scratch, &grp_units);
     int32_t pred0 = gp.y + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z), scratch, &tot);
     int32_t pred1 = gp.z + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z >> 16), scratch, &tot);
     int32_t pred2 = gp.w + (int32_t)wg_excl_scan((uint32_t)sx16(mine.w), scratch, &tot);
-    __syncthreads();  // staged tables and stream are complete
+
+    // The group clears the coefficients it is about to fill: those from where its first subsequence takes
+    // over (data unit and zig-zag index) to where the next group's does; the last group goes on to the end of
+    // the image.  The ranges of the groups tile the image, and a lane only stores inside its group's range.
+    {
+        const uint64_t end_all = (uint64_t)D.total_units * 64u;
+        const uint32_t x_in = i0 > 0u ? rec[i0 - 1u].x : 0u;
+        const uint32_t x_out = rec[i0 + nloc - 1u].x;
+        uint64_t a = (uint64_t)(uint32_t)gp.x * 64u + state_z(x_in);
+        uint64_t b = i0 + nloc >= nsub ? end_all : ((uint64_t)(uint32_t)gp.x + grp_units) * 64u + state_z(x_out);
+        if (i0 == 0u) a = 0u;
+        if (b > end_all) b = end_all;
+        if (a < b) {
+            int16_t* c0 = P.coef + D.coef_off;
+            uint64_t a8 = (a + 7u) & ~(uint64_t)7u;
+            if (a8 > b) a8 = b;
+            const uint64_t b8 = a8 + ((b - a8) & ~(uint64_t)7u);
+            if (a + t < a8) c0[a + t] = 0;
+            if (b8 + t < b) c0[b8 + t] = 0;
+            uint4* body = reinterpret_cast<uint4*>(c0 + a8);
+            const uint32_t n16 = (uint32_t)((b8 - a8) >> 3);
+            const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+            for (uint32_t k = t; k < n16; k += kWG) body[k] = zero;
+        }
+    }
+    __syncthreads();  // staged tables and stream are complete; the cleared range is in place
     if (!valid) return;
 
-    const Syntax sx = syntax_of(D);
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
     int16_t* coef = P.coef + D.coef_off;
@@ -528,12 +542,12 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     BitWin w;
     l.p = (i << P.logL) + state_prel(xprev);
     l.z = state_z(xprev);
-    l.u4 = state_u(xprev) * 4u;
+    l.u = state_u(xprev);
     l.nb = 0u;
     pred0 = (int32_t)(int16_t)pred0; pred1 = (int32_t)(int16_t)pred1; pred2 = (int32_t)(int16_t)pred2;
     uint32_t flags = 0u;
     const uint32_t total = D.total_units;
-    if (unit < total && (unit % D.upm) * 4u != l.u4) flags |= kStUnit;
+    if (unit < total && unit % D.upm != l.u) flags |= kStUnit;
     const uint32_t limit = (i + 1u) << P.logL;
     if (unit < total) {
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
@@ -542,7 +556,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     }
     // every lane checks the chain: unless the image is complete it must end in the recorded state
     if (unit < total) {
-        if (l.p < limit || pack_state(l.p - limit, l.z, l.u4 >> 2) != mine.x) flags |= kStMismatch;
+        if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;
         if (i == nsub - 1u) flags |= kStShort;
     }
     if (flags) atomicOr(&P.status->flags, flags);

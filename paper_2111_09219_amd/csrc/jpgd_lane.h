@@ -15,73 +15,78 @@
 
 namespace jpgd {
 
+// What a lane needs to know about one data unit of the MCU: where the tables of its symbols are, which
+// DC sum it feeds, and which unit follows.  One row per data unit, 16 bytes, read as a whole.
+struct alignas(16) UnitRow {
+    uint32_t tb_ac;       // first entry of the unit's AC table inside the LUT array
+    uint32_t tb_dc_next;  // first entry of the DC table of the unit that follows
+    uint32_t dcmul;       // 1 << (15 * component): the component's field of the packed DC sums
+    uint32_t next;        // index of the unit that follows
+};
+
+// sched_*: 4 bits per data unit (see ImgDesc)
+JPGD_HD UnitRow make_unit_row(uint32_t u, uint32_t upm, uint32_t sched_dc, uint32_t sched_ac, uint32_t sched_comp) {
+    UnitRow r;
+    const uint32_t un = u + 1u == upm ? 0u : u + 1u;
+    r.tb_ac = ((sched_ac >> (4u * u)) & 15u) * (uint32_t)kLutEntries;
+    r.tb_dc_next = ((sched_dc >> (4u * un)) & 15u) * (uint32_t)kLutEntries;
+    r.dcmul = 1u << (15u * ((sched_comp >> (4u * u)) & 15u));
+    r.next = un;
+    return r;
+}
+
 // Decoder state of the paper, (p, n, c, z), with c refined to the data unit inside the MCU
 // (two decoders inside different luminance units of a 4:2:0 MCU agree on the component but
 // not on what follows) and n kept as completed data units (see SInfo).
 struct Lane {
     uint32_t p;    // bit position in the unstuffed stream of the next syntax element
-    uint32_t u4;   // 4 * (data unit inside the MCU)
+    uint32_t u;    // data unit inside the MCU
     uint32_t z;    // zig-zag index of the next coefficient (0 = a DC symbol is next)
     uint32_t nb;   // data units completed since the counter was last cleared
-    // derived from u4 (set_unit)
-    uint32_t tb_ac;       // first entry of the unit's AC table inside the LUT array
-    uint32_t tb_dc_next;  // first entry of the DC table of the unit that follows
-    uint32_t comp;        // component of the unit
+    UnitRow row;   // row of unit u (prime, step_finish)
     // pipeline registers (prime)
-    uint32_t e;           // table entry already read for the symbol at p (possibly a first-level escape)
-    uint32_t base;        // table that entry came from
+    uint32_t e;    // table entry already read for the symbol at p (possibly a first-level escape)
+    uint32_t base; // table that entry came from
 };
 
-// 64-bit window on the stream, most significant bit first; at least 32 bits are valid before
-// every symbol (a codeword has at most 16 bits, its value at most 16).
+// Window on the stream: two consecutive big-endian words and the offset of the next unread bit in the
+// first; `peek` is the 32 bits that start there (a codeword has at most 16 bits, its value at most 16).
 struct BitWin {
-    uint64_t bb;
-    int32_t cnt;     // valid bits in bb
+    uint32_t hi, lo;
+    uint32_t o;      // 0..31
+    uint32_t peek;
     uint32_t next;   // cursor of the word held in `ahead`, in the units of the Fetch functor
-    uint32_t ahead;  // the next 32-bit word, fetched one refill early so that its latency is hidden
+    uint32_t ahead;  // the word after `lo`, fetched one refill early so that its latency is hidden
 };
 
 // per-image constants of the scan syntax
 struct Syntax {
-    uint32_t sched_dc, sched_ac, sched_comp;  // 4 bits per data unit (see ImgDesc)
-    uint32_t upm4;                            // 4 * units per MCU
+    const UnitRow* rows;  // one per data unit of the MCU
+    uint32_t upm;         // units per MCU
 };
 
-JPGD_HD uint32_t next_unit(uint32_t u4, const Syntax& sx) {
-    uint32_t un = u4 + 4u;
-    return un == sx.upm4 ? 0u : un;
-}
-
-JPGD_HD void set_unit(Lane& l, const Syntax& sx) {
-    l.tb_ac = ((sx.sched_ac >> l.u4) & 15u) * (uint32_t)kLutEntries;
-    l.tb_dc_next = ((sx.sched_dc >> next_unit(l.u4, sx)) & 15u) * (uint32_t)kLutEntries;
-    l.comp = (sx.sched_comp >> l.u4) & 15u;
+JPGD_HD uint32_t win_peek(const BitWin& w) {
+    return (uint32_t)(((((uint64_t)w.hi << 32) | (uint64_t)w.lo) << w.o) >> 32);
 }
 
 // `cursor` addresses the 32-bit word that holds bit p
 template <class Fetch>
 JPGD_HD void win_init(BitWin& w, uint32_t p, uint32_t cursor, Fetch fetch) {
-    uint32_t o = p & 31u;
-    uint64_t v = ((uint64_t)fetch(cursor) << 32) | (uint64_t)fetch(cursor + 1u);
-    w.bb = v << o;
-    w.cnt = 64 - (int32_t)o;
+    w.hi = fetch(cursor);
+    w.lo = fetch(cursor + 1u);
+    w.o = p & 31u;
+    w.peek = win_peek(w);
     w.next = cursor + 2u;
     w.ahead = fetch(w.next);
-    if (w.cnt <= 32) {
-        w.bb |= (uint64_t)w.ahead << (32 - w.cnt);
-        w.cnt += 32;
-        w.next++;
-        w.ahead = fetch(w.next);
-    }
 }
 
-// Starts the pipeline: after (p, u4, z) and the window are set, read the entry of the symbol at p.
+// Starts the pipeline: after (p, u, z) and the window are set, read the entry of the symbol at p.
 template <class LutPtr>
 JPGD_HD void prime(Lane& l, const BitWin& w, const Syntax& sx, LutPtr lut) {
-    set_unit(l, sx);
-    const uint32_t tb_dc = ((sx.sched_dc >> l.u4) & 15u) * (uint32_t)kLutEntries;
-    l.base = l.z == 0u ? tb_dc : l.tb_ac;
-    l.e = lut[l.base + ((uint32_t)(w.bb >> 32) >> (32 - kLutK))];
+    l.row = sx.rows[l.u];
+    const uint32_t tb_dc = sx.rows[l.u == 0u ? sx.upm - 1u : l.u - 1u].tb_dc_next;
+    l.base = l.z == 0u ? tb_dc : l.row.tb_ac;
+    l.e = lut[l.base + (w.peek >> (32 - kLutK))];
 }
 
 // value bits follow the codeword; "signed ones' complement" (paper, Section 2): a leading 1 means the
@@ -117,7 +122,7 @@ struct Step {
     bool esc;        // first-level escape: nothing was consumed, the state did not change
     bool is_dc;
     bool done;       // the symbol completed its data unit
-    bool need;       // the window took the word in `ahead`; step_finish fetches the next one
+    bool need;       // the window moved on by a word; step_finish fetches the next one
     uint32_t z;      // zig-zag index the symbol started at
 };
 
@@ -125,47 +130,44 @@ template <class LutPtr>
 JPGD_HD Step step_and_request(Lane& l, BitWin& w, LutPtr lut) {
     Step s;
     const uint32_t e = l.e;
-    s.peek = (uint32_t)(w.bb >> 32);
+    s.peek = w.peek;
     s.len = lut_len(e);
     s.esc = s.len == 0u;
     s.size = s.esc ? 0u : lut_size(e);
     s.adv = s.esc ? 0u : lut_adv(e);
     s.is_dc = l.z == 0u;
     s.z = l.z;
-    const uint32_t total = s.len + s.size;
-    // window past the symbol; a word is taken from `ahead` when fewer than 33 bits remain
-    w.bb <<= total;
-    w.cnt -= (int32_t)total;
-    s.need = w.cnt <= 32;
-    const uint64_t more = (uint64_t)w.ahead << ((32 - w.cnt) & 63);
-    w.bb |= s.need ? more : 0ull;
-    w.cnt += s.need ? 32 : 0;
+    const uint32_t total = s.len + s.size;  // at most 32
+    // window past the symbol
+    const uint32_t o2 = w.o + total;
+    s.need = o2 >= 32u;
+    w.o = o2 & 31u;
+    w.hi = s.need ? w.lo : w.hi;
+    w.lo = s.need ? w.ahead : w.lo;
+    w.peek = win_peek(w);
     // (z, u) past the symbol
     const uint32_t zn = l.z + s.adv;
     s.done = zn >= 64u;
     l.z = s.done ? 0u : zn;
     // request: next symbol from the DC table of the next unit or the AC table of this one; an escape asks
     // the second level of the table it came from
-    const uint32_t peek2 = (uint32_t)(w.bb >> 32);
-    const uint32_t base2 = s.done ? l.tb_dc_next : l.tb_ac;
+    const uint32_t base2 = s.done ? l.row.tb_dc_next : l.row.tb_ac;
     const uint32_t nb2 = (e >> 5) & 7u;
     const uint32_t sub = (uint32_t)kLutL1 + ((e >> 8) << 1) + ((s.peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
-    const uint32_t idx = s.esc ? l.base + sub : base2 + (peek2 >> (32 - kLutK));
+    const uint32_t idx = s.esc ? l.base + sub : base2 + (w.peek >> (32 - kLutK));
     l.base = s.esc ? l.base : base2;
     l.e = lut[idx];
     l.p += total;
     return s;
 }
 
-// the part of the bookkeeping that is not needed to request the next entry
+// the part of the bookkeeping that is not needed to request the next entry; without branches: when the
+// unit did not change its row is read again, when no word was taken the word already held is
 template <class Fetch>
 JPGD_HD void step_finish(Lane& l, BitWin& w, const Step& s, const Syntax& sx, Fetch fetch) {
     l.nb += s.done ? 1u : 0u;
-    if (s.done) {
-        l.u4 = next_unit(l.u4, sx);
-        set_unit(l, sx);
-    }
-    // without a branch: when no word was taken this re-reads the word already held
+    l.u = s.done ? l.row.next : l.u;
+    l.row = sx.rows[l.u];
     w.next += s.need ? 1u : 0u;
     w.ahead = fetch(w.next);
 }
@@ -177,10 +179,10 @@ template <class Fetch, class LutPtr>
 JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
                               LutPtr lut) {
     while (l.p < limit) {
-        const uint32_t comp = l.comp;
+        const uint32_t dcmul = l.row.dcmul;
         const Step s = step_and_request(l, w, lut);
         const int32_t v = symbol_value(s.peek, s.len, s.size);
-        const int32_t mul = s.is_dc ? (int32_t)(1u << (15u * comp)) : 0;
+        const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
         dcacc += (int64_t)v * (int64_t)mul;
         step_finish(l, w, s, sx, fetch);
     }
@@ -194,17 +196,17 @@ JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& uni
                                int32_t& pred0, int32_t& pred1, int32_t& pred2, const Syntax& sx, Fetch fetch,
                                LutPtr lut, Store store, uint32_t& flags) {
     while (l.p < limit && unit < total_units) {
-        const uint32_t comp = l.comp;
+        const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
         const Step s = step_and_request(l, w, lut);
         const int32_t value = symbol_value(s.peek, s.len, s.size);
         if (!s.esc) {
             if (s.adv == 0u) flags |= kStInvalid;  // no codeword starts with these bits
             if (s.is_dc) {
-                int32_t pred = comp == 0u ? pred0 : (comp == 1u ? pred1 : pred2);
+                int32_t pred = comp0 ? pred0 : (comp1 ? pred1 : pred2);
                 pred += value;
-                pred0 = comp == 0u ? pred : pred0;
-                pred1 = comp == 1u ? pred : pred1;
-                pred2 = comp == 2u ? pred : pred2;
+                pred0 = comp0 ? pred : pred0;
+                pred1 = comp1 ? pred : pred1;
+                pred2 = comp0 || comp1 ? pred2 : pred;
                 if (s.adv) store(unit, 0u, (int16_t)pred);
             } else if (s.size) {
                 const uint32_t at = s.z + s.adv - 1u;  // after the run of zeros

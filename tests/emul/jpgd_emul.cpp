@@ -105,6 +105,7 @@ struct Emul {
     Image im;
     uint32_t logL, H, seq_len;
     std::vector<SInfo> sinfo;
+    UnitRow rows[8];
     Syntax sx;
     uint32_t inter_changed = 0, rounds_max = 0, flags = 0;
 };
@@ -137,13 +138,13 @@ void sync_intra(Emul& E) {
             active[t] = false;
             if (t < t0 || t >= t1) continue;
             uint32_t i = (uint32_t)(base + (int32_t)t);
-            l[t].p = i << logL; l[t].u4 = 0; l[t].z = 0; l[t].nb = 0;
+            l[t].p = i << logL; l[t].u = 0; l[t].z = 0; l[t].nb = 0;
             dcacc[t] = 0;
             win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);
             prime(l[t], bw[t], E.sx, im.lut.data());
             uint32_t limit = (i + 1) << logL;
             decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
-            sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
+            sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u);
             pnb[t] = l[t].nb;
             pdc01[t] = pack_dc01(dcacc[t]);
             pdc2[t] = pack_dc2(dcacc[t]);
@@ -164,7 +165,7 @@ void sync_intra(Emul& E) {
                 prime(l[t], bw[t], E.sx, im.lut.data());
                 uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
                 decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
-                uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u4 >> 2);
+                uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u);
                 bool synced = x == sw[tt[t]];
                 sw[tt[t]] = x; pnb[tt[t]] = l[t].nb;
                 pdc01[tt[t]] = pack_dc01(dcacc[t]);
@@ -194,7 +195,7 @@ void sync_inter(Emul& E) {
         uint32_t x0 = E.sinfo[g - 1].x;
         Lane l;
         BitWin w;
-        l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u4 = state_u(x0) * 4;
+        l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u = state_u(x0);
         win_init(w, l.p, l.p >> 5, fetch);
         prime(l, w, E.sx, im.lut.data());
         bool first = true;
@@ -203,7 +204,7 @@ void sync_inter(Emul& E) {
             int64_t dcacc = 0;
             uint32_t limit = (g + 1) << logL;
             decode_span_sync(l, w, limit, dcacc, E.sx, fetch, im.lut.data());
-            SInfo r = {pack_state(l.p - limit, l.z, l.u4 >> 2), l.nb, pack_dc01(dcacc), pack_dc2(dcacc)};
+            SInfo r = {pack_state(l.p - limit, l.z, l.u), l.nb, pack_dc01(dcacc), pack_dc2(dcacc)};
             bool synced = r.x == E.sinfo[g].x;
             if (first && !synced) E.inter_changed++;
             first = false;
@@ -218,7 +219,9 @@ void scan_and_write(Emul& E, int16_t* coef) {
     const Image& im = E.im;
     const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5;
     const uint32_t total = im.in.total_units;
-    memset(coef, 0, (size_t)total * 128);
+    // poison: every coefficient has to be cleared by the group whose range holds it
+    for (size_t k = 0; k < (size_t)total * 64; ++k) coef[k] = 0x5A5A;
+    std::vector<uint8_t> cleared((size_t)total * 64, 0);
     const uint32_t* words = (const uint32_t*)im.stream.data();
     uint32_t unit0 = 0;
     int32_t pred[3] = {0, 0, 0};
@@ -237,16 +240,31 @@ void scan_and_write(Emul& E, int16_t* coef) {
             if (k >= total || at > 63) abort();
             coef[(size_t)k * 64 + at] = v;
         };
+        {
+            uint32_t grp_units = 0;
+            for (uint32_t t = 0; t < nloc; ++t) grp_units += E.sinfo[i0 + t].y;
+            const uint64_t end_all = (uint64_t)total * 64;
+            const uint32_t x_in = i0 ? E.sinfo[i0 - 1].x : 0u, x_out = E.sinfo[i0 + nloc - 1].x;
+            uint64_t a = (uint64_t)unit0 * 64 + state_z(x_in);
+            uint64_t b = i0 + nloc >= nsub ? end_all : ((uint64_t)unit0 + grp_units) * 64 + state_z(x_out);
+            if (i0 == 0) a = 0;
+            if (b > end_all) b = end_all;
+            for (uint64_t k = a; k < b; ++k) {
+                if (cleared[k]) abort();  // ranges of different groups must not overlap
+                cleared[k] = 1;
+                coef[k] = 0;
+            }
+        }
         for (uint32_t t = 0; t < nloc; ++t) {
             const uint32_t i = i0 + t;
             const SInfo mine = E.sinfo[i];
             const uint32_t xprev = i ? E.sinfo[i - 1].x : 0u;
             Lane l;
             BitWin w;
-            l.p = (i << logL) + state_prel(xprev); l.z = state_z(xprev); l.u4 = state_u(xprev) * 4; l.nb = 0;
+            l.p = (i << logL) + state_prel(xprev); l.z = state_z(xprev); l.u = state_u(xprev); l.nb = 0;
             int32_t p0 = (int16_t)pred[0], p1 = (int16_t)pred[1], p2 = (int16_t)pred[2];
             uint32_t unit = unit0, flags = 0;
-            if (unit < total && (unit % im.in.units_per_mcu) * 4 != l.u4) flags |= kStUnit;
+            if (unit < total && unit % im.in.units_per_mcu != l.u) flags |= kStUnit;
             const uint32_t limit = (i + 1) << logL;
             if (unit < total) {
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
@@ -254,7 +272,7 @@ void scan_and_write(Emul& E, int16_t* coef) {
                 decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
             }
             if (unit < total) {
-                if (l.p < limit || pack_state(l.p - limit, l.z, l.u4 >> 2) != mine.x) flags |= kStMismatch;
+                if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;
                 if (i == nsub - 1) flags |= kStShort;
             }
             E.flags |= flags;
@@ -320,8 +338,10 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
     while ((1u << E.logL) < L) ++E.logL;
     E.H = H;
     E.seq_len = kWG - H;
-    E.sx.sched_dc = E.im.sched_dc; E.sx.sched_ac = E.im.sched_ac; E.sx.sched_comp = E.im.sched_comp;
-    E.sx.upm4 = E.im.in.units_per_mcu * 4;
+    for (uint32_t u = 0; u < E.im.in.units_per_mcu; ++u)
+        E.rows[u] = make_unit_row(u, E.im.in.units_per_mcu, E.im.sched_dc, E.im.sched_ac, E.im.sched_comp);
+    E.sx.rows = E.rows;
+    E.sx.upm = E.im.in.units_per_mcu;
     unstuff(file + E.im.in.scan_offset, (uint32_t)E.im.in.scan_bytes, E.logL, E.im);
     E.sinfo.assign(E.im.nsub, SInfo{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu});
     sync_intra(E);
