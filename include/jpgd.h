@@ -124,7 +124,8 @@ typedef struct {
  * JPGD_E_UNSUPPORTED: progressive / extended / lossless / arithmetic frames,
  * 12-bit, other component counts or sampling, DRI != 0, several scans.
  * JPGD_E_TABLE: table id > 3, more than 256 symbols, more codes of some
- * length than that length can hold, a table a component refers to missing.
+ * length than that length can hold, a DC table with a symbol above 15 (a DC
+ * symbol is a number of value bits), a table a component refers to missing.
  * JPGD_E_TRUNCATED / JPGD_E_MARKER: as named.
  */
 int jpgd_parse(const uint8_t* file /*[host]*/, size_t len, jpgd_info* out /*[host]*/);
@@ -158,12 +159,16 @@ size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, con
  *  stream                  a hipStream_t (as void*); NULL = the default stream
  *  report         [host]   may be NULL
  *
- * All work is enqueued on `stream`; the call returns after the stream has
- * drained, because the device's verdict (every lane of the write pass checks
- * that it ends in the state recorded for its subsequence) decides whether
- * further synchronisation rounds are needed and is the source of
- * JPGD_E_CORRUPT.  On JPGD_E_CORRUPT the outputs hold unspecified values but
- * nothing outside them has been written.
+ * All work is enqueued on `stream`.  The call returns once the device's
+ * verdict has arrived (every lane of the write pass checks that it ends in
+ * the state recorded for its subsequence): the verdict decides whether further
+ * synchronisation rounds are needed and is the source of JPGD_E_CORRUPT.  At
+ * that point d_coef is complete; the kernel that fills d_pixels may still be
+ * running, so d_pixels is complete in stream order like the output of any
+ * kernel: work enqueued on `stream` afterwards sees it, a host that reads it
+ * synchronises the stream first.  Calls are serialised inside the library.
+ * On JPGD_E_CORRUPT the outputs hold unspecified values but nothing outside
+ * them has been written.
  *
  * DC: the per-component prefix sum of Section 4.2 is computed hierarchically
  * -- per-subsequence sums of DC differences during synchronisation, their

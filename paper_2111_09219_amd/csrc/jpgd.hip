@@ -179,39 +179,99 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     return JPGD_OK;
 }
 
-// ---- pinned staging for the per-call upload ----------------------------------------------------------
+// ---- pinned host memory for the per-call parameters and the verdict ------------------------------------
+// Both are reached from the GPU directly: a small kernel copies the parameters into the workspace and another
+// one reports the verdict, so that nothing but kernels sits in the stream (a copy engine between two kernels,
+// or an event, costs several microseconds of an otherwise idle GPU each).  A call only returns after its verdict
+// has arrived, which is after its parameters were read: one staging buffer is enough, and it may be replaced
+// by a larger one at the start of a call.
 struct Staging {
     std::mutex mu;
-    uint8_t* buf[2] = {nullptr, nullptr};
-    size_t cap[2] = {0, 0};
-    hipEvent_t ev[2] = {nullptr, nullptr};
-    bool pending[2] = {false, false};
-    uint32_t* verdict = nullptr;  // pinned, 64 bytes
-    int turn = 0;
+    uint8_t* buf = nullptr;        // pinned
+    uint8_t* buf_dev = nullptr;    // the same bytes as the device addresses them
+    size_t cap = 0;
+    uint32_t* verdict = nullptr;   // pinned, 16 words: [0] flags, [1] inter_changed, [15] ticket of the report
+    uint32_t* verdict_dev = nullptr;
+    uint32_t ticket = 0;
     std::vector<hipEvent_t> timers;  // pairs of events for timing_mask
 };
 Staging g_stage;
 
-int stage_acquire(size_t bytes, int* slot) {
+int stage_acquire(size_t bytes) {
     Staging& s = g_stage;
-    int k = s.turn;
-    s.turn ^= 1;
-    if (s.pending[k]) {
-        if (hipEventSynchronize(s.ev[k]) != hipSuccess) return JPGD_E_HIP;
-        s.pending[k] = false;
-    }
-    if (!s.ev[k] && hipEventCreateWithFlags(&s.ev[k], hipEventDisableTiming) != hipSuccess) return JPGD_E_HIP;
-    if (s.cap[k] < bytes) {
-        if (s.buf[k]) (void)hipHostFree(s.buf[k]);
-        s.buf[k] = nullptr;
-        s.cap[k] = 0;
+    if (s.cap < bytes) {
+        if (s.buf) (void)hipHostFree(s.buf);
+        s.buf = s.buf_dev = nullptr;
+        s.cap = 0;
         size_t want = bytes + (bytes >> 2) + 4096;
-        if (hipHostMalloc((void**)&s.buf[k], want, hipHostMallocDefault) != hipSuccess) return JPGD_E_HIP;
-        s.cap[k] = want;
+        if (hipHostMalloc((void**)&s.buf, want, hipHostMallocMapped) != hipSuccess) return JPGD_E_HIP;
+        if (hipHostGetDevicePointer((void**)&s.buf_dev, s.buf, 0) != hipSuccess) return JPGD_E_HIP;
+        s.cap = want;
     }
-    if (!s.verdict && hipHostMalloc((void**)&s.verdict, 64, hipHostMallocDefault) != hipSuccess) return JPGD_E_HIP;
-    *slot = k;
+    if (!s.verdict) {
+        if (hipHostMalloc((void**)&s.verdict, 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return JPGD_E_HIP;
+        if (hipHostGetDevicePointer((void**)&s.verdict_dev, s.verdict, 0) != hipSuccess) return JPGD_E_HIP;
+        memset(s.verdict, 0, 64);
+    }
     return JPGD_OK;
+}
+
+__global__ __launch_bounds__(kWG) void k_upload(const uint4* __restrict__ src, uint4* __restrict__ dst, uint32_t n16) {
+    for (uint32_t k = blockIdx.x * kWG + threadIdx.x; k < n16; k += gridDim.x * kWG) dst[k] = src[k];
+}
+
+// one lane: status words to the host, then the ticket the host is waiting for
+__global__ void k_verdict(const Status* st, volatile uint32_t* host, uint32_t ticket) {
+    if (threadIdx.x == 0) {
+        host[0] = st->flags;
+        host[1] = st->inter_changed;
+        __threadfence_system();
+        host[15] = ticket;
+    }
+}
+
+// Lookup tables built recently, keyed by the DHT lists they came from: most files share a handful of
+// tables (the typical ones of the standard above all), and building one costs a few microseconds of a
+// call that may take a hundred.  Callers hold g_stage.mu.
+struct LutCacheEntry {
+    bool is_dc;
+    uint8_t bits[16];
+    uint8_t vals[256];
+    uint32_t nvals;
+    uint64_t stamp;
+    uint16_t lut[kLutEntries];
+};
+std::vector<LutCacheEntry> g_lut_cache;
+uint64_t g_lut_clock = 0;
+constexpr size_t kLutCacheMax = 32;
+
+bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_t* out) {
+    uint32_t nvals = 0;
+    for (int k = 0; k < 16; ++k) nvals += bits[k];
+    if (nvals > 256u) return false;
+    for (LutCacheEntry& e : g_lut_cache)
+        if (e.is_dc == is_dc && e.nvals == nvals && !memcmp(e.bits, bits, 16) && !memcmp(e.vals, vals, nvals)) {
+            e.stamp = ++g_lut_clock;
+            memcpy(out, e.lut, sizeof e.lut);
+            return true;
+        }
+    if (!build_lut(bits, vals, is_dc, out)) return false;
+    LutCacheEntry* victim;
+    if (g_lut_cache.size() < kLutCacheMax) {
+        g_lut_cache.emplace_back();
+        victim = &g_lut_cache.back();
+    } else {
+        victim = &g_lut_cache[0];
+        for (LutCacheEntry& e : g_lut_cache)
+            if (e.stamp < victim->stamp) victim = &e;  // least recently used
+    }
+    victim->is_dc = is_dc;
+    memcpy(victim->bits, bits, 16);
+    memcpy(victim->vals, vals, nvals);
+    victim->nvals = nvals;
+    victim->stamp = ++g_lut_clock;
+    memcpy(victim->lut, out, sizeof victim->lut);
+    return true;
 }
 
 int hip_failed(const char* what, hipError_t e) {
@@ -223,6 +283,26 @@ int hip_failed(const char* what, hipError_t e) {
         hipError_t e_ = (expr);                                     \
         if (e_ != hipSuccess) return hip_failed(#expr, e_);         \
     } while (0)
+
+// Spins until k_verdict has reported under `ticket`.  The stream is asked now and then, so that a failed
+// launch or a lost report ends the wait with an error instead of hanging.
+int wait_verdict(hipStream_t stream, uint32_t ticket) {
+    volatile uint32_t* v = g_stage.verdict;
+    for (uint32_t spins = 1;; ++spins) {
+        if (v[15] == ticket) break;
+        if ((spins & 0x3FFFu) == 0u) {
+            hipError_t q = hipStreamQuery(stream);
+            if (q == hipSuccess) {
+                if (v[15] == ticket) break;
+                fprintf(stderr, "jpgd: the stream is idle but the verdict has not arrived\n");
+                return JPGD_E_HIP;
+            }
+            if (q != hipErrorNotReady) return hip_failed("hipStreamQuery", q);
+        }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return JPGD_OK;
+}
 
 // subsequences of up to this many bits are staged in LDS by the sync and write kernels
 // (JPGD_STAGED_MAX_BITS overrides it for tuning runs)
@@ -292,10 +372,9 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         (rc = grant_lds(staged ? 1 : 4, staged ? (const void*)k_write<true> : (const void*)k_write<false>, lds_write)) ||
         (rc = grant_lds(2, (const void*)k_sync_inter, lds_inter)))
         return rc;
-    int slot;
-    rc = stage_acquire(pl.h.upload_bytes, &slot);
+    rc = stage_acquire(pl.h.upload_bytes + 16);
     if (rc) return rc;
-    uint8_t* up = g_stage.buf[slot];
+    uint8_t* up = g_stage.buf;
     memset(up, 0, pl.h.upload_bytes);
     memcpy(up, &pl.h, sizeof pl.h);
     memcpy(up + pl.h.off_img, pl.img.data(), sizeof(ImgDesc) * (size_t)n);
@@ -306,21 +385,30 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         const ImgDesc& d = pl.img[i];
         if (i == 0 || pl.lut_of_img[i] != pl.lut_of_img[i - 1]) {
             uint16_t* set = luts + d.lut_off;
+            uint32_t built = 0u;  // slots of this set already filled
             for (uint32_t u = 0; u < d.upm; ++u) {
                 uint32_t c = (d.sched_comp >> (4 * u)) & 15u;
                 uint32_t sd = (d.sched_dc >> (4 * u)) & 15u, sa = (d.sched_ac >> (4 * u)) & 15u;
-                if (!build_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, set + sd * kLutEntries) ||
-                    !build_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, set + sa * kLutEntries))
+                if (!(built & (1u << sd)) &&
+                    !cached_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, set + sd * kLutEntries))
                     return JPGD_E_TABLE;
+                built |= 1u << sd;
+                if (!(built & (1u << sa)) &&
+                    !cached_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, set + sa * kLutEntries))
+                    return JPGD_E_TABLE;
+                built |= 1u << sa;
             }
         }
         for (uint32_t c = 0; c < in.ncomp; ++c)
             for (int k = 0; k < 64; ++k) qts[d.qt_off + c * 64 + k] = in.qt[in.tq[c]][k];
     }
     uint8_t* ws = (uint8_t*)d_workspace;
-    HIP_OK(hipMemcpyAsync(ws, up, pl.h.upload_bytes, hipMemcpyHostToDevice, stream));
-    HIP_OK(hipEventRecord(g_stage.ev[slot], stream));
-    g_stage.pending[slot] = true;
+    {
+        const uint32_t n16 = (uint32_t)((pl.h.upload_bytes + 15u) / 16u);
+        const uint32_t wgs = (n16 + kWG - 1u) / kWG;
+        hipLaunchKernelGGL(k_upload, dim3(wgs < 256u ? wgs : 256u), dim3(kWG), 0, stream, (const uint4*)g_stage.buf_dev,
+                           (uint4*)ws, n16);
+    }
 
     Params P;
     P.img = (const ImgDesc*)(ws + pl.h.off_img);
@@ -392,13 +480,15 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         if (big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
         if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
         else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
-        HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + pl.h.off_status, sizeof(Status), hipMemcpyDeviceToHost, stream));
+        const uint32_t ticket = ++g_stage.ticket;
+        hipLaunchKernelGGL(k_verdict, dim3(1), dim3(64), 0, stream, (const Status*)(ws + pl.h.off_status),
+                           (volatile uint32_t*)g_stage.verdict_dev, ticket);
         // The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the
-        // verdict is bad its output is either redone below or reported as unspecified.  This keeps one host
-        // round trip out of the critical path.
+        // verdict is bad its output is either redone below or reported as unspecified.  The host waits for
+        // the verdict alone; the pixels are complete in stream order, like the output of any kernel.
         if (want_pixels) LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
         HIP_OK(hipGetLastError());
-        HIP_OK(hipStreamSynchronize(stream));
+        if ((rc = wait_verdict(stream, ticket)) != JPGD_OK) return rc;
         flags = g_stage.verdict[0];
         const bool chain_broken = (flags & (kStMismatch | kStUnit)) != 0;
         // A broken chain with more than one sequence may only mean that synchronisation needs another
@@ -419,6 +509,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         for (int k = 0; k < JPGD_N_KERNELS; ++k) report->launches[k] = launches[k];
         for (const Timed& t : timed) {
             float ms = 0.f;
+            (void)hipEventSynchronize(g_stage.timers[t.ev + 1]);  // the pixel kernel may still be running
             if (hipEventElapsedTime(&ms, g_stage.timers[t.ev], g_stage.timers[t.ev + 1]) == hipSuccess)
                 report->kernel_ms[t.kernel] += ms;
         }
@@ -479,10 +570,9 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     if (workspace_bytes < need) return JPGD_E_WORKSPACE;
     hipStream_t stream = (hipStream_t)stream_v;
     std::lock_guard<std::mutex> lock(g_stage.mu);
-    int slot;
-    int rc = stage_acquire(off_tiles, &slot);
+    int rc = stage_acquire(off_tiles);
     if (rc) return rc;
-    uint8_t* up = g_stage.buf[slot];
+    uint8_t* up = g_stage.buf;
     memset(up, 0, off_tiles);
     ImgDesc d;
     memset(&d, 0, sizeof d);
@@ -491,8 +581,6 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     memcpy(up + off_img, &d, sizeof d);
     uint8_t* ws = (uint8_t*)d_workspace;
     HIP_OK(hipMemcpyAsync(ws, up, off_tiles, hipMemcpyHostToDevice, stream));
-    HIP_OK(hipEventRecord(g_stage.ev[slot], stream));
-    g_stage.pending[slot] = true;
     Params P;
     memset(&P, 0, sizeof P);
     P.img = (const ImgDesc*)(ws + off_img);

@@ -19,13 +19,14 @@ constexpr int kMaxOverlap = 191;  // warm-up lanes a sequence may borrow from it
 // ---- Huffman lookup tables ---------------------------------------------------------------------
 // One table = kLutL1 first-level entries indexed by the next kLutK bits, followed by up to kLutL2
 // second-level entries for codewords longer than kLutK bits.  uint16 entries:
-//   bits 0..4   codeword length, 1..16; 0 marks a first-level escape (see below)
-//   bits 5..9   number of value bits that follow the codeword, 0..16
-//   bits 10..15 zig-zag slots the symbol covers: run+1 for a coefficient, 1 for a DC symbol, 16 for
+//   bits 0..4   bits the symbol takes: codeword (1..16) plus value bits, at most 31
+//   bits 5..8   number of value bits that follow the codeword, 0..15
+//   bits 9..14  zig-zag slots the symbol covers: run+1 for a coefficient, 1 for a DC symbol, 16 for
 //               ZRL, 63 for end-of-block (any z >= 1 plus 63 reaches 64 = unit complete), and 0 for
-//               "no codeword starts with these bits" (length 1: skip one bit, state unchanged)
-//   escape (first level only): bits 5..7 = number of further bits that index the second level,
-//               bits 8..15 = half the offset of the subtable inside the second level
+//               "no codeword starts with these bits" (one bit taken: skip it, state unchanged)
+//   bit 15      0
+//   first-level escape: bit 15 = 1, bits 0..2 = number of further bits that index the second level,
+//               bits 3..10 = half the offset of the subtable inside the second level
 // Bound on the second level: codes of one length are consecutive, so those of length l > kLutK touch
 // at most n_l / 2^(l-kLutK) + 2 first-level prefixes; summed over l = 11..16 with at most 256 symbols
 // this is below 510 entries; two more hold the shared "no codeword" record.
@@ -36,9 +37,12 @@ constexpr int kLutEntries = kLutL1 + kLutL2;
 constexpr int kMaxSlots = 6;  // up to 3 DC and 3 AC tables per image (one pair per component)
 constexpr uint32_t kAdvEob = 63u;
 
-JPGD_HD uint32_t lut_len(uint32_t e) { return e & 31u; }
-JPGD_HD uint32_t lut_size(uint32_t e) { return (e >> 5) & 31u; }
-JPGD_HD uint32_t lut_adv(uint32_t e) { return e >> 10; }
+JPGD_HD bool lut_esc(uint32_t e) { return e >= 0x8000u; }
+JPGD_HD uint32_t lut_total(uint32_t e) { return e & 31u; }
+JPGD_HD uint32_t lut_size(uint32_t e) { return (e >> 5) & 15u; }
+JPGD_HD uint32_t lut_adv(uint32_t e) { return (e >> 9) & 63u; }
+JPGD_HD uint32_t lut_esc_bits(uint32_t e) { return e & 7u; }
+JPGD_HD uint32_t lut_esc_offset(uint32_t e) { return ((e >> 3) & 255u) << 1; }
 
 // ---- s_info (paper, Section 4.1): one 16-byte record per subsequence --------------------------
 //  x : decoder state after the last symbol that starts inside the subsequence

@@ -43,7 +43,7 @@ struct Lane {
     uint32_t u;    // data unit inside the MCU
     uint32_t z;    // zig-zag index of the next coefficient (0 = a DC symbol is next)
     uint32_t nb;   // data units completed since the counter was last cleared
-    UnitRow row;   // row of unit u (prime, step_finish)
+    UnitRow row;   // row of unit u (prime, step_and_request)
     // pipeline registers (prime)
     uint32_t e;    // table entry already read for the symbol at p (possibly a first-level escape)
     uint32_t base; // table that entry came from
@@ -89,15 +89,13 @@ JPGD_HD void prime(Lane& l, const BitWin& w, const Syntax& sx, LutPtr lut) {
     l.e = lut[l.base + (w.peek >> (32 - kLutK))];
 }
 
-// value bits follow the codeword; "signed ones' complement" (paper, Section 2): a leading 1 means the
-// bits are the value itself, a leading 0 means value = bits - (2^size - 1), i.e. minus the complemented
-// bits; size 0 gives 0
-JPGD_HD int32_t symbol_value(uint32_t peek, uint32_t len, uint32_t size) {
-    uint32_t t = peek << len;
-    uint32_t m = (uint32_t)((int32_t)(~t) >> 31);   // all ones for a negative value
-    // (t ^ m) >> (32 - size) without a special case for size 0: two shifts, the first by at least one
-    uint32_t r = ((t ^ m) >> 1) >> (31u - size);
-    return (int32_t)((r ^ m) - m);
+// The value bits are the last `size` of the `total` bits a symbol takes; "signed ones' complement" (paper,
+// Section 2): a leading 1 means the bits are the value itself, a leading 0 means value = bits - (2^size - 1);
+// size 0 gives 0.  peek holds the symbol from its most significant bit on.
+JPGD_HD int32_t symbol_value(uint32_t peek, uint32_t total, uint32_t size) {
+    const uint32_t mask = (1u << size) - 1u;
+    const uint32_t raw = (peek >> ((32u - total) & 31u)) & mask;
+    return (int32_t)(raw - ((raw << 1) <= mask ? mask : 0u));
 }
 
 // DC-difference sums of the three components, kept in one 64-bit accumulator with 15-bit fields
@@ -118,58 +116,58 @@ JPGD_HD void dc_unpack(int64_t acc, int32_t& d0, int32_t& d1, int32_t& d2) {
 // that request.
 struct Step {
     uint32_t peek;   // window as the symbol saw it
-    uint32_t len, size, adv;
+    uint32_t total, size, adv;  // bits taken, value bits among them, zig-zag slots covered
     bool esc;        // first-level escape: nothing was consumed, the state did not change
     bool is_dc;
     bool done;       // the symbol completed its data unit
-    bool need;       // the window moved on by a word; step_finish fetches the next one
+    bool need;       // the window moved on by a word
     uint32_t z;      // zig-zag index the symbol started at
 };
 
-template <class LutPtr>
-JPGD_HD Step step_and_request(Lane& l, BitWin& w, LutPtr lut) {
+// LDS answers in the order it was asked, and the compiler waits for everything outstanding at once.  So the
+// two reads that are off the chain (the next stream word, the row of the unit now current) are issued first
+// and the table entry last: when the entry has arrived, so have they, and nothing waits for them.
+template <class Fetch, class LutPtr>
+JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch, LutPtr lut) {
     Step s;
     const uint32_t e = l.e;
     s.peek = w.peek;
-    s.len = lut_len(e);
-    s.esc = s.len == 0u;
-    s.size = s.esc ? 0u : lut_size(e);
-    s.adv = s.esc ? 0u : lut_adv(e);
+    s.esc = lut_esc(e);
+    const uint32_t ee = s.esc ? 0u : e;
+    s.total = lut_total(ee);  // at most 31
+    s.size = lut_size(ee);
+    s.adv = lut_adv(ee);
     s.is_dc = l.z == 0u;
     s.z = l.z;
-    const uint32_t total = s.len + s.size;  // at most 32
-    // window past the symbol
-    const uint32_t o2 = w.o + total;
+    const uint32_t o2 = w.o + s.total;
     s.need = o2 >= 32u;
+    const uint32_t zn = l.z + s.adv;
+    s.done = zn >= 64u;
+    // off the chain, without branches: when no word is taken the word already held is read again, when the
+    // unit does not change its row is
+    w.next += s.need ? 1u : 0u;
+    const uint32_t ahead = fetch(w.next);
+    const UnitRow old = l.row;
+    l.u = s.done ? old.next : l.u;
+    l.row = sx.rows[l.u];
+    l.nb += s.done ? 1u : 0u;
+    // window past the symbol
     w.o = o2 & 31u;
     w.hi = s.need ? w.lo : w.hi;
     w.lo = s.need ? w.ahead : w.lo;
+    w.ahead = ahead;
     w.peek = win_peek(w);
-    // (z, u) past the symbol
-    const uint32_t zn = l.z + s.adv;
-    s.done = zn >= 64u;
     l.z = s.done ? 0u : zn;
     // request: next symbol from the DC table of the next unit or the AC table of this one; an escape asks
     // the second level of the table it came from
-    const uint32_t base2 = s.done ? l.row.tb_dc_next : l.row.tb_ac;
-    const uint32_t nb2 = (e >> 5) & 7u;
-    const uint32_t sub = (uint32_t)kLutL1 + ((e >> 8) << 1) + ((s.peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
+    const uint32_t base2 = s.done ? old.tb_dc_next : old.tb_ac;
+    const uint32_t nb2 = lut_esc_bits(e);
+    const uint32_t sub = (uint32_t)kLutL1 + lut_esc_offset(e) + ((s.peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
     const uint32_t idx = s.esc ? l.base + sub : base2 + (w.peek >> (32 - kLutK));
     l.base = s.esc ? l.base : base2;
     l.e = lut[idx];
-    l.p += total;
+    l.p += s.total;
     return s;
-}
-
-// the part of the bookkeeping that is not needed to request the next entry; without branches: when the
-// unit did not change its row is read again, when no word was taken the word already held is
-template <class Fetch>
-JPGD_HD void step_finish(Lane& l, BitWin& w, const Step& s, const Syntax& sx, Fetch fetch) {
-    l.nb += s.done ? 1u : 0u;
-    l.u = s.done ? l.row.next : l.u;
-    l.row = sx.rows[l.u];
-    w.next += s.need ? 1u : 0u;
-    w.ahead = fetch(w.next);
 }
 
 // Synchronisation pass (write = false in Algorithm 2): decode while the next symbol starts before
@@ -180,11 +178,10 @@ JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc
                               LutPtr lut) {
     while (l.p < limit) {
         const uint32_t dcmul = l.row.dcmul;
-        const Step s = step_and_request(l, w, lut);
-        const int32_t v = symbol_value(s.peek, s.len, s.size);
+        const Step s = step_and_request(l, w, sx, fetch, lut);
+        const int32_t v = symbol_value(s.peek, s.total, s.size);
         const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
         dcacc += (int64_t)v * (int64_t)mul;
-        step_finish(l, w, s, sx, fetch);
     }
 }
 
@@ -197,8 +194,8 @@ JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& uni
                                LutPtr lut, Store store, uint32_t& flags) {
     while (l.p < limit && unit < total_units) {
         const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
-        const Step s = step_and_request(l, w, lut);
-        const int32_t value = symbol_value(s.peek, s.len, s.size);
+        const Step s = step_and_request(l, w, sx, fetch, lut);
+        const int32_t value = symbol_value(s.peek, s.total, s.size);
         if (!s.esc) {
             if (s.adv == 0u) flags |= kStInvalid;  // no codeword starts with these bits
             if (s.is_dc) {
@@ -217,7 +214,6 @@ JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& uni
             }
         }
         if (s.done) unit++;
-        step_finish(l, w, s, sx, fetch);
     }
 }
 

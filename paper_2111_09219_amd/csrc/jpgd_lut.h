@@ -23,18 +23,21 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
         code <<= 1;
     }
     if (k > 256) return false;
+    if (is_dc)
+        for (uint32_t i = 0; i < k; ++i)
+            if (vals[i] > 15) return false;  // a DC symbol is a number of value bits; 8-bit samples need at most 11
 
     auto entry_for = [&](uint32_t sym, int len) -> uint16_t {
         uint32_t size, adv;
         if (is_dc) {
-            size = sym > 16 ? 16 : sym;
+            size = sym;  // at most 15, checked below
             adv = 1;
         } else {
             uint32_t run = sym >> 4;
             size = sym & 15;
             adv = size ? run + 1 : (run == 15 ? 16u : kAdvEob);
         }
-        return (uint16_t)((uint32_t)len | (size << 5) | (adv << 10));
+        return (uint16_t)(((uint32_t)len + size) | (size << 5) | (adv << 9));
     };
 
     const uint16_t kUnset = 0xFFFF;
@@ -53,7 +56,7 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
                 if (maxlen[prefix] < len) maxlen[prefix] = (uint8_t)len;
             }
         }
-    // second level: entries 0 and 1 are the shared "no codeword" record (length 1, nothing else), then one
+    // second level: entries 0 and 1 are the shared "no codeword" record (one bit, nothing else), then one
     // subtable per escaping prefix; subtables hold 2, 4, .. 64 entries, so every offset is even
     uint16_t* l2 = out + kLutL1;
     const uint16_t invalid = 1u;
@@ -66,10 +69,10 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
             uint32_t nb2 = maxlen[p] - kLutK, n = 1u << nb2;
             if (used + n > (uint32_t)kLutL2) return false;
             suboff[p] = used;
-            out[p] = (uint16_t)((nb2 << 5) | ((used >> 1) << 8));
+            out[p] = (uint16_t)(0x8000u | nb2 | ((used >> 1) << 3));
             used += n;
         } else if (out[p] == kUnset) {
-            out[p] = 0u;  // escape with zero further bits and offset 0: the invalid record
+            out[p] = 0x8000u;  // escape with zero further bits and offset 0: the invalid record
         }
     }
     for (int len = kLutK + 1; len <= 16; ++len)

@@ -106,6 +106,9 @@ def test_parse_rejections():
     # a DHT whose lengths cannot form a prefix code: three codes of length 1
     _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q}, [(0, 0, [3] + [0] * 15, [0, 1, 2]), (1, 0, *ac)],
                         b"\x00"), "TABLE")
+    # a DC table with a symbol that cannot be a number of value bits
+    _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q},
+                        [(0, 0, [0, 2] + [0] * 14, [3, 16]), (1, 0, *ac)], b"\x00"), "TABLE")
     # scan refers to an AC table that was never defined
     _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 1)], {0: q}, [(0, 0, *std_dc), (1, 0, *ac)], b"\x00"), "TABLE")
     # 4 components, and chroma sampled 2x2
@@ -206,11 +209,13 @@ def test_lookup_tables_decode_every_codeword(emul, optimize):
 
                 def look(peek16):
                     e = int(lut[peek16 >> (16 - K)])
-                    if e & 31 == 0:                         # escape to the second level
-                        nb2, off = (e >> 5) & 7, (e >> 8) << 1
+                    if e & 0x8000:                          # escape to the second level
+                        nb2, off = e & 7, ((e >> 3) & 255) << 1
                         j = (peek16 >> (16 - K - nb2)) & ((1 << nb2) - 1)
                         e = int(lut[L1 + off + j])
-                    ln, size, adv = e & 31, (e >> 5) & 31, e >> 10
+                        assert not e & 0x8000
+                    total, size, adv = e & 31, (e >> 5) & 15, (e >> 9) & 63
+                    ln = total - size
                     if adv == 0:
                         assert (ln, size) == (1, 0)         # "no codeword": skip one bit
                         return None
@@ -220,7 +225,7 @@ def test_lookup_tables_decode_every_codeword(emul, optimize):
                     ln = int(length[s])
                     lo = int(code[s]) << (16 - ln)
                     covered[lo:lo + (1 << (16 - ln))] = True
-                    want_size = min(int(s), 16) if cls == 0 else int(s) & 15
+                    want_size = int(s) if cls == 0 else int(s) & 15
                     run = int(s) >> 4
                     # slots covered: DC 1; coefficient run+1; ZRL 16; end of block 63 (completes any unit from z >= 1)
                     want_adv = 1 if cls == 0 else (run + 1 if want_size else (16 if run == 15 else 63))
