@@ -27,11 +27,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # counters read for a plain copy of known size; taken from the summaries in profiles/ (same commands).
 MEASURED_TRAFFIC = {
     ("hd1088_444_q90", "sync_intra"): 1.71e6,
-    ("hd1088_444_q90", "write"): 8.09e6,
-    ("hd1088_444_q90", "pixels"): 18.91e6,
+    ("hd1088_444_q90", "write"): 14.60e6,
+    ("hd1088_444_q90", "pixels"): 18.90e6,
     ("uhd16k_420_q92_flat_random", "sync_intra"): 84.64e6,
-    ("uhd16k_420_q92_flat_random", "write"): 1543.65e6,
-    ("uhd16k_420_q92_flat_random", "pixels"): 796.34e6,
+    ("uhd16k_420_q92_flat_random", "write"): 1669.9e6,
+    ("uhd16k_420_q92_flat_random", "pixels"): 796.3e6,
 }
 
 
