@@ -537,7 +537,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
     int16_t* coef = P.coef + D.coef_off;
-    auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)k * 64u + at] = v; };
+    auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)(k * 64u + at)] = v; };
     Lane l;
     BitWin w;
     l.p = (i << P.logL) + state_prel(xprev);

@@ -192,28 +192,28 @@ template <class Fetch, class LutPtr, class Store>
 JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& unit, uint32_t total_units,
                                int32_t& pred0, int32_t& pred1, int32_t& pred2, const Syntax& sx, Fetch fetch,
                                LutPtr lut, Store store, uint32_t& flags) {
+    // Without branches except around the store itself: a wavefront holds lanes in every kind of symbol at
+    // once, so each arm of a branch would be walked anyway.
     while (l.p < limit && unit < total_units) {
         const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
         const Step s = step_and_request(l, w, sx, fetch, lut);
-        const int32_t value = symbol_value(s.peek, s.total, s.size);
-        if (!s.esc) {
-            if (s.adv == 0u) flags |= kStInvalid;  // no codeword starts with these bits
-            if (s.is_dc) {
-                int32_t pred = comp0 ? pred0 : (comp1 ? pred1 : pred2);
-                pred += value;
-                pred0 = comp0 ? pred : pred0;
-                pred1 = comp1 ? pred : pred1;
-                pred2 = comp0 || comp1 ? pred2 : pred;
-                if (s.adv) store(unit, 0u, (int16_t)pred);
-            } else if (s.size) {
-                const uint32_t at = s.z + s.adv - 1u;  // after the run of zeros
-                if (at < 64u) store(unit, at, (int16_t)value);
-                else flags |= kStInvalid;
-            } else if (s.adv == 16u && s.z + 16u > 64u) {
-                flags |= kStInvalid;  // ZRL running past the end of the unit
-            }
-        }
-        if (s.done) unit++;
+        const int32_t value = symbol_value(s.peek, s.total, s.size);  // 0 for an escape
+        const bool real = !s.esc;
+        const bool dc = s.is_dc && real;
+        const int32_t pred = (comp0 ? pred0 : (comp1 ? pred1 : pred2)) + value;
+        pred0 = dc && comp0 ? pred : pred0;
+        pred1 = dc && comp1 ? pred : pred1;
+        pred2 = dc && !comp0 && !comp1 ? pred : pred2;
+        // where the symbol ends: a coefficient sits in the last slot it covers (after its run of zeros)
+        const uint32_t zn = s.z + s.adv;
+        const uint32_t at = dc ? 0u : zn - 1u;
+        const bool has_value = dc || s.size != 0u;  // a DC symbol of size 0 still yields the predictor
+        if (real && s.adv != 0u && has_value && at < 64u) store(unit, at, (int16_t)(dc ? pred : value));
+        // no codeword starts with these bits; or a coefficient or a run of sixteen zeros (not end-of-block,
+        // which may be coded anywhere) that runs past the end of the unit
+        const bool bad = real && (s.adv == 0u || (zn > 64u && s.adv != kAdvEob));
+        flags |= bad ? kStInvalid : 0u;
+        unit += s.done ? 1u : 0u;
     }
 }
 

@@ -133,6 +133,41 @@ def test_batch_of_different_images():
             _check_image(batch, i, f)
 
 
+def test_tables_change_between_calls():
+    """Lookup tables are cached inside the library by the DHT lists they were built from: files with
+    different tables decoded in turn, and again, must each get their own."""
+    px = small_image(11, 120, 168, sigma=18)
+    files = [encode_jpeg(px, 85, "420", False).data,      # typical tables of the standard
+             encode_jpeg(px, 85, "420", True).data,       # tables optimised for this image
+             encode_jpeg(small_image(12, 120, 168, sigma=40), 97, "444", True).data,
+             encode_jpeg(px[:, :, 0].copy(), 60, "gray", True).data]
+    batches = [J.prepare_batch([f]) for f in files]
+    for rounds in range(2):
+        for b, f in zip(batches, files):
+            b.decode()
+            _check_image(b, 0, f)
+
+
+def test_output_buffers_need_not_be_cleared():
+    """The write pass clears the coefficients itself, group by group: stale values of an earlier, different image
+    in the same buffers must not survive (flat image after a busy one, so most slots have to become zero)."""
+    busy = encode_jpeg(small_image(21, 256, 384, sigma=60), 98, "444").data
+    flat = encode_jpeg(np.full((256, 384, 3), 117, np.uint8), 98, "444").data
+    sparse = encode_jpeg(small_image(22, 256, 384, sigma=0.0, shapes=3), 50, "444").data
+    for L in (128, 1024):
+        b = J.prepare_batch([busy], J.Config.make(subseq_bits=L))
+        b.decode()
+        _check_image(b, 0, busy)
+        for other in (flat, sparse):
+            info = J.jpgd_parse(other)
+            assert info.total_units == b.infos[0].total_units
+            b2 = J.prepare_batch([other], J.Config.make(subseq_bits=L))
+            b2.d_coef.copy_(b.d_coef)                     # start from the busy image's coefficients
+            b2.d_pixels.fill_(0x5A)
+            b2.decode()
+            _check_image(b2, 0, other)
+
+
 def test_config4_batch_slice():
     files = [e.data for e in config_jpeg(4, limit=24)]
     batch, rep = _decode(files)
