@@ -429,6 +429,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.overlap = pl.h.overlap;
     P.seq_len = kWG - pl.h.overlap;
     P.lut_slots = pl.lut_slots;
+    P.img0 = pl.img[0];
 
     // optional bracketing of single kernels with events (jpgd_config.timing_mask)
     const uint32_t tmask = cfg ? cfg->timing_mask : 0u;
@@ -589,6 +590,7 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     P.stream = d_out;
     P.tile_cnt = (uint32_t*)(ws + off_tiles);
     P.nimg = 1;
+    P.img0 = d;
     P.logL = 10;
     hipLaunchKernelGGL(k_unstuff_count, dim3(tiles), dim3(kWG), 0, stream, P);
     if (tiles > (uint32_t)kWG) hipLaunchKernelGGL(k_unstuff_scan, dim3(1), dim3(kWG), 0, stream, P);

@@ -31,7 +31,16 @@ struct Params {
     uint32_t overlap;       // H: warm-up lanes in front of each sequence
     uint32_t seq_len;       // kWG - H: subsequences a sequence owns
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
+    // A call with one image carries its descriptor in the kernel arguments: every workgroup of every kernel
+    // starts by reading the descriptor, and when all of them ask memory for the same freshly written line
+    // that read alone was measured at 1 to 11 microseconds per kernel.
+    ImgDesc img0;
 };
+
+__device__ __forceinline__ ImgDesc image_desc(const Params& P, uint32_t ii) {
+    if (P.nimg == 1u) return P.img0;
+    return P.img[ii];
+}
 
 // ---- small helpers ------------------------------------------------------------------------------
 
@@ -120,16 +129,16 @@ struct UnstuffLane {
     uint32_t nvalid;    // bytes of this lane that exist
 };
 
+// pos is a multiple of 16.  A lane that holds any byte loads its whole 16-byte word (the input is readable up
+// to the next multiple of 16); bytes past the end are masked out.  No private array is indexed with a variable:
+// the compiler would move such an array to LDS and read the dispatch packet for the workgroup's shape, and that
+// packet lives in host memory -- measured at 2 to 11 microseconds per wavefront when a whole grid asks at once.
 __device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_t n, uint32_t pos) {
     UnstuffLane r;
     r.nvalid = pos >= n ? 0u : (n - pos < 16u ? n - pos : 16u);
-    if (r.nvalid == 16u) {
-        uint4 v = *reinterpret_cast<const uint4*>(scan + pos);
-        r.bytes[0] = v.x; r.bytes[1] = v.y; r.bytes[2] = v.z; r.bytes[3] = v.w;
-    } else {
-        r.bytes[0] = r.bytes[1] = r.bytes[2] = r.bytes[3] = 0u;
-        for (uint32_t j = 0; j < r.nvalid; ++j) r.bytes[j >> 2] |= (uint32_t)scan[pos + j] << (8u * (j & 3u));
-    }
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r.nvalid) v = *reinterpret_cast<const uint4*>(scan + pos);
+    r.bytes[0] = v.x; r.bytes[1] = v.y; r.bytes[2] = v.z; r.bytes[3] = v.w;
     uint32_t prev = (pos > 0u && r.nvalid) ? scan[pos - 1u] : 0u;
     uint32_t mask = 0u;
 #pragma unroll
@@ -147,7 +156,7 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t lt = wg - D.tile0;
     const uint8_t* scan = P.scans + D.scan_off;
     const uint32_t pos = lt * (uint32_t)kUnstuffTile + threadIdx.x * 16u;
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
 __global__ __launch_bounds__(kWG) void k_unstuff_scan(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t ii = blockIdx.x;
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     if (D.ntiles <= (uint32_t)kWG) return;  // images of up to 256 tiles: the scatter kernel sums the counts itself
     uint32_t carry = 0u;
     for (uint32_t base = 0; base < D.ntiles; base += kWG) {
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     __shared__ __attribute__((aligned(16))) uint8_t buf[kUnstuffTile + 16];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t lt = wg - D.tile0;
     const uint8_t* scan = P.scans + D.scan_off;
     uint8_t* out = P.stream + D.stream_off;
@@ -253,7 +262,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t nsub = P.st[ii].nsub;
     const int32_t base = (int32_t)((wg - D.seq0) * P.seq_len) - (int32_t)P.overlap;
     if (base >= (int32_t)nsub || (int32_t)((wg - D.seq0) * P.seq_len) >= (int32_t)nsub) return;  // nothing owned
@@ -362,7 +371,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.bnd0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t nsub = P.st[ii].nsub;
     uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
     __shared__ UnitRow rows[8];
@@ -415,7 +424,7 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t nsub = P.st[ii].nsub;
     const uint32_t i = (wg - D.grp0) * kWG + threadIdx.x;
     SInfo r = {0u, 0u, 0u, 0u};
@@ -432,7 +441,7 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
 __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t ii = blockIdx.x;
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     if (D.ngrp_max <= (uint32_t)kWG) return;  // images of up to 256 groups: the write kernel sums the totals itself
     const uint32_t ngrp = (P.st[ii].nsub + kWG - 1u) / kWG;
     uint32_t carry[4] = {0u, 0u, 0u, 0u};
@@ -459,7 +468,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t nsub = P.st[ii].nsub;
     const uint32_t lg = wg - D.grp0;
     const uint32_t i0 = lg * kWG;
@@ -576,7 +585,7 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     __shared__ uint8_t zoff[64];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.pix_wg0; });
-    const ImgDesc& D = P.img[ii];
+    const ImgDesc D = image_desc(P, ii);
     const uint32_t lw = wg - D.pix_wg0;
     const uint32_t mrow = lw / D.pix_runs, run = lw % D.pix_runs;
     const uint32_t upm = D.upm;
