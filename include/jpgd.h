@@ -143,7 +143,10 @@ size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, con
  *  infos          [host]   n parsed headers
  *  d_scans        [device] the entropy-coded bytes of all images (still byte-stuffed, without the
  *                          EOI marker); image i occupies scan_offsets[i] .. + infos[i].scan_bytes;
- *                          16-byte aligned
+ *                          16-byte aligned.  The kernels read whole 16-byte words: the bytes up to
+ *                          the next multiple of 16 after each scan must be readable (their content
+ *                          is ignored; device allocations are granular enough that this only
+ *                          matters for a scan placed at the very end of a sub-allocated block)
  *  scan_offsets   [host]   n byte offsets into d_scans, each a multiple of 16
  *  d_coef         [device] int16 output, 16-byte aligned, may not be NULL; image i gets 64*total_units
  *                          values at element offset coef_offsets[i] (must be a multiple of 64):
@@ -188,7 +191,8 @@ int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, u
 /*
  * Stage-level entry points (used by the tests to check single steps against the oracle).
  *
- * jpgd_unstuff: the byte-unstuffing step alone.  d_in (16-byte aligned, n bytes) is compacted into
+ * jpgd_unstuff: the byte-unstuffing step alone.  d_in (16-byte aligned, n bytes, readable up to the
+ * next multiple of 16) is compacted into
  * d_out (256-byte aligned, room for n + 256 bytes: the kernel clears 192 bytes after the last one);
  * *out_len [host] receives the unstuffed length.  d_workspace: 256-byte aligned, at least
  * 1024 + 4 * ceil(n / 4096) bytes.  Returns after the stream has drained.
