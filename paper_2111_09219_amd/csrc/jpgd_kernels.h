@@ -312,17 +312,25 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     }
     // Overflow rounds: in round r the chain that started at subsequence c decodes subsequence c+r from its own
     // state and compares with the record left there one round earlier by the chain that started at c+1.
-    // Chains drop out as they synchronise.  To keep the wavefronts full, the chains still running are packed
-    // into the lowest lanes whenever their number has changed: a chain is (p, u, z, target), everything else is
-    // rebuilt from the staged stream, so moving one costs three LDS words.
+    // Chains drop out as they synchronise.  The chains still running are packed into the lowest lanes whenever
+    // that frees a whole wavefront: a chain is (p, u, z, target), everything else is rebuilt from the staged
+    // stream, so moving one costs three LDS words.  Between packings a round costs one barrier: the count of
+    // running chains goes through one LDS word per wavefront, double-buffered by the parity of the round.
     bool active = valid && (t + 1u < t1);
     uint32_t tt = t + 1u;
-    uint32_t running = kWG + 1u;  // chains running after the previous round (more than any count: first round packs)
-    for (;;) {
-        uint32_t now;
-        const uint32_t rank = wg_excl_scan(active ? 1u : 0u, scratch, &now);
+    uint32_t waves_used = kWG / 64u;
+    for (uint32_t round = 0u;; ++round) {
+        const uint64_t bal = __ballot(active);
+        uint32_t* cnt = scratch + ((round & 1u) << 2);
+        if ((t & 63u) == 0u) cnt[t >> 6] = (uint32_t)__popcll(bal);
+        __syncthreads();  // also orders the records written in the previous round before their readers
+        const uint32_t c0 = cnt[0], c1 = cnt[1], c2 = cnt[2], c3 = cnt[3];
+        const uint32_t now = c0 + c1 + c2 + c3;
         if (now == 0u) break;
-        if (now != running) {
+        if (((now + 63u) >> 6) < waves_used) {
+            const uint32_t wave = t >> 6;
+            const uint32_t before = wave == 0u ? 0u : wave == 1u ? c0 : wave == 2u ? c0 + c1 : c0 + c1 + c2;
+            const uint32_t rank = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
             if (active) {
                 mv_p[rank] = l.p;
                 mv_uz[rank] = (l.u << 8) | l.z;
@@ -339,7 +347,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
                 prime(l, w, sx, lut_s);
             }
-            running = now;
+            waves_used = (now + 63u) >> 6;
         }
         if (active) {
             l.nb = 0u;
