@@ -77,6 +77,25 @@ __device__ __forceinline__ uint32_t wg_excl_scan(uint32_t v, uint32_t* scratch, 
     return before + inc - v;
 }
 
+// the same for four values at once (one pair of barriers); scratch: 16 words of LDS
+__device__ __forceinline__ uint4 wg_excl_scan4(uint4 v, uint32_t* scratch, uint4* total) {
+    uint4 inc;
+    inc.x = wave_incl_scan(v.x); inc.y = wave_incl_scan(v.y); inc.z = wave_incl_scan(v.z); inc.w = wave_incl_scan(v.w);
+    const uint32_t wave = threadIdx.x >> 6;
+    uint4* s4 = reinterpret_cast<uint4*>(scratch);
+    __syncthreads();  // scratch may still be read from a previous use
+    if ((threadIdx.x & 63u) == 63u) s4[wave] = inc;
+    __syncthreads();
+    const uint4 w0 = s4[0], w1 = s4[1], w2 = s4[2], w3 = s4[3];
+    uint4 before = make_uint4(0u, 0u, 0u, 0u);
+    if (wave >= 1u) { before.x += w0.x; before.y += w0.y; before.z += w0.z; before.w += w0.w; }
+    if (wave >= 2u) { before.x += w1.x; before.y += w1.y; before.z += w1.z; before.w += w1.w; }
+    if (wave >= 3u) { before.x += w2.x; before.y += w2.y; before.z += w2.z; before.w += w2.w; }
+    *total = make_uint4(w0.x + w1.x + w2.x + w3.x, w0.y + w1.y + w2.y + w3.y, w0.z + w1.z + w2.z + w3.z,
+                        w0.w + w1.w + w2.w + w3.w);
+    return make_uint4(before.x + inc.x - v.x, before.y + inc.y - v.y, before.z + inc.z - v.z, before.w + inc.w - v.w);
+}
+
 __device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, uint16_t* lut_s) {
     const uint32_t n16 = D.nslots * (uint32_t)kLutEntries;       // uint16 count, multiple of 8
     const uint4* src = reinterpret_cast<const uint4*>(P.luts + D.lut_off);
@@ -429,7 +448,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
 __device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
 
 __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
-    __shared__ uint32_t scratch[8];
+    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
     const ImgDesc D = image_desc(P, ii);
@@ -437,17 +456,14 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
     const uint32_t i = (wg - D.grp0) * kWG + threadIdx.x;
     SInfo r = {0u, 0u, 0u, 0u};
     if (i < nsub) r = P.sinfo[D.sub0 + i];
-    uint32_t tot[4];
-    wg_excl_scan(r.y, scratch, &tot[0]);
-    wg_excl_scan((uint32_t)sx16(r.z), scratch, &tot[1]);
-    wg_excl_scan((uint32_t)sx16(r.z >> 16), scratch, &tot[2]);
-    wg_excl_scan((uint32_t)sx16(r.w), scratch, &tot[3]);
-    if (threadIdx.x == 0) P.grp_tot[wg] = make_int4((int)tot[0], (int)tot[1], (int)tot[2], (int)tot[3]);
+    uint4 tot;
+    wg_excl_scan4(make_uint4(r.y, (uint32_t)sx16(r.z), (uint32_t)sx16(r.z >> 16), (uint32_t)sx16(r.w)), scratch, &tot);
+    if (threadIdx.x == 0) P.grp_tot[wg] = make_int4((int)tot.x, (int)tot.y, (int)tot.z, (int)tot.w);
 }
 
 // one workgroup per image: exclusive prefix of the group totals
 __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
-    __shared__ uint32_t scratch[8];
+    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
     const uint32_t ii = blockIdx.x;
     const ImgDesc D = image_desc(P, ii);
     if (D.ngrp_max <= (uint32_t)kWG) return;  // images of up to 256 groups: the write kernel sums the totals itself
@@ -456,15 +472,12 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
     for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
         uint32_t k = b0 + threadIdx.x;
         int4 v = k < ngrp ? P.grp_tot[D.grp0 + k] : make_int4(0, 0, 0, 0);
-        uint32_t ct[4];
-        uint32_t e0 = wg_excl_scan((uint32_t)v.x, scratch, &ct[0]);
-        uint32_t e1 = wg_excl_scan((uint32_t)v.y, scratch, &ct[1]);
-        uint32_t e2 = wg_excl_scan((uint32_t)v.z, scratch, &ct[2]);
-        uint32_t e3 = wg_excl_scan((uint32_t)v.w, scratch, &ct[3]);
+        uint4 ct;
+        const uint4 e = wg_excl_scan4(make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w), scratch, &ct);
         if (k < ngrp)
-            P.grp_pref[D.grp0 + k] = make_int4((int)(carry[0] + e0), (int)(carry[1] + e1), (int)(carry[2] + e2),
-                                               (int)(carry[3] + e3));
-        for (int c = 0; c < 4; ++c) carry[c] += ct[c];
+            P.grp_pref[D.grp0 + k] = make_int4((int)(carry[0] + e.x), (int)(carry[1] + e.y), (int)(carry[2] + e.z),
+                                               (int)(carry[3] + e.w));
+        carry[0] += ct.x; carry[1] += ct.y; carry[2] += ct.z; carry[3] += ct.w;
     }
 }
 
@@ -473,7 +486,7 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
 template <bool STAGED>
 __global__ __launch_bounds__(kWG) void k_write(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    __shared__ uint32_t scratch[8];
+    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
     const ImgDesc D = image_desc(P, ii);
@@ -506,23 +519,22 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
     // plus the group's prefix
     int4 gp;
-    uint32_t tot;
     if (D.ngrp_max <= (uint32_t)kWG) {
         const int4 v = (t < lg) ? P.grp_tot[D.grp0 + t] : make_int4(0, 0, 0, 0);
-        uint32_t g0, g1, g2, g3;
-        wg_excl_scan((uint32_t)v.x, scratch, &g0);
-        wg_excl_scan((uint32_t)v.y, scratch, &g1);
-        wg_excl_scan((uint32_t)v.z, scratch, &g2);
-        wg_excl_scan((uint32_t)v.w, scratch, &g3);
-        gp = make_int4((int)g0, (int)g1, (int)g2, (int)g3);
+        uint4 g;
+        wg_excl_scan4(make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w), scratch, &g);
+        gp = make_int4((int)g.x, (int)g.y, (int)g.z, (int)g.w);
     } else {
         gp = P.grp_pref[wg];
     }
-    uint32_t grp_units;
-    uint32_t unit = (uint32_t)gp.x + wg_excl_scan(mine.y, scratch, &grp_units);
-    int32_t pred0 = gp.y + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z), scratch, &tot);
-    int32_t pred1 = gp.z + (int32_t)wg_excl_scan((uint32_t)sx16(mine.z >> 16), scratch, &tot);
-    int32_t pred2 = gp.w + (int32_t)wg_excl_scan((uint32_t)sx16(mine.w), scratch, &tot);
+    uint4 grp_tot;
+    const uint4 ex = wg_excl_scan4(make_uint4(mine.y, (uint32_t)sx16(mine.z), (uint32_t)sx16(mine.z >> 16), (uint32_t)sx16(mine.w)),
+                                   scratch, &grp_tot);
+    const uint32_t grp_units = grp_tot.x;
+    uint32_t unit = (uint32_t)gp.x + ex.x;
+    int32_t pred0 = gp.y + (int32_t)ex.y;
+    int32_t pred1 = gp.z + (int32_t)ex.z;
+    int32_t pred2 = gp.w + (int32_t)ex.w;
 
     // The group clears the coefficients it is about to fill: those from where its first subsequence takes
     // over (data unit and zig-zag index) to where the next group's does; the last group goes on to the end of
