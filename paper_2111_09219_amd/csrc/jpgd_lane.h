@@ -39,7 +39,8 @@ JPGD_HD UnitRow make_unit_row(uint32_t u, uint32_t upm, uint32_t sched_dc, uint3
 // (two decoders inside different luminance units of a 4:2:0 MCU agree on the component but
 // not on what follows) and n kept as completed data units (see SInfo).
 struct Lane {
-    uint32_t p;    // bit position in the unstuffed stream of the next syntax element
+    uint32_t p;    // bit position in the unstuffed stream of the next syntax element (kept by the window inside the
+                   // decode loops, written back when they end)
     uint32_t u;    // data unit inside the MCU
     uint32_t z;    // zig-zag index of the next coefficient (0 = a DC symbol is next)
     uint32_t nb;   // data units completed since the counter was last cleared
@@ -55,9 +56,15 @@ struct BitWin {
     uint32_t hi, lo;
     uint32_t o;      // 0..31
     uint32_t peek;
-    uint32_t next;   // cursor of the word held in `ahead`, in the units of the Fetch functor
+    uint32_t next;   // cursor of the word held in `ahead`, in the units of the Fetch functor; hi is word next - 2
     uint32_t ahead;  // the word after `lo`, fetched one refill early so that its latency is hidden
+    uint32_t origin; // bit position in the stream of the word with cursor 0
 };
+
+// bit position of the next unread bit
+JPGD_HD uint32_t win_pos(const BitWin& w) { return w.origin + ((w.next - 2u) << 5) + w.o; }
+// the window has reached bit `limit` (a multiple of 32) as soon as its cursor `next` has reached this value
+JPGD_HD uint32_t win_stop(const BitWin& w, uint32_t limit) { return ((limit - w.origin) >> 5) + 2u; }
 
 // per-image constants of the scan syntax
 struct Syntax {
@@ -78,6 +85,7 @@ JPGD_HD void win_init(BitWin& w, uint32_t p, uint32_t cursor, Fetch fetch) {
     w.peek = win_peek(w);
     w.next = cursor + 2u;
     w.ahead = fetch(w.next);
+    w.origin = (p & ~31u) - (cursor << 5);
 }
 
 // Starts the pipeline: after (p, u, z) and the window are set, read the entry of the symbol at p.
@@ -91,11 +99,17 @@ JPGD_HD void prime(Lane& l, const BitWin& w, const Syntax& sx, LutPtr lut) {
 
 // The value bits are the last `size` of the `total` bits a symbol takes; "signed ones' complement" (paper,
 // Section 2): a leading 1 means the bits are the value itself, a leading 0 means value = bits - (2^size - 1);
-// size 0 gives 0.  peek holds the symbol from its most significant bit on.
+// size 0 gives 0.  peek holds the symbol from its most significant bit on.  With the field read as a signed
+// number s (leading 1 = negative): value = s + 2^size if s < 0, else s - 2^size + 1.
 JPGD_HD int32_t symbol_value(uint32_t peek, uint32_t total, uint32_t size) {
-    const uint32_t mask = (1u << size) - 1u;
-    const uint32_t raw = (peek >> ((32u - total) & 31u)) & mask;
-    return (int32_t)(raw - ((raw << 1) <= mask ? mask : 0u));
+#if defined(__HIP_DEVICE_COMPILE__)
+    const int32_t s = __builtin_amdgcn_sbfe((int32_t)peek, (32u - total) & 31u, size);
+#else
+    const uint32_t raw = (peek >> ((32u - total) & 31u)) & ((1u << size) - 1u);
+    const int32_t s = size ? (int32_t)(raw << (32u - size)) >> (32u - size) : 0;
+#endif
+    const int32_t one = (int32_t)(1u << size);
+    return s + (s < 0 ? one : 1 - one);
 }
 
 // DC-difference sums of the three components, kept in one 64-bit accumulator with 15-bit fields
@@ -166,7 +180,6 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
     const uint32_t idx = s.esc ? l.base + sub : base2 + (w.peek >> (32 - kLutK));
     l.base = s.esc ? l.base : base2;
     l.e = lut[idx];
-    l.p += s.total;
     return s;
 }
 
@@ -176,13 +189,15 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
 template <class Fetch, class LutPtr>
 JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
                               LutPtr lut) {
-    while (l.p < limit) {
+    const uint32_t stop = win_stop(w, limit);
+    while (w.next < stop) {
         const uint32_t dcmul = l.row.dcmul;
         const Step s = step_and_request(l, w, sx, fetch, lut);
         const int32_t v = symbol_value(s.peek, s.total, s.size);
         const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
         dcacc += (int64_t)v * (int64_t)mul;
     }
+    l.p = win_pos(w);
 }
 
 // Write pass (write = true in Algorithm 2): the same walk, storing every non-zero coefficient at
@@ -194,7 +209,8 @@ JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& uni
                                LutPtr lut, Store store, uint32_t& flags) {
     // Without branches except around the store itself: a wavefront holds lanes in every kind of symbol at
     // once, so each arm of a branch would be walked anyway.
-    while (l.p < limit && unit < total_units) {
+    const uint32_t stop = win_stop(w, limit);
+    while (w.next < stop && unit < total_units) {
         const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
         const Step s = step_and_request(l, w, sx, fetch, lut);
         const int32_t value = symbol_value(s.peek, s.total, s.size);  // 0 for an escape
@@ -215,6 +231,7 @@ JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& uni
         flags |= bad ? kStInvalid : 0u;
         unit += s.done ? 1u : 0u;
     }
+    l.p = win_pos(w);
 }
 
 }  // namespace jpgd
