@@ -192,7 +192,6 @@ int orc_open(const uint8_t* file, size_t len, orc_image** out) {
         }
         pos += 2 + (size_t)seglen;
     }
-    if (!rc && im->info.restart_interval != 0) rc = ORC_E_UNSUPPORTED;
     if (!rc) {
         orc_info* in = &im->info;
         if (in->ncomp == 1) { in->hs[0] = in->vs[0] = 1; } /* a single component is never interleaved */
@@ -229,11 +228,15 @@ int orc_open(const uint8_t* file, size_t len, orc_image** out) {
         }
     }
     if (!rc) {
-        /* the entropy-coded segment runs up to the next marker: 0xFF followed by anything but 0x00 */
+        /* the entropy-coded segment runs up to the next marker that is neither a stuffed zero nor, when a
+         * restart interval is defined, a restart marker RST0..RST7 */
         size_t p = (size_t)im->info.scan_offset;
-        while (p + 1 < len && !(file[p] == 0xFF && file[p + 1] != 0x00)) ++p;
+        int ri = im->info.restart_interval != 0;
+        while (p + 1 < len &&
+               !(file[p] == 0xFF && file[p + 1] != 0x00 && !(ri && file[p + 1] >= 0xD0 && file[p + 1] <= 0xD7)))
+            ++p;
         if (p + 1 >= len) rc = ORC_E_TRUNCATED;
-        else if (file[p + 1] != 0xD9) rc = ORC_E_UNSUPPORTED; /* restart markers, further scans */
+        else if (file[p + 1] != 0xD9) rc = ORC_E_UNSUPPORTED; /* further scans, stray markers */
         im->info.scan_len = (int64_t)p - im->info.scan_offset;
     }
     if (rc) { free(im); return rc; }
@@ -282,6 +285,37 @@ int64_t orc_unstuff_bytes(const uint8_t* in, int64_t n, uint8_t* out) {
         ++k;
         if (in[i] == 0xFF && i + 1 < n && in[i + 1] == 0x00) ++i;
     }
+    return k;
+}
+
+/*
+ * The same for a segment with restart markers (T.81 E.1.4 / F.1.2.3: every Ri MCUs the encoder pads the
+ * last byte with 1-bits and emits RSTm, m = 0..7 in turn; the decoder discards the padding, checks the
+ * marker and resets the DC predictors).  Stuffed zeros and the two bytes of every RSTm are removed;
+ * starts[k] receives the offset, in the output, of the first byte of restart interval k (starts[0] = 0).
+ * Returns the output length, or -1 if the markers do not count 0,1,..7,0,.. or there are more than
+ * max_starts intervals.  out and starts may be NULL.
+ */
+int64_t orc_unstuff_restart(const uint8_t* in, int64_t n, uint8_t* out, int64_t* starts, int64_t max_starts,
+                            int64_t* nstarts) {
+    int64_t k = 0, ns = 1;
+    if (starts && max_starts > 0) starts[0] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (in[i] == 0xFF && i + 1 < n && in[i + 1] >= 0xD0 && in[i + 1] <= 0xD7) {
+            if ((in[i + 1] & 7) != ((ns - 1) & 7)) return -1;
+            if (starts) {
+                if (ns >= max_starts) return -1;
+                starts[ns] = k;
+            }
+            ++ns;
+            ++i;
+            continue;
+        }
+        if (out) out[k] = in[i];
+        ++k;
+        if (in[i] == 0xFF && i + 1 < n && in[i + 1] == 0x00) ++i;
+    }
+    if (nstarts) *nstarts = ns;
     return k;
 }
 
@@ -387,23 +421,59 @@ static void step(const orc_image* im, bitrd* r, orc_state* s, orc_symbol* sym) {
     }
 }
 
-static int unstuffed_scan(const orc_image* im, uint8_t** buf, int64_t* nbytes) {
+/* number of restart intervals of the scan (1 without DRI) */
+static int64_t interval_count(const orc_image* im) {
+    const orc_info* in = &im->info;
+    if (in->restart_interval == 0) return 1;
+    int64_t mcus = (int64_t)in->mcus_x * in->mcus_y;
+    return (mcus + in->restart_interval - 1) / in->restart_interval;
+}
+
+/* unstuffed stream (markers removed) and, if starts != NULL, the byte offset of every restart interval */
+static int unstuffed_scan(const orc_image* im, uint8_t** buf, int64_t* nbytes, int64_t** starts) {
     const uint8_t* src = im->file + im->info.scan_offset;
-    int64_t n = orc_unstuff_bytes(src, im->info.scan_len, NULL);
+    int64_t nint = interval_count(im);
+    int64_t* st = (int64_t*)malloc((size_t)nint * sizeof(int64_t));
+    if (!st) return ORC_E_ARG;
+    int64_t found = 0;
+    int64_t n = orc_unstuff_restart(src, im->info.scan_len, NULL, NULL, 0, &found);
+    if (n < 0 || found != nint) { free(st); return ORC_E_CORRUPT; } /* wrong number or order of markers */
     uint8_t* b = (uint8_t*)malloc((size_t)n + 8);
-    if (!b) return ORC_E_ARG;
-    orc_unstuff_bytes(src, im->info.scan_len, b);
+    if (!b) { free(st); return ORC_E_ARG; }
+    orc_unstuff_restart(src, im->info.scan_len, b, st, nint, &found);
     memset(b + n, 0, 8);
     *buf = b;
     *nbytes = n;
+    if (starts) *starts = st; else free(st);
     return ORC_OK;
 }
 
 int64_t orc_unstuffed_len(const orc_image* im) {
-    return orc_unstuff_bytes(im->file + im->info.scan_offset, im->info.scan_len, NULL);
+    return orc_unstuff_restart(im->file + im->info.scan_offset, im->info.scan_len, NULL, NULL, 0, NULL);
 }
 int orc_unstuff(const orc_image* im, uint8_t* out) {
-    orc_unstuff_bytes(im->file + im->info.scan_offset, im->info.scan_len, out);
+    return orc_unstuff_restart(im->file + im->info.scan_offset, im->info.scan_len, out, NULL, 0, NULL) < 0 ? ORC_E_CORRUPT
+                                                                                                       : ORC_OK;
+}
+int64_t orc_interval_count(const orc_image* im) { return interval_count(im); }
+/* byte offsets of the restart intervals in the unstuffed stream; starts has room for orc_interval_count() */
+int orc_interval_starts(const orc_image* im, int64_t* starts) {
+    int64_t found = 0;
+    int64_t n = orc_unstuff_restart(im->file + im->info.scan_offset, im->info.scan_len, NULL, starts, interval_count(im),
+                                    &found);
+    return (n < 0 || found != interval_count(im)) ? ORC_E_CORRUPT : ORC_OK;
+}
+
+/*
+ * End of a restart interval: the decoder stands at bit *p after the interval's last symbol; what is left of
+ * that byte must be 1-bits (at most 7), and decoding continues at the first bit of the next interval.
+ */
+static int enter_interval(const uint8_t* buf, int64_t* p, int64_t start_byte) {
+    int64_t target = start_byte * 8;
+    if (*p > target || target - *p > 7) return ORC_E_CORRUPT;
+    for (int64_t b = *p; b < target; ++b)
+        if (!((buf[b >> 3] >> (7 - (b & 7))) & 1)) return ORC_E_CORRUPT;
+    *p = target;
     return ORC_OK;
 }
 
@@ -417,7 +487,8 @@ int orc_decode_coefficients(const orc_image* im, int16_t* coef, int64_t* end_bit
     if (!im || !coef) return ORC_E_ARG;
     uint8_t* buf;
     int64_t nbytes;
-    int rc = unstuffed_scan(im, &buf, &nbytes);
+    int64_t* starts;
+    int rc = unstuffed_scan(im, &buf, &nbytes, &starts);
     if (rc) return rc;
     bitrd r = {buf, nbytes * 8, 0, 0};
     const orc_info* in = &im->info;
@@ -425,7 +496,14 @@ int orc_decode_coefficients(const orc_image* im, int16_t* coef, int64_t* end_bit
     int32_t pred[3] = {0, 0, 0};
     orc_state s = {0, 0, 0};
     orc_symbol sym;
+    const int64_t units_per_interval = (int64_t)in->restart_interval * in->units_per_mcu; /* 0: no restarts */
     for (int64_t k = 0; k < in->total_units && !rc; ++k) {
+        if (units_per_interval && k > 0 && k % units_per_interval == 0) {
+            /* a new restart interval: padding discarded, predictors back to zero */
+            rc = enter_interval(buf, &s.p, starts[k / units_per_interval]);
+            if (rc) break;
+            pred[0] = pred[1] = pred[2] = 0;
+        }
         int unit_u = s.u;
         for (;;) {
             int z_before = s.z;
@@ -448,6 +526,7 @@ int orc_decode_coefficients(const orc_image* im, int16_t* coef, int64_t* end_bit
     }
     if (end_bit) *end_bit = s.p;
     free(buf);
+    free(starts);
     return rc;
 }
 
@@ -474,39 +553,59 @@ int orc_trace(const orc_image* im, const uint8_t* bits, int64_t nbits, int64_t s
  *   p[i], u[i], z[i]   its state there,
  *   units[i]           data units completed by symbols that start inside subsequence i,
  *   slots[i]           zig-zag slots those symbols cover (= 64*units[i] + z[i] - z[i-1]),
- *   dcsum[3*i + c]     sum of the DC differences of component c among them.
- * Once all data units are decoded the state stays at the end position.
+ *   dcsum[3*i + c]     sum of the DC differences of component c among them,
+ *   restart[i]         1 if one of them is the first symbol of a restart interval other than the first;
+ *                      dcsum then only counts symbols from the last such one on (the predictors were reset).
+ * At the end of a restart interval the decoder moves to the first bit of the next interval at once, so a
+ * state never points into padding.  Once all data units are decoded the state stays at the end position.
  * nsub must be ceil(8*unstuffed_len / L).
  */
 int orc_boundary_states(const orc_image* im, int L, int64_t nsub, int64_t* p, int32_t* u, int32_t* z,
-                        int32_t* units, int64_t* slots, int32_t* dcsum) {
+                        int32_t* units, int64_t* slots, int32_t* dcsum, int32_t* restart) {
     if (!im || L < 32 || nsub < 1) return ORC_E_ARG;
     uint8_t* buf;
     int64_t nbytes;
-    int rc = unstuffed_scan(im, &buf, &nbytes);
+    int64_t* starts;
+    int rc = unstuffed_scan(im, &buf, &nbytes, &starts);
     if (rc) return rc;
     bitrd r = {buf, nbytes * 8, 0, 0};
     const orc_info* in = &im->info;
+    const int64_t units_per_interval = (int64_t)in->restart_interval * in->units_per_mcu;
     orc_state s = {0, 0, 0};
     orc_symbol sym;
     int64_t done = 0;
+    int fresh = 0; /* the next symbol is the first of a restart interval (other than the image's first) */
     for (int64_t i = 0; i < nsub; ++i) {
         int64_t limit = (i + 1) * (int64_t)L;
-        int32_t nu = 0, dc[3] = {0, 0, 0};
+        int32_t nu = 0, dc[3] = {0, 0, 0}, rs = 0;
         int64_t ns = 0;
         while (s.p < limit && done < in->total_units) {
+            if (fresh) { rs = 1; dc[0] = dc[1] = dc[2] = 0; fresh = 0; }
             int zb = s.z, ub = s.u;
             step(im, &r, &s, &sym);
-            if (sym.kind == 3 || r.overrun) { free(buf); return ORC_E_CORRUPT; }
+            if (sym.kind == 3 || r.overrun) { free(buf); free(starts); return ORC_E_CORRUPT; }
             if (sym.is_dc) dc[im->unit_comp[ub]] += sym.value;
-            if (s.z == 0) { ++nu; ++done; ns += 64 - zb; }
-            else ns += s.z - zb;
+            if (s.z == 0) {
+                ++nu; ++done; ns += 64 - zb;
+                if (units_per_interval && done < in->total_units && done % units_per_interval == 0) {
+                    /* the interval is complete: the decoder moves on to the next one at once */
+                    if (enter_interval(buf, &s.p, starts[done / units_per_interval])) {
+                        free(buf); free(starts);
+                        return ORC_E_CORRUPT;
+                    }
+                    fresh = 1;
+                }
+            } else {
+                ns += s.z - zb;
+            }
         }
         p[i] = s.p; u[i] = s.u; z[i] = s.z;
         units[i] = nu; slots[i] = ns;
         dcsum[3 * i] = dc[0]; dcsum[3 * i + 1] = dc[1]; dcsum[3 * i + 2] = dc[2];
+        if (restart) restart[i] = rs;
     }
     free(buf);
+    free(starts);
     return ORC_OK;
 }
 

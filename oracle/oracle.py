@@ -71,7 +71,10 @@ def _load():
         lib.orc_unstuff.argtypes = [vp, vp]
         lib.orc_decode_coefficients.argtypes = [vp, vp, ctypes.POINTER(i64)]
         lib.orc_trace.argtypes = [vp, vp, i64, i64, i32, i32, ctypes.POINTER(_Symbol), i32]
-        lib.orc_boundary_states.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp, vp]
+        lib.orc_boundary_states.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp, vp, vp]
+        lib.orc_interval_count.argtypes = [vp]
+        lib.orc_interval_count.restype = i64
+        lib.orc_interval_starts.argtypes = [vp, vp]
         lib.orc_zigzag.argtypes = [vp]
         lib.orc_zigzag.restype = None
         lib.orc_idct8x8.argtypes = [vp, vp]
@@ -201,6 +204,20 @@ class OracleImage:
         units = np.empty(nsub, dtype=np.int32)
         slots = np.empty(nsub, dtype=np.int64)
         dcsum = np.empty((nsub, 3), dtype=np.int32)
+        restart = np.empty(nsub, dtype=np.int32)
         _check(self._lib.orc_boundary_states(self._h, L, nsub, p.ctypes.data, u.ctypes.data, z.ctypes.data,
-                                             units.ctypes.data, slots.ctypes.data, dcsum.ctypes.data))
-        return dict(p=p, u=u, z=z, units=units, slots=slots, dcsum=dcsum)
+                                             units.ctypes.data, slots.ctypes.data, dcsum.ctypes.data,
+                                             restart.ctypes.data))
+        return dict(p=p, u=u, z=z, units=units, slots=slots, dcsum=dcsum, restart=restart)
+
+    @property
+    def restart_interval(self) -> int:
+        """MCUs per restart interval (0: the scan has no restart markers)."""
+        return self.info.restart_interval
+
+    def interval_starts(self) -> np.ndarray:
+        """Byte offset, in the unstuffed stream, of the first byte of every restart interval."""
+        n = self._lib.orc_interval_count(self._h)
+        out = np.zeros(n, dtype=np.int64)
+        _check(self._lib.orc_interval_starts(self._h, out.ctypes.data))
+        return out

@@ -404,3 +404,152 @@ def test_boundary_states_are_the_sequential_decoder_s_states(sub, L):
     for c in range(img.ncomp):
         last = [k for k in range(img.total_units) if comp_of_unit[k % upm] == c][-1]
         assert int(bs["dcsum"][:, c].sum()) == int(coef[last, 0])
+
+
+# ------------------------------------------------------------------ restart intervals (T.81 DRI / RSTm)
+
+def test_hand_written_restart_stream_resets_prediction_and_skips_padding():
+    """Four gray blocks, restart interval of one MCU, written by hand: after every RSTm the DC predictor is
+    zero again (so the coded difference IS the DC value) and the 1-bits that pad the last byte are not data.
+    The same blocks without restart markers need the differences of a running prediction."""
+    DC, AC = jf.K3_DC_LUMA, jf.K5_AC_LUMA
+    dcs = [5, 2, -7, 40]
+    ac = [[(0, 3)], [], [(1, -2), (0, 1)], []]
+
+    def block_bits(diff, coeffs):
+        size, vb = jf.value_bits(diff)
+        out = DC[size] + vb
+        for run, v in coeffs:
+            s, b = jf.value_bits(v)
+            out += AC[(run, s)] + b
+        return out + AC[(0, 0)]
+
+    expect = np.zeros((4, 64), np.int16)
+    for k, (d, cs) in enumerate(zip(dcs, ac)):
+        expect[k, 0] = d
+        z = 1
+        for run, v in cs:
+            z += run
+            expect[k, z] = v
+            z += 1
+    enc = encode_jpeg(np.full((8, 32), 128, np.uint8), quality=50, restart_interval=1)
+    head = enc.data[:enc.scan_offset].tobytes()                       # header with DRI = 1
+    scan = b""
+    for k, (d, cs) in enumerate(zip(dcs, ac)):
+        scan += jf.stuff(jf.pack_bits(block_bits(d, cs)))             # predictor 0: the difference is the value
+        if k < 3:
+            scan += bytes([0xFF, 0xD0 + k])
+    img = OracleImage(np.frombuffer(head + scan + b"\xFF\xD9", np.uint8).copy())
+    assert img.restart_interval == 1
+    assert np.array_equal(img.coefficients(), expect)
+    starts = img.interval_starts()
+    assert starts[0] == 0 and len(starts) == 4
+    # the same blocks as one interval: differences against the previous block's DC
+    bits, pred = "", 0
+    for d, cs in zip(dcs, ac):
+        bits += block_bits(d - pred, cs)
+        pred = d
+    plain = OracleImage(_annexk_header_file(32, 8, jf.pack_bits(bits)))
+    assert np.array_equal(plain.coefficients(), expect)
+    # markers out of order, and padding that is not all ones, are corrupt
+    bad = bytearray(head + scan + b"\xFF\xD9")
+    i = bytes(bad).index(b"\xFF\xD1")
+    bad[i + 1] = 0xD3
+    with pytest.raises(OracleError):
+        OracleImage(np.frombuffer(bytes(bad), np.uint8).copy()).coefficients()
+    first = block_bits(dcs[0], ac[0])
+    assert len(first) % 8                                             # the first interval ends with padding
+    padded0 = bytearray(jf.pack_bits(first))
+    padded0[-1] &= 0xFE                                               # clear one padding bit
+    assert 0xFF not in padded0
+    scan2 = bytes(padded0) + scan[len(padded0):]
+    with pytest.raises(OracleError):
+        OracleImage(np.frombuffer(head + scan2 + b"\xFF\xD9", np.uint8).copy()).coefficients()
+
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_restart_intervals_do_not_change_the_coefficients(sub):
+    """An image coded with any restart interval decodes to the coefficients of the same image coded without
+    (absolute DC values: the prediction restarts, the values do not change), and to what the independent
+    encoder quantised."""
+    px = small_image(31, 70, 100, ncomp=1 if sub == "gray" else 3, sigma=14.0)
+    base = encode_jpeg(px, quality=85, subsampling=sub)
+    ref = OracleImage(base.data).coefficients()
+    for ri in (1, 2, 7, 13, 1000):
+        for opt in (False, True):
+            e = encode_jpeg(px, quality=85, subsampling=sub, optimize=opt, restart_interval=ri)
+            o = OracleImage(e.data)
+            assert o.restart_interval == ri
+            c = o.coefficients()
+            assert np.array_equal(c, ref) and np.array_equal(c, e.coef)
+            mcus = o.info.mcus_x * o.info.mcus_y
+            assert len(o.interval_starts()) == -(-mcus // ri)
+
+
+@pytest.mark.parametrize("kw", [dict(restart_marker_blocks=3), dict(restart_marker_rows=1), dict(restart_marker_blocks=1)])
+def test_decodes_pillow_files_with_restart_markers(kw):
+    """Restart markers written by libjpeg (through Pillow), decoded by the oracle and by libjpeg itself."""
+    for ncomp, extra in ((1, {}), (3, dict(subsampling=0)), (3, dict(subsampling=2))):
+        px = small_image(12, 72, 88, ncomp=ncomp, sigma=7.0, shapes=0 if extra.get("subsampling") == 2 else 4)
+        if extra.get("subsampling") == 2:
+            px[...] = px.mean(axis=(0, 1), keepdims=True).astype(np.uint8)   # flat chroma: no interpolation differences
+            px[::2, :, :] = np.clip(px[::2, :, :].astype(int) + 9, 0, 255).astype(np.uint8)
+            px[..., 0], px[..., 2] = px[..., 1], px[..., 1]
+        data = _pillow_jpeg(px, quality=88, **extra, **kw)
+        assert b"\xFF\xDD" in data.tobytes()
+        img = OracleImage(data)
+        assert img.restart_interval > 0
+        ref = np.asarray(Image.open(io.BytesIO(data.tobytes())))
+        got = img.pixels()
+        assert got.shape == ref.shape
+        assert np.abs(got.astype(int) - ref.astype(int)).max() <= 2
+
+
+@pytest.mark.parametrize("sub,L,ri", [("gray", 128, 1), ("444", 256, 2), ("420", 1024, 3), ("420", 128, 1), ("422", 512, 40)])
+def test_boundary_states_with_restart_intervals(sub, L, ri):
+    """With restart intervals a reported state never points into padding, decoding on from it stays on the
+    sequential decoder's symbols up to the end of the interval, and the per-subsequence DC sums, restarted
+    where a subsequence holds the first symbol of an interval, rebuild every DC value."""
+    px = small_image(23, 80, 112, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+    enc = encode_jpeg(px, quality=88, subsampling=sub, restart_interval=ri)
+    img = OracleImage(enc.data)
+    raw = img.unstuffed()
+    starts = img.interval_starts()
+    bs = img.boundary_states(L)
+    n = len(bs["p"])
+    assert n == -(-(raw.size * 8) // L)
+    assert int(bs["units"].sum()) == img.total_units
+    # flagged subsequences are exactly those in which an interval (other than the first) begins at a symbol
+    # start: every interval start is a symbol start, so flag i <=> some start lies in [i*L, (i+1)*L) -- except
+    # that a start inside the overhang of the previous subsequence's last symbol cannot happen (symbols do
+    # not straddle interval boundaries)
+    want = np.zeros(n, np.int32)
+    for sb in starts[1:]:
+        want[(8 * int(sb)) // L] = 1
+    assert np.array_equal(bs["restart"], want)
+    # segmented prefix of the DC sums = predictor of each component at every boundary
+    coef = img.coefficients()
+    upm, comp_of = img.units_per_mcu, None
+    ncomp = img.ncomp
+    comp_of = [0] * (upm - 2) + [1, 2] if ncomp == 3 else [0]
+    per_int = ri * upm
+    pred = np.zeros(3, np.int64)
+    unit = 0
+    for i in range(n):
+        if bs["restart"][i]:
+            pred[:] = 0
+        pred += bs["dcsum"][i]
+        unit += int(bs["units"][i])
+        z, u = int(bs["z"][i]), int(bs["u"][i])
+        # units whose DC symbol has been decoded: all completed ones, plus the current one if z > 0
+        seen = unit + (1 if z > 0 else 0)
+        if seen == 0 or unit >= img.total_units:
+            continue
+        first_of_interval = ((seen - 1) // per_int) * per_int
+        for c in range(ncomp):
+            ks = [k for k in range(first_of_interval, seen) if comp_of[k % upm] == c]
+            assert pred[c] == (coef[ks[-1], 0] if ks else 0), (i, c)
+    # no state points into padding: p is a symbol start of the sequential decode
+    for i in range(0, n, max(1, n // 40)):
+        p = int(bs["p"][i])
+        assert p >= (i + 1) * L or unit >= img.total_units
