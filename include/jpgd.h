@@ -69,7 +69,7 @@ typedef struct {
     uint32_t total_units;         /* data units (8x8 blocks) in the scan                             */
     uint64_t scan_offset;         /* first entropy-coded byte inside the file                        */
     uint64_t scan_bytes;          /* entropy-coded bytes, still byte-stuffed, up to the EOI marker   */
-    uint32_t restart_interval;    /* always 0 in an accepted file                                    */
+    uint32_t restart_interval;    /* MCUs per restart interval (DRI); 0 = the scan has no markers    */
 } jpgd_info;
 
 typedef struct {
@@ -120,9 +120,10 @@ typedef struct {
  * scanning it: it ends at the last EOI marker of the file.
  *
  * Accepted: SOF0, 8-bit, one scan, 1 component or 3 components with chroma
- * sampled 1x1 and luma 1x1, 2x1, 1x2 or 2x2; no restart interval.
+ * sampled 1x1 and luma 1x1, 2x1, 1x2 or 2x2; with or without restart
+ * intervals (DRI / RSTm).
  * JPGD_E_UNSUPPORTED: progressive / extended / lossless / arithmetic frames,
- * 12-bit, other component counts or sampling, DRI != 0, several scans.
+ * 12-bit, other component counts or sampling, several scans.
  * JPGD_E_TABLE: table id > 3, more than 256 symbols, more codes of some
  * length than that length can hold, a DC table with a symbol above 15 (a DC
  * symbol is a number of value bits), a table a component refers to missing.
@@ -205,8 +206,10 @@ int jpgd_unstuff(const uint8_t* d_in /*[device]*/, size_t n, uint8_t* d_out /*[d
  * this workspace to the host: for image `image`, subsequence i < *n_subseq,
  *   p[i]      bit position (unstuffed stream) of the first symbol starting at or after (i+1)*subseq_bits
  *   u[i],z[i] data unit inside the MCU and zig-zag index at that point
- *   units[i]  data units completed by symbols starting inside subsequence i
- *   dcsum[3*i+c] sum of DC differences of component c among those symbols (as int16, wrapped)
+ *   units[i]  bits 0..30: data units completed by symbols starting inside subsequence i;
+ *             bit 31: one of those symbols was the first of a restart interval
+ *   dcsum[3*i+c] sum of DC differences of component c among those symbols (as int16, wrapped),
+ *             counted from the last symbol that began a restart interval, if there was one
  * Arrays must have room for `capacity` entries; JPGD_E_ARG if fewer than needed.
  */
 int jpgd_read_sync_info(const void* d_workspace, int image, uint32_t capacity, uint32_t* n_subseq,

@@ -227,7 +227,8 @@ def jpgd_read_sync_info(d_workspace, image: int, capacity: int, stream=None):
                                        u.ctypes.data, z.ctypes.data, units.ctypes.data, dcsum.ctypes.data,
                                        _stream_handle(stream)), "jpgd_read_sync_info")
     k = n.value
-    return dict(p=p[:k], u=u[:k], z=z[:k], units=units[:k], dcsum=dcsum[:k])
+    # the unit count shares its word with the flag "a restart interval began in this subsequence"
+    return dict(p=p[:k], u=u[:k], z=z[:k], units=units[:k] & 0x7FFFFFFF, restart=units[:k] >> 31, dcsum=dcsum[:k])
 
 
 # ------------------------------------------------------------------------------- convenience: buffers

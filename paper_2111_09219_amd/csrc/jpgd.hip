@@ -23,7 +23,7 @@ constexpr uint32_t kMagic = 0x4A504744u;  // "JPGD"
 struct WsHeader {
     uint32_t magic, nimg, logL, overlap;
     uint64_t off_status, off_state, off_img, off_lut, off_qt;       // uploaded region
-    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref; // device-written regions
+    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref, off_bmap; // device-written regions
     uint64_t upload_bytes, total_bytes;
 };
 
@@ -33,6 +33,7 @@ struct Plan {
     std::vector<uint32_t> lut_of_img;  // index of the table set of image i
     uint32_t nsets = 0, lut_slots = 0;
     uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, nsub_total = 0;
+    uint32_t bmap_words = 0;  // interval-start bitmaps of the images that have restart intervals
     uint32_t L = 0;
 };
 
@@ -89,11 +90,19 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         if (in.units_per_mcu < 1 || in.units_per_mcu > 6 || kPixBlocks % in.units_per_mcu) return JPGD_E_ARG;
         if (in.scan_bytes < 1 || in.scan_bytes >= (1ull << 28)) return JPGD_E_ARG;
         if (in.total_units < 1 || in.total_units > 0x3FFFFFFu) return JPGD_E_ARG;
-        if (in.restart_interval) return JPGD_E_UNSUPPORTED;
         d.scan_bytes = (uint32_t)in.scan_bytes;
         d.tile0 = pl.tiles;
         d.ntiles = (d.scan_bytes + kUnstuffTile - 1) / kUnstuffTile;
         pl.tiles += d.ntiles;
+        d.restart = in.restart_interval;
+        d.nint = 1;
+        d.bmap_off = 0;
+        if (d.restart) {
+            const uint64_t mcus = (uint64_t)in.mcus_x * in.mcus_y;
+            d.nint = (uint32_t)((mcus + d.restart - 1) / d.restart);
+            d.bmap_off = pl.bmap_words;
+            pl.bmap_words += d.ntiles * 128u + 128u;
+        }
         d.stream_off = stream_bytes;
         stream_bytes += up256((size_t)d.scan_bytes + L / 8 + 64 + 16);
         d.nsub_max = (uint32_t)(((uint64_t)d.scan_bytes * 8 + L - 1) / L);
@@ -175,6 +184,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     h.off_sinfo = off;  off = up256(off + (size_t)pl.nsub_total * sizeof(SInfo));
     h.off_gtot = off;   off = up256(off + (size_t)pl.grps * 16);
     h.off_gpref = off;  off = up256(off + (size_t)pl.grps * 16);
+    h.off_bmap = off;   off = up256(off + (size_t)pl.bmap_words * 4);
     h.total_bytes = off;
     return JPGD_OK;
 }
@@ -315,13 +325,17 @@ uint32_t staged_max_bits() {
 }
 #define kStagedMaxL staged_max_bits()
 
-size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots) {
-    uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
-    return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4;
+// with restart intervals the kernels also keep the interval-start bitmap of the staged bytes: one bit per byte
+size_t lds_bitmap_bytes(uint32_t L, bool restart) {
+    return restart ? ((size_t)(kWG * (L / 32) + 4 + 7) / 8 + 2) * 4 : 0;
 }
-size_t lds_write_bytes(uint32_t L, uint32_t lut_slots) {
+size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
-    return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4;
+    return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
+}
+size_t lds_write_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
+    uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
+    return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
 }
 
 // dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
@@ -362,7 +376,8 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         pl.img[i].pix_off = want_pixels ? pixel_offsets[i] : 0;
     }
     hipStream_t stream = (hipStream_t)stream_v;
-    const size_t lds_sync = lds_sync_bytes(pl.L, pl.lut_slots), lds_write = lds_write_bytes(pl.L, pl.lut_slots);
+    const bool any_restart = pl.bmap_words != 0u;
+    const size_t lds_sync = lds_sync_bytes(pl.L, pl.lut_slots, any_restart), lds_write = lds_write_bytes(pl.L, pl.lut_slots, any_restart);
     const size_t lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
     if (lds_sync > 150 * 1024) return JPGD_E_ARG;
 
@@ -420,6 +435,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.sinfo = (SInfo*)(ws + pl.h.off_sinfo);
     P.grp_tot = (int4*)(ws + pl.h.off_gtot);
     P.grp_pref = (int4*)(ws + pl.h.off_gpref);
+    P.bmap = (uint32_t*)(ws + pl.h.off_bmap);
     P.luts = (const uint16_t*)(ws + pl.h.off_lut);
     P.qts = (const uint16_t*)(ws + pl.h.off_qt);
     P.coef = d_coef;

@@ -49,14 +49,18 @@ JPGD_HD uint32_t lut_esc_offset(uint32_t e) { return ((e >> 3) & 255u) << 1; }
 //        bits 0..5   p - (i+1)*L  (bit position relative to the end of the subsequence, 0..31)
 //        bits 6..11  z            (zig-zag index of the next coefficient)
 //        bits 12..15 u            (data unit inside the MCU)
-//  y : data units completed by the symbols that start inside the subsequence.  The paper's count n
-//      (zig-zag slots covered) is 64*y + z_i - z_{i-1}; keeping units and z apart makes the exclusive
-//      scan deliver the output position as (unit index, z) without overflow.
+//  y : bits 0..30: data units completed by the symbols that start inside the subsequence; bit 31: one of
+//      those symbols was the first of a restart interval (the DC sums below then start at that symbol).
+//      The paper's count n (zig-zag slots covered) is 64*units + z_i - z_{i-1}; keeping units and z apart
+//      makes the exclusive scan deliver the output position as (unit index, z) without overflow.
 //  z : sum of DC differences of component 0 (low 16 bits) and component 1 (high 16 bits), wrapped
 //  w : the same for component 2 (low 16 bits)
 struct SInfo {
     uint32_t x, y, z, w;
 };
+
+JPGD_HD uint32_t rec_units(uint32_t y) { return y & 0x7FFFFFFFu; }
+JPGD_HD uint32_t rec_restarted(uint32_t y) { return y >> 31; }
 
 JPGD_HD uint32_t pack_state(uint32_t p_rel, uint32_t z, uint32_t u) { return (p_rel & 63u) | (z << 6) | (u << 12); }
 JPGD_HD uint32_t state_prel(uint32_t x) { return x & 63u; }
@@ -98,14 +102,20 @@ struct ImgDesc {
     uint32_t pix_wg0;      // first workgroup of the pixel kernel
     uint32_t pix_runs;     // workgroups per MCU row
     uint32_t qt_off;       // element (uint16) offset of 3 x 64 quantisation values (per component, zig-zag)
-    uint32_t pad_;
+    // restart intervals (0 = the scan has none)
+    uint32_t restart;      // MCUs per interval
+    uint32_t nint;         // intervals in the scan
+    uint32_t bmap_off;     // word offset of this image's interval-start bitmap (one bit per unstuffed byte,
+                           // 128 words per unstuff tile plus 128 of slack)
+    uint32_t pad_[2];
 };
 
 // written by the unstuff kernels
 struct ImgState {
     uint32_t nbytes;   // unstuffed length B
     uint32_t nsub;     // ceil(8B / L)
-    uint32_t pad_[2];
+    uint32_t markers;  // restart markers met (counted by the unstuff kernels; must be nint - 1)
+    uint32_t pad_;
 };
 
 // status word bits (device -> host)

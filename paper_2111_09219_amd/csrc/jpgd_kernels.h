@@ -22,6 +22,7 @@ struct Params {
     SInfo* sinfo;
     int4* grp_tot;          // per group of kWG subsequences: (units, dc0, dc1, dc2) totals
     int4* grp_pref;         // exclusive prefix of grp_tot inside the image
+    uint32_t* bmap;         // interval-start bitmaps of images with restart intervals (ImgDesc::bmap_off)
     const uint16_t* luts;
     const uint16_t* qts;
     int16_t* coef;
@@ -77,23 +78,68 @@ __device__ __forceinline__ uint32_t wg_excl_scan(uint32_t v, uint32_t* scratch, 
     return before + inc - v;
 }
 
-// the same for four values at once (one pair of barriers); scratch: 16 words of LDS
-__device__ __forceinline__ uint4 wg_excl_scan4(uint4 v, uint32_t* scratch, uint4* total) {
-    uint4 inc;
-    inc.x = wave_incl_scan(v.x); inc.y = wave_incl_scan(v.y); inc.z = wave_incl_scan(v.z); inc.w = wave_incl_scan(v.w);
-    const uint32_t wave = threadIdx.x >> 6;
-    uint4* s4 = reinterpret_cast<uint4*>(scratch);
+// What the scan over s_info carries (paper, Algorithm 1: exclusive prefix sum on s_info.n; Section 4.2: prefix
+// sum of the DC differences): data units, and the DC sums of the three components.  With restart intervals
+// the DC sums are a segmented sum: a record whose subsequence holds the first symbol of an interval (flag)
+// starts them afresh.  join(a, b) = a followed by b; it is associative, so the usual scans apply.
+struct Seg {
+    uint32_t units, flag;
+    int32_t d0, d1, d2;
+};
+__device__ __forceinline__ Seg seg_zero() { return Seg{0u, 0u, 0, 0, 0}; }
+__device__ __forceinline__ Seg seg_join(const Seg& a, const Seg& b) {
+    Seg r;
+    r.units = a.units + b.units;
+    r.flag = a.flag | b.flag;
+    r.d0 = b.flag ? b.d0 : a.d0 + b.d0;
+    r.d1 = b.flag ? b.d1 : a.d1 + b.d1;
+    r.d2 = b.flag ? b.d2 : a.d2 + b.d2;
+    return r;
+}
+__device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
+__device__ __forceinline__ Seg seg_of_record(const SInfo& r) {
+    return Seg{rec_units(r.y), rec_restarted(r.y), sx16(r.z), sx16(r.z >> 16), sx16(r.w)};
+}
+// group totals travel as int4: units with the flag in bit 31, then the three sums
+__device__ __forceinline__ int4 seg_pack(const Seg& s) { return make_int4((int)(s.units | (s.flag << 31)), s.d0, s.d1, s.d2); }
+__device__ __forceinline__ Seg seg_unpack(const int4& v) {
+    return Seg{(uint32_t)v.x & 0x7FFFFFFFu, (uint32_t)v.x >> 31, v.y, v.z, v.w};
+}
+__device__ __forceinline__ Seg seg_shfl_up(const Seg& v, int d) {
+    Seg o;
+    o.units = __shfl_up(v.units, d, 64); o.flag = __shfl_up(v.flag, d, 64);
+    o.d0 = __shfl_up(v.d0, d, 64); o.d1 = __shfl_up(v.d1, d, 64); o.d2 = __shfl_up(v.d2, d, 64);
+    return o;
+}
+
+// exclusive scan of v over the 256 lanes of the workgroup under seg_join; *total gets the join of all.
+// scratch: 20 words of LDS.
+__device__ __forceinline__ Seg wg_excl_segscan(Seg v, uint32_t* scratch, Seg* total) {
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    Seg inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const Seg o = seg_shfl_up(inc, d);
+        if (lane >= (uint32_t)d) inc = seg_join(o, inc);
+    }
     __syncthreads();  // scratch may still be read from a previous use
-    if ((threadIdx.x & 63u) == 63u) s4[wave] = inc;
+    if (lane == 63u) {
+        uint32_t* s5 = scratch + wave * 5u;
+        s5[0] = inc.units; s5[1] = inc.flag; s5[2] = (uint32_t)inc.d0; s5[3] = (uint32_t)inc.d1; s5[4] = (uint32_t)inc.d2;
+    }
     __syncthreads();
-    const uint4 w0 = s4[0], w1 = s4[1], w2 = s4[2], w3 = s4[3];
-    uint4 before = make_uint4(0u, 0u, 0u, 0u);
-    if (wave >= 1u) { before.x += w0.x; before.y += w0.y; before.z += w0.z; before.w += w0.w; }
-    if (wave >= 2u) { before.x += w1.x; before.y += w1.y; before.z += w1.z; before.w += w1.w; }
-    if (wave >= 3u) { before.x += w2.x; before.y += w2.y; before.z += w2.z; before.w += w2.w; }
-    *total = make_uint4(w0.x + w1.x + w2.x + w3.x, w0.y + w1.y + w2.y + w3.y, w0.z + w1.z + w2.z + w3.z,
-                        w0.w + w1.w + w2.w + w3.w);
-    return make_uint4(before.x + inc.x - v.x, before.y + inc.y - v.y, before.z + inc.z - v.z, before.w + inc.w - v.w);
+    Seg carry = seg_zero(), all = seg_zero();
+#pragma unroll
+    for (uint32_t k = 0; k < 4u; ++k) {
+        const uint32_t* s5 = scratch + k * 5u;
+        const Seg t = Seg{s5[0], s5[1], (int32_t)s5[2], (int32_t)s5[3], (int32_t)s5[4]};
+        if (k < wave) carry = seg_join(carry, t);
+        all = seg_join(all, t);
+    }
+    *total = all;
+    Seg before = seg_shfl_up(inc, 1);
+    if (lane == 0u) before = seg_zero();
+    return seg_join(carry, before);
 }
 
 __device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, uint16_t* lut_s) {
@@ -127,6 +173,14 @@ __device__ __forceinline__ void stage_stream(const uint8_t* stream_img, uint32_t
     }
 }
 
+// LDS copy of the part of an image's interval-start bitmap that covers stream words first_word .. +nwords;
+// word k of the bitmap is then bm_s[k - (first_word >> 3)]
+__device__ __forceinline__ void stage_bitmap(const uint32_t* bmap_img, uint32_t first_word, uint32_t nwords, uint32_t* bm_s) {
+    const uint32_t k0 = first_word >> 3;
+    const uint32_t n = ((first_word + nwords + 7u) >> 3) - k0 + 1u;
+    for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) bm_s[k] = bmap_img[k0 + k];
+}
+
 __device__ __forceinline__ uint32_t pack_dc01(int64_t acc) {
     int32_t d0, d1, d2;
     dc_unpack(acc, d0, d1, d2);
@@ -139,12 +193,15 @@ __device__ __forceinline__ uint32_t pack_dc2(int64_t acc) {
 }
 
 // ---- unstuffing (byte compaction) -----------------------------------------------------------------
-// A 0x00 is dropped iff the byte before it is 0xFF: inside entropy-coded data without restart markers a
-// 0xFF is always followed by its stuffed 0x00, so the decision is local.
+// A 0x00 is dropped iff the byte before it is 0xFF: inside entropy-coded data a 0xFF is always followed by
+// its stuffed 0x00 or, in a scan with restart intervals, by the second byte of a marker RST0..RST7; both
+// bytes of such a marker are dropped too, and the byte that follows it is the first of an interval.  All
+// decisions are local (one byte back, one byte ahead).
 
 struct UnstuffLane {
     uint32_t bytes[4];  // 16 input bytes
     uint32_t keep_mask; // bit j set = byte j is kept
+    uint32_t mark_mask; // bit j set = byte j is the second byte of a restart marker
     uint32_t nvalid;    // bytes of this lane that exist
 };
 
@@ -152,22 +209,30 @@ struct UnstuffLane {
 // to the next multiple of 16); bytes past the end are masked out.  No private array is indexed with a variable:
 // the compiler would move such an array to LDS and read the dispatch packet for the workgroup's shape, and that
 // packet lives in host memory -- measured at 2 to 11 microseconds per wavefront when a whole grid asks at once.
-__device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_t n, uint32_t pos) {
+__device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_t n, uint32_t pos, bool restart) {
     UnstuffLane r;
     r.nvalid = pos >= n ? 0u : (n - pos < 16u ? n - pos : 16u);
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (r.nvalid) v = *reinterpret_cast<const uint4*>(scan + pos);
     r.bytes[0] = v.x; r.bytes[1] = v.y; r.bytes[2] = v.z; r.bytes[3] = v.w;
     uint32_t prev = (pos > 0u && r.nvalid) ? scan[pos - 1u] : 0u;
-    uint32_t mask = 0u;
+    const uint32_t after = (restart && pos + 16u < n) ? scan[pos + 16u] : 0u;
+    uint32_t mask = 0u, marks = 0u;
 #pragma unroll
     for (uint32_t j = 0; j < 16u; ++j) {
-        uint32_t b = (r.bytes[j >> 2] >> (8u * (j & 3u))) & 255u;
-        bool drop = (b == 0u) && (prev == 255u);
-        if (j < r.nvalid && !drop) mask |= 1u << j;
+        const uint32_t b = (r.bytes[j >> 2] >> (8u * (j & 3u))) & 255u;
+        const uint32_t nx = j < 15u ? (r.bytes[(j + 1u) >> 2] >> (8u * ((j + 1u) & 3u))) & 255u : after;
+        const bool exists = j < r.nvalid;
+        const bool nx_exists = j + 1u < r.nvalid || (j == 15u && pos + 16u < n);
+        const bool rst2 = restart && prev == 255u && (b & 0xF8u) == 0xD0u;                // RSTm, second byte
+        const bool rst1 = restart && b == 255u && nx_exists && (nx & 0xF8u) == 0xD0u;     // RSTm, first byte
+        const bool drop = (b == 0u && prev == 255u) || rst1 || rst2;
+        if (exists && !drop) mask |= 1u << j;
+        if (exists && rst2) marks |= 1u << j;
         prev = b;
     }
     r.keep_mask = mask;
+    r.mark_mask = marks;
     return r;
 }
 
@@ -179,11 +244,22 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     const uint32_t lt = wg - D.tile0;
     const uint8_t* scan = P.scans + D.scan_off;
     const uint32_t pos = lt * (uint32_t)kUnstuffTile + threadIdx.x * 16u;
-    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos);
+    const bool restart = D.restart != 0u;
+    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos, restart);
     uint32_t removed = u.nvalid - (uint32_t)__popc(u.keep_mask);
     uint32_t total;
     wg_excl_scan(removed, scratch, &total);
     if (threadIdx.x == 0) P.tile_cnt[wg] = total;
+    if (restart) {
+        // this tile's share of the interval-start bitmap is cleared here, the scatter kernel sets the bits;
+        // the markers are counted so that the write pass can tell whether all intervals are there
+        uint32_t* bm = P.bmap + D.bmap_off + lt * 128u;
+        if (threadIdx.x < 128u) bm[threadIdx.x] = 0u;
+        if (lt == D.ntiles - 1u && threadIdx.x < 128u) bm[128u + threadIdx.x] = 0u;
+        uint32_t marks;
+        wg_excl_scan((uint32_t)__popc(u.mark_mask), scratch, &marks);
+        if (threadIdx.x == 0 && marks) atomicAdd(&P.st[ii].markers, marks);
+    }
 }
 
 // one workgroup per image: per-tile counts -> bytes removed before each tile; unstuffed length and
@@ -220,10 +296,11 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     const uint8_t* scan = P.scans + D.scan_off;
     uint8_t* out = P.stream + D.stream_off;
     const uint32_t pos = lt * (uint32_t)kUnstuffTile + threadIdx.x * 16u;
-    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos);
+    UnstuffLane u = unstuff_load(scan, D.scan_bytes, pos, D.restart != 0u);
     uint32_t kept = (uint32_t)__popc(u.keep_mask);
     uint32_t T;
     uint32_t off = wg_excl_scan(kept, scratch, &T);
+    const uint32_t lane_off = off;
 #pragma unroll
     for (uint32_t j = 0; j < 16u; ++j)
         if (u.keep_mask & (1u << j)) buf[off++] = (uint8_t)(u.bytes[j >> 2] >> (8u * (j & 3u)));
@@ -260,6 +337,15 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
                 int32_t s = s0 + b;
                 if (s >= 0 && (uint32_t)s < T) out[o - a + 4u * d + (uint32_t)b] = buf[s];
             }
+        }
+    }
+    // the byte after a restart marker starts an interval: its position in the output goes into the bitmap
+    if (u.mark_mask) {
+        uint32_t* bm = P.bmap + D.bmap_off;
+        for (uint32_t m = u.mark_mask; m; m &= m - 1u) {
+            const uint32_t j = (uint32_t)__ffs((int)m) - 1u;
+            const uint32_t at = o + lane_off + (uint32_t)__popc(u.keep_mask & ((1u << j) - 1u));
+            atomicOr(&bm[at >> 5], 1u << (at & 31u));
         }
     }
     // the last tile clears what lanes may read past the end: one subsequence plus 64 bytes
@@ -307,6 +393,12 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
+    // scans with restart intervals: the bitmap of interval starts, for the bytes staged above
+    const bool restart = D.restart != 0u;
+    uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
+    const uint32_t bm_k0 = first_word >> 3;
+    if (restart) stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
+    auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
     __syncthreads();
 
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
@@ -323,9 +415,11 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
         prime(l, w, sx, lut_s);
         const uint32_t limit = (i + 1u) << P.logL;
-        decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
+        uint32_t crossed = 0u;
+        if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
+        else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         sw[t] = pack_state(l.p - limit, l.z, l.u);
-        pnb[t] = l.nb;
+        pnb[t] = l.nb | (crossed << 31);
         pdc01[t] = pack_dc01(dcacc);
         pdc2[t] = pack_dc2(dcacc);
     }
@@ -372,11 +466,13 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
             l.nb = 0u;
             dcacc = 0;
             const uint32_t limit = ((uint32_t)(base + (int32_t)tt) + 1u) << P.logL;
-            decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
+            uint32_t crossed = 0u;
+            if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
+            else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
             const uint32_t x = pack_state(l.p - limit, l.z, l.u);
             const bool synced = x == sw[tt];
             sw[tt] = x;
-            pnb[tt] = l.nb;
+            pnb[tt] = l.nb | (crossed << 31);
             pdc01[tt] = pack_dc01(dcacc);
             pdc2[tt] = pack_dc2(dcacc);
             ++tt;
@@ -412,6 +508,8 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     const uint32_t gend = min(nsub, g + P.seq_len);
     const uint32_t* words = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off);
     auto fetch = [&](uint32_t w) { return __builtin_bswap32(words[w]); };
+    const uint32_t* bmap_img = P.bmap + D.bmap_off;
+    auto bword = [&](uint32_t k) { return bmap_img[k]; };
     SInfo* rec = P.sinfo + D.sub0;
     const uint32_t x0 = rec[g - 1u].x;
     Lane l;
@@ -426,10 +524,12 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
         l.nb = 0u;
         int64_t dcacc = 0;
         const uint32_t limit = (g + 1u) << P.logL;
-        decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
+        uint32_t crossed = 0u;
+        if (D.restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
+        else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         SInfo r;
         r.x = pack_state(l.p - limit, l.z, l.u);
-        r.y = l.nb;
+        r.y = l.nb | (crossed << 31);
         r.z = pack_dc01(dcacc);
         r.w = pack_dc2(dcacc);
         const bool synced = r.x == rec[g].x;
@@ -445,10 +545,8 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
 // Level 1: totals of each group of kWG records.  Level 2: one workgroup per image scans the image's
 // group totals.  Level 3 (inside the write kernel): scan within the group.
 
-__device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
-
 __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
-    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
+    __shared__ uint32_t scratch[20];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
     const ImgDesc D = image_desc(P, ii);
@@ -456,28 +554,26 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
     const uint32_t i = (wg - D.grp0) * kWG + threadIdx.x;
     SInfo r = {0u, 0u, 0u, 0u};
     if (i < nsub) r = P.sinfo[D.sub0 + i];
-    uint4 tot;
-    wg_excl_scan4(make_uint4(r.y, (uint32_t)sx16(r.z), (uint32_t)sx16(r.z >> 16), (uint32_t)sx16(r.w)), scratch, &tot);
-    if (threadIdx.x == 0) P.grp_tot[wg] = make_int4((int)tot.x, (int)tot.y, (int)tot.z, (int)tot.w);
+    Seg tot;
+    wg_excl_segscan(seg_of_record(r), scratch, &tot);
+    if (threadIdx.x == 0) P.grp_tot[wg] = seg_pack(tot);
 }
 
 // one workgroup per image: exclusive prefix of the group totals
 __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
-    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
+    __shared__ uint32_t scratch[20];
     const uint32_t ii = blockIdx.x;
     const ImgDesc D = image_desc(P, ii);
     if (D.ngrp_max <= (uint32_t)kWG) return;  // images of up to 256 groups: the write kernel sums the totals itself
     const uint32_t ngrp = (P.st[ii].nsub + kWG - 1u) / kWG;
-    uint32_t carry[4] = {0u, 0u, 0u, 0u};
+    Seg carry = seg_zero();
     for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
         uint32_t k = b0 + threadIdx.x;
-        int4 v = k < ngrp ? P.grp_tot[D.grp0 + k] : make_int4(0, 0, 0, 0);
-        uint4 ct;
-        const uint4 e = wg_excl_scan4(make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w), scratch, &ct);
-        if (k < ngrp)
-            P.grp_pref[D.grp0 + k] = make_int4((int)(carry[0] + e.x), (int)(carry[1] + e.y), (int)(carry[2] + e.z),
-                                               (int)(carry[3] + e.w));
-        carry[0] += ct.x; carry[1] += ct.y; carry[2] += ct.z; carry[3] += ct.w;
+        const Seg v = k < ngrp ? seg_unpack(P.grp_tot[D.grp0 + k]) : seg_zero();
+        Seg ct;
+        const Seg e = wg_excl_segscan(v, scratch, &ct);
+        if (k < ngrp) P.grp_pref[D.grp0 + k] = seg_pack(seg_join(carry, e));
+        carry = seg_join(carry, ct);
     }
 }
 
@@ -486,7 +582,7 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
 template <bool STAGED>
 __global__ __launch_bounds__(kWG) void k_write(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
-    __shared__ __attribute__((aligned(16))) uint32_t scratch[16];
+    __shared__ uint32_t scratch[20];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.grp0; });
     const ImgDesc D = image_desc(P, ii);
@@ -505,6 +601,11 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
+    const bool restart = D.restart != 0u;
+    uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
+    const uint32_t bm_k0 = first_word >> 3;
+    if (restart) stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
+    auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
 
     const uint32_t t = threadIdx.x;
     const uint32_t i = i0 + t;
@@ -518,23 +619,18 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     }
     // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
     // plus the group's prefix
-    int4 gp;
+    Seg gp;
     if (D.ngrp_max <= (uint32_t)kWG) {
-        const int4 v = (t < lg) ? P.grp_tot[D.grp0 + t] : make_int4(0, 0, 0, 0);
-        uint4 g;
-        wg_excl_scan4(make_uint4((uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w), scratch, &g);
-        gp = make_int4((int)g.x, (int)g.y, (int)g.z, (int)g.w);
+        const Seg v = (t < lg) ? seg_unpack(P.grp_tot[D.grp0 + t]) : seg_zero();
+        wg_excl_segscan(v, scratch, &gp);
     } else {
-        gp = P.grp_pref[wg];
+        gp = seg_unpack(P.grp_pref[wg]);
     }
-    uint4 grp_tot;
-    const uint4 ex = wg_excl_scan4(make_uint4(mine.y, (uint32_t)sx16(mine.z), (uint32_t)sx16(mine.z >> 16), (uint32_t)sx16(mine.w)),
-                                   scratch, &grp_tot);
-    const uint32_t grp_units = grp_tot.x;
-    uint32_t unit = (uint32_t)gp.x + ex.x;
-    int32_t pred0 = gp.y + (int32_t)ex.y;
-    int32_t pred1 = gp.z + (int32_t)ex.z;
-    int32_t pred2 = gp.w + (int32_t)ex.w;
+    Seg grp_tot;
+    const Seg ex = seg_join(gp, wg_excl_segscan(seg_of_record(mine), scratch, &grp_tot));
+    const uint32_t grp_units = grp_tot.units;
+    uint32_t unit = ex.units;
+    int32_t pred0 = ex.d0, pred1 = ex.d1, pred2 = ex.d2;
 
     // The group clears the coefficients it is about to fill: those from where its first subsequence takes
     // over (data unit and zig-zag index) to where the next group's does; the last group goes on to the end of
@@ -543,8 +639,8 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
         const uint64_t end_all = (uint64_t)D.total_units * 64u;
         const uint32_t x_in = i0 > 0u ? rec[i0 - 1u].x : 0u;
         const uint32_t x_out = rec[i0 + nloc - 1u].x;
-        uint64_t a = (uint64_t)(uint32_t)gp.x * 64u + state_z(x_in);
-        uint64_t b = i0 + nloc >= nsub ? end_all : ((uint64_t)(uint32_t)gp.x + grp_units) * 64u + state_z(x_out);
+        uint64_t a = (uint64_t)gp.units * 64u + state_z(x_in);
+        uint64_t b = i0 + nloc >= nsub ? end_all : ((uint64_t)gp.units + grp_units) * 64u + state_z(x_out);
         if (i0 == 0u) a = 0u;
         if (b > end_all) b = end_all;
         if (a < b) {
@@ -581,8 +677,11 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     if (unit < total) {
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
         prime(l, w, sx, lut_s);
-        decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
+        if (restart) decode_span_write_rst(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags, bword);
+        else decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
+    // all restart markers must have been there (the first lane of the image speaks for it)
+    if (restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
     // every lane checks the chain: unless the image is complete it must end in the recorded state
     if (unit < total) {
         if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;

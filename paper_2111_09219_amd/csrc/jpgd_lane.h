@@ -183,53 +183,185 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
     return s;
 }
 
-// Synchronisation pass (write = false in Algorithm 2): decode while the next symbol starts before
-// `limit`, keeping the state, the count of completed units and the per-component DC sums.
-// The lane must have been primed.
+// One symbol of the synchronisation pass (write = false in Algorithm 2): state, count of completed units
+// (inside step_and_request) and the per-component sums of DC differences.
+template <class Fetch, class LutPtr>
+JPGD_HD void sync_symbol(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& sx, Fetch fetch, LutPtr lut) {
+    const uint32_t dcmul = l.row.dcmul;
+    const Step s = step_and_request(l, w, sx, fetch, lut);
+    const int32_t v = symbol_value(s.peek, s.total, s.size);
+    const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
+    dcacc += (int64_t)v * (int64_t)mul;
+}
+
+// Synchronisation pass: decode while the next symbol starts before `limit`.  The lane must have been primed.
 template <class Fetch, class LutPtr>
 JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
                               LutPtr lut) {
     const uint32_t stop = win_stop(w, limit);
-    while (w.next < stop) {
-        const uint32_t dcmul = l.row.dcmul;
-        const Step s = step_and_request(l, w, sx, fetch, lut);
-        const int32_t v = symbol_value(s.peek, s.total, s.size);
-        const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
-        dcacc += (int64_t)v * (int64_t)mul;
-    }
+    while (w.next < stop) sync_symbol(l, w, dcacc, sx, fetch, lut);
     l.p = win_pos(w);
 }
 
-// Write pass (write = true in Algorithm 2): the same walk, storing every non-zero coefficient at
-// 64*unit + zig-zag index, DC values un-differenced.  `unit` is the index of the data unit being
-// decoded, `total_units` the end of the image, pred0..2 the DC predictors; `flags` collects kSt* bits.
+// One symbol of the write pass (write = true in Algorithm 2): every non-zero coefficient goes to
+// 64*unit + zig-zag index, DC values un-differenced.  `unit` is the index of the data unit being decoded,
+// pred0..2 the DC predictors; `flags` collects kSt* bits.  Without branches except around the store itself:
+// a wavefront holds lanes in every kind of symbol at once, so each arm of a branch would be walked anyway.
+template <class Fetch, class LutPtr, class Store>
+JPGD_HD void write_symbol(Lane& l, BitWin& w, uint32_t& unit, int32_t& pred0, int32_t& pred1, int32_t& pred2,
+                          const Syntax& sx, Fetch fetch, LutPtr lut, Store store, uint32_t& flags) {
+    const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
+    const Step s = step_and_request(l, w, sx, fetch, lut);
+    const int32_t value = symbol_value(s.peek, s.total, s.size);  // 0 for an escape
+    const bool real = !s.esc;
+    const bool dc = s.is_dc && real;
+    const int32_t pred = (comp0 ? pred0 : (comp1 ? pred1 : pred2)) + value;
+    pred0 = dc && comp0 ? pred : pred0;
+    pred1 = dc && comp1 ? pred : pred1;
+    pred2 = dc && !comp0 && !comp1 ? pred : pred2;
+    // where the symbol ends: a coefficient sits in the last slot it covers (after its run of zeros)
+    const uint32_t zn = s.z + s.adv;
+    const uint32_t at = dc ? 0u : zn - 1u;
+    const bool has_value = dc || s.size != 0u;  // a DC symbol of size 0 still yields the predictor
+    if (real && s.adv != 0u && has_value && at < 64u) store(unit, at, (int16_t)(dc ? pred : value));
+    // no codeword starts with these bits; or a coefficient or a run of sixteen zeros (not end-of-block,
+    // which may be coded anywhere) that runs past the end of the unit
+    const bool bad = real && (s.adv == 0u || (zn > 64u && s.adv != kAdvEob));
+    flags |= bad ? kStInvalid : 0u;
+    unit += s.done ? 1u : 0u;
+}
+
+// Write pass: the same walk as the synchronisation pass, up to the image's last data unit.
 template <class Fetch, class LutPtr, class Store>
 JPGD_HD void decode_span_write(Lane& l, BitWin& w, uint32_t limit, uint32_t& unit, uint32_t total_units,
                                int32_t& pred0, int32_t& pred1, int32_t& pred2, const Syntax& sx, Fetch fetch,
                                LutPtr lut, Store store, uint32_t& flags) {
-    // Without branches except around the store itself: a wavefront holds lanes in every kind of symbol at
-    // once, so each arm of a branch would be walked anyway.
     const uint32_t stop = win_stop(w, limit);
-    while (w.next < stop && unit < total_units) {
-        const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
-        const Step s = step_and_request(l, w, sx, fetch, lut);
-        const int32_t value = symbol_value(s.peek, s.total, s.size);  // 0 for an escape
-        const bool real = !s.esc;
-        const bool dc = s.is_dc && real;
-        const int32_t pred = (comp0 ? pred0 : (comp1 ? pred1 : pred2)) + value;
-        pred0 = dc && comp0 ? pred : pred0;
-        pred1 = dc && comp1 ? pred : pred1;
-        pred2 = dc && !comp0 && !comp1 ? pred : pred2;
-        // where the symbol ends: a coefficient sits in the last slot it covers (after its run of zeros)
-        const uint32_t zn = s.z + s.adv;
-        const uint32_t at = dc ? 0u : zn - 1u;
-        const bool has_value = dc || s.size != 0u;  // a DC symbol of size 0 still yields the predictor
-        if (real && s.adv != 0u && has_value && at < 64u) store(unit, at, (int16_t)(dc ? pred : value));
-        // no codeword starts with these bits; or a coefficient or a run of sixteen zeros (not end-of-block,
-        // which may be coded anywhere) that runs past the end of the unit
-        const bool bad = real && (s.adv == 0u || (zn > 64u && s.adv != kAdvEob));
-        flags |= bad ? kStInvalid : 0u;
-        unit += s.done ? 1u : 0u;
+    while (w.next < stop && unit < total_units) write_symbol(l, w, unit, pred0, pred1, pred2, sx, fetch, lut, store, flags);
+    l.p = win_pos(w);
+}
+
+// ---- restart intervals -------------------------------------------------------------------------------
+// A scan with restart intervals (DRI) is a chain of independently coded intervals: each ends with up to seven
+// 1-bits of padding and a marker RSTm, and the next starts byte-aligned with the DC predictors at zero.  The
+// unstuff kernels drop the markers and mark the first byte of every interval in a bitmap (one bit per byte
+// of the unstuffed stream; bit b of word k stands for byte 32k + b).  The paper does not treat restart
+// markers.  The rules below are stated on positions alone, so that a decoder in any state obeys them, and on
+// the synchronised chain they are what a sequential decoder does:
+//   * after a symbol, if the next interval starts at most 7 bits further on and those bits are all 1, or if
+//     the symbol ran past that start, the decoder moves to the start with z = 0 and u = 0 (a real symbol
+//     never consists of 1-bits only: the all-ones codeword is reserved);
+//   * a symbol that starts at the first bit of an interval finds the DC sums / predictors at zero.
+// Every decoder is therefore synchronised from the next interval on, whatever it did before.
+
+constexpr uint32_t kNoBoundary = 0xFFFFFFFFu;
+
+// first bit position B >= from_bit, B < end_bit, at which an interval starts; bword(k) = word k of the bitmap
+template <class BWord>
+JPGD_HD uint32_t next_boundary(uint32_t from_bit, uint32_t end_bit, BWord bword) {
+    const uint32_t byte = (from_bit + 7u) >> 3, endb = (end_bit + 7u) >> 3;
+    if (byte >= endb) return kNoBoundary;
+    uint32_t k = byte >> 5;
+    uint32_t m = bword(k) & (0xFFFFFFFFu << (byte & 31u));
+    for (;;) {
+        if (m) {
+            const uint32_t b = (k << 5) + (uint32_t)__builtin_ctz(m);
+            return b < endb ? b << 3 : kNoBoundary;
+        }
+        ++k;
+        if ((k << 5) >= endb) return kNoBoundary;
+        m = bword(k);
+    }
+}
+
+// the window moves to bit B (a multiple of 8) and the decoder starts a fresh MCU there
+template <class Fetch, class LutPtr>
+JPGD_HD void move_to_interval(Lane& l, BitWin& w, uint32_t B, const Syntax& sx, Fetch fetch, LutPtr lut) {
+    l.z = 0u;
+    l.u = 0u;
+    win_init(w, B, (B - w.origin) >> 5, fetch);
+    prime(l, w, sx, lut);
+}
+
+// after a symbol: has the decoder reached the padding in front of the interval that starts at B, or passed B?
+JPGD_HD bool at_interval_end(const BitWin& w, uint32_t pos, uint32_t B) {
+    if (pos >= B) return true;
+    const uint32_t r = B - pos;
+    return r <= 7u && (~w.peek >> (32u - r)) == 0u;
+}
+
+// Synchronisation pass over a stream with restart intervals.  `crossed` is set when a symbol of this span
+// started an interval (dcacc then holds the sums since the last such symbol).
+template <class Fetch, class LutPtr, class BWord>
+JPGD_HD void decode_span_sync_rst(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, uint32_t& crossed, const Syntax& sx,
+                                  Fetch fetch, LutPtr lut, BWord bword) {
+    uint32_t from = win_pos(w);
+    for (;;) {
+        const uint32_t B = next_boundary(from, limit + 64u, bword);
+        // a symbol that starts before `calm` ends more than 7 bits before B: nothing to check on the way there
+        uint32_t calm = limit;
+        if (B != kNoBoundary) {
+            const uint32_t c = B >= 40u ? (B - 39u) & ~31u : 0u;
+            calm = c < limit ? c : limit;
+        }
+        const uint32_t stop = calm > w.origin ? win_stop(w, calm) : 0u;
+        while (w.next < stop) sync_symbol(l, w, dcacc, sx, fetch, lut);
+        if (B == kNoBoundary) break;
+        uint32_t pos = win_pos(w);
+        bool next_interval = false;
+        while (pos < limit) {
+            if (pos == B) {  // this symbol starts the interval
+                dcacc = 0;
+                crossed = 1u;
+                from = B + 1u;
+                next_interval = true;
+                break;
+            }
+            sync_symbol(l, w, dcacc, sx, fetch, lut);
+            pos = win_pos(w);
+            if (at_interval_end(w, pos, B)) {
+                move_to_interval(l, w, B, sx, fetch, lut);
+                pos = B;
+            }
+        }
+        if (!next_interval) break;
+    }
+    l.p = win_pos(w);
+}
+
+// Write pass over a stream with restart intervals: the predictors return to zero where an interval starts.
+template <class Fetch, class LutPtr, class Store, class BWord>
+JPGD_HD void decode_span_write_rst(Lane& l, BitWin& w, uint32_t limit, uint32_t& unit, uint32_t total_units,
+                                   int32_t& pred0, int32_t& pred1, int32_t& pred2, const Syntax& sx, Fetch fetch,
+                                   LutPtr lut, Store store, uint32_t& flags, BWord bword) {
+    uint32_t from = win_pos(w);
+    for (;;) {
+        const uint32_t B = next_boundary(from, limit + 64u, bword);
+        uint32_t calm = limit;
+        if (B != kNoBoundary) {
+            const uint32_t c = B >= 40u ? (B - 39u) & ~31u : 0u;
+            calm = c < limit ? c : limit;
+        }
+        const uint32_t stop = calm > w.origin ? win_stop(w, calm) : 0u;
+        while (w.next < stop && unit < total_units) write_symbol(l, w, unit, pred0, pred1, pred2, sx, fetch, lut, store, flags);
+        if (B == kNoBoundary) break;
+        uint32_t pos = win_pos(w);
+        bool next_interval = false;
+        while (pos < limit && unit < total_units) {
+            if (pos == B) {
+                pred0 = pred1 = pred2 = 0;
+                from = B + 1u;
+                next_interval = true;
+                break;
+            }
+            write_symbol(l, w, unit, pred0, pred1, pred2, sx, fetch, lut, store, flags);
+            pos = win_pos(w);
+            if (at_interval_end(w, pos, B)) {
+                move_to_interval(l, w, B, sx, fetch, lut);
+                pos = B;
+            }
+        }
+        if (!next_interval) break;
     }
     l.p = win_pos(w);
 }

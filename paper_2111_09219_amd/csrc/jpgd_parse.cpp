@@ -120,7 +120,6 @@ extern "C" int jpgd_parse(const uint8_t* file, size_t len, jpgd_info* out) {
         pos += 2 + seglen;
     }
 
-    if (out->restart_interval != 0) return JPGD_E_UNSUPPORTED;
     if (out->ncomp == 1) {
         out->hsamp[0] = out->vsamp[0] = 1;  // a single component is never interleaved
     } else {

@@ -31,7 +31,8 @@ struct Image {
     uint32_t sched_dc = 0, sched_ac = 0, sched_comp = 0, nslots = 0;
     std::vector<uint16_t> lut;
     std::vector<uint8_t> stream;  // unstuffed + zero slack
-    uint32_t nbytes = 0, nsub = 0;
+    std::vector<uint32_t> bmap;   // restart intervals: one bit per unstuffed byte, set at the first byte of an interval
+    uint32_t nbytes = 0, nsub = 0, markers = 0;
 };
 
 int prepare(const uint8_t* file, size_t len, Image& im) {
@@ -68,21 +69,30 @@ int prepare(const uint8_t* file, size_t len, Image& im) {
 // the two unstuff kernels, tile by tile and lane by lane
 void unstuff(const uint8_t* scan, uint32_t n, uint32_t logL, Image& im) {
     const uint32_t tiles = (n + kUnstuffTile - 1) / kUnstuffTile;
+    const bool restart = im.in.restart_interval != 0;
     std::vector<uint32_t> removed(tiles, 0), before(tiles, 0);
-    auto keep_mask = [&](uint32_t pos, uint32_t& nvalid) {
+    auto keep_mask = [&](uint32_t pos, uint32_t& nvalid, uint32_t& marks) {
         nvalid = pos >= n ? 0u : std::min(16u, n - pos);
         uint32_t prev = (pos > 0 && nvalid) ? scan[pos - 1] : 0u, mask = 0;
+        marks = 0;
         for (uint32_t j = 0; j < nvalid; ++j) {
             uint32_t b = scan[pos + j];
-            if (!(b == 0 && prev == 255)) mask |= 1u << j;
+            bool nx_exists = pos + j + 1 < n;
+            uint32_t nx = nx_exists ? scan[pos + j + 1] : 0u;
+            bool rst2 = restart && prev == 255 && (b & 0xF8) == 0xD0;
+            bool rst1 = restart && b == 255 && nx_exists && (nx & 0xF8) == 0xD0;
+            if (!((b == 0 && prev == 255) || rst1 || rst2)) mask |= 1u << j;
+            if (rst2) marks |= 1u << j;
             prev = b;
         }
         return mask;
     };
+    im.markers = 0;
     for (uint32_t t = 0; t < tiles; ++t)
         for (uint32_t lane = 0; lane < (uint32_t)kWG; ++lane) {
-            uint32_t nv, m = keep_mask(t * kUnstuffTile + lane * 16, nv);
+            uint32_t nv, mk, m = keep_mask(t * kUnstuffTile + lane * 16, nv, mk);
             removed[t] += nv - (uint32_t)__builtin_popcount(m);
+            im.markers += (uint32_t)__builtin_popcount(mk);
         }
     uint32_t carry = 0;
     for (uint32_t t = 0; t < tiles; ++t) { before[t] = carry; carry += removed[t]; }
@@ -90,12 +100,15 @@ void unstuff(const uint8_t* scan, uint32_t n, uint32_t logL, Image& im) {
     const uint32_t L = 1u << logL;
     im.nsub = (uint32_t)(((uint64_t)im.nbytes * 8 + L - 1) >> logL);
     im.stream.assign((size_t)n + L / 8 + 64 + 16 + 256, 0xAA);  // poison: the kernels must define what they read
+    im.bmap.assign((size_t)tiles * 128 + 128, 0);
     for (uint32_t t = 0; t < tiles; ++t) {
         uint32_t o = t * kUnstuffTile - before[t];
         for (uint32_t lane = 0; lane < (uint32_t)kWG; ++lane) {
-            uint32_t pos = t * kUnstuffTile + lane * 16, nv, m = keep_mask(pos, nv);
-            for (uint32_t j = 0; j < nv; ++j)
+            uint32_t pos = t * kUnstuffTile + lane * 16, nv, mk, m = keep_mask(pos, nv, mk);
+            for (uint32_t j = 0; j < nv; ++j) {
+                if (mk & (1u << j)) im.bmap[o >> 5] |= 1u << (o & 31);  // the next kept byte starts an interval
                 if (m & (1u << j)) im.stream[o++] = scan[pos + j];
+            }
         }
     }
     for (uint32_t k = 0; k < L / 8 + 64; ++k) im.stream[im.nbytes + k] = 0;
@@ -128,6 +141,13 @@ void sync_intra(Emul& E) {
             if (c >= nwords) abort();  // a lane read outside the staged window
             return strm[c];
         };
+        // the part of the bitmap the kernel stages with these words
+        const bool restart = im.in.restart_interval != 0;
+        const uint32_t bm_k0 = first_word >> 3, bm_n = ((first_word + nwords + 7) >> 3) - bm_k0 + 1;
+        auto bword = [&](uint32_t k) {
+            if (k < bm_k0 || k - bm_k0 >= bm_n) abort();  // a lane looked outside the staged bitmap
+            return im.bmap[k];
+        };
         uint32_t sw[kWG], pnb[kWG], pdc01[kWG], pdc2[kWG];
         Lane l[kWG];
         BitWin bw[kWG];
@@ -143,9 +163,11 @@ void sync_intra(Emul& E) {
             win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);
             prime(l[t], bw[t], E.sx, im.lut.data());
             uint32_t limit = (i + 1) << logL;
-            decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
+            uint32_t crossed = 0;
+            if (restart) decode_span_sync_rst(l[t], bw[t], limit, dcacc[t], crossed, E.sx, fetch, im.lut.data(), bword);
+            else decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
             sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u);
-            pnb[t] = l[t].nb;
+            pnb[t] = l[t].nb | (crossed << 31);
             pdc01[t] = pack_dc01(dcacc[t]);
             pdc2[t] = pack_dc2(dcacc[t]);
             active[t] = t + 1 < t1;
@@ -164,10 +186,12 @@ void sync_intra(Emul& E) {
                 win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);  // a chain moved to another lane restarts its window
                 prime(l[t], bw[t], E.sx, im.lut.data());
                 uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
-                decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
+                uint32_t crossed = 0;
+                if (restart) decode_span_sync_rst(l[t], bw[t], limit, dcacc[t], crossed, E.sx, fetch, im.lut.data(), bword);
+                else decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
                 uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u);
                 bool synced = x == sw[tt[t]];
-                sw[tt[t]] = x; pnb[tt[t]] = l[t].nb;
+                sw[tt[t]] = x; pnb[tt[t]] = l[t].nb | (crossed << 31);
                 pdc01[tt[t]] = pack_dc01(dcacc[t]);
                 pdc2[tt[t]] = pack_dc2(dcacc[t]);
                 ++tt[t];
@@ -187,6 +211,8 @@ void sync_inter(Emul& E) {
     const uint32_t nsub = im.nsub, logL = E.logL;
     const uint32_t* words = (const uint32_t*)im.stream.data();
     auto fetch = [&](uint32_t w) { return bswap(words[w]); };
+    auto bword = [&](uint32_t k) { return im.bmap[k]; };
+    const bool restart = im.in.restart_interval != 0;
     E.inter_changed = 0;
     for (uint32_t b = 0;; ++b) {
         uint64_t gfirst = (uint64_t)(b + 1) * E.seq_len;
@@ -203,8 +229,10 @@ void sync_inter(Emul& E) {
             l.nb = 0;
             int64_t dcacc = 0;
             uint32_t limit = (g + 1) << logL;
-            decode_span_sync(l, w, limit, dcacc, E.sx, fetch, im.lut.data());
-            SInfo r = {pack_state(l.p - limit, l.z, l.u), l.nb, pack_dc01(dcacc), pack_dc2(dcacc)};
+            uint32_t crossed = 0;
+            if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, E.sx, fetch, im.lut.data(), bword);
+            else decode_span_sync(l, w, limit, dcacc, E.sx, fetch, im.lut.data());
+            SInfo r = {pack_state(l.p - limit, l.z, l.u), l.nb | (crossed << 31), pack_dc01(dcacc), pack_dc2(dcacc)};
             bool synced = r.x == E.sinfo[g].x;
             if (first && !synced) E.inter_changed++;
             first = false;
@@ -240,9 +268,15 @@ void scan_and_write(Emul& E, int16_t* coef) {
             if (k >= total || at > 63) abort();
             coef[(size_t)k * 64 + at] = v;
         };
+        const bool restart = im.in.restart_interval != 0;
+        const uint32_t bm_k0 = first_word >> 3, bm_n = ((first_word + nwords + 7) >> 3) - bm_k0 + 1;
+        auto bword = [&](uint32_t k) {
+            if (k < bm_k0 || k - bm_k0 >= bm_n) abort();
+            return im.bmap[k];
+        };
         {
             uint32_t grp_units = 0;
-            for (uint32_t t = 0; t < nloc; ++t) grp_units += E.sinfo[i0 + t].y;
+            for (uint32_t t = 0; t < nloc; ++t) grp_units += rec_units(E.sinfo[i0 + t].y);
             const uint64_t end_all = (uint64_t)total * 64;
             const uint32_t x_in = i0 ? E.sinfo[i0 - 1].x : 0u, x_out = E.sinfo[i0 + nloc - 1].x;
             uint64_t a = (uint64_t)unit0 * 64 + state_z(x_in);
@@ -269,15 +303,21 @@ void scan_and_write(Emul& E, int16_t* coef) {
             if (unit < total) {
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
                 prime(l, w, E.sx, im.lut.data());
-                decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
+                if (restart) decode_span_write_rst(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags, bword);
+                else decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
+            }
+            if (restart && i == 0) {
+                const uint64_t mcus = (uint64_t)im.in.mcus_x * im.in.mcus_y;
+                if (im.markers != (uint32_t)((mcus + im.in.restart_interval - 1) / im.in.restart_interval) - 1) flags |= kStInvalid;
             }
             if (unit < total) {
                 if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;
                 if (i == nsub - 1) flags |= kStShort;
             }
             E.flags |= flags;
-            // exclusive scan, lane by lane
-            unit0 += mine.y;
+            // exclusive scan, lane by lane; the DC sums start afresh after a subsequence in which an interval began
+            unit0 += rec_units(mine.y);
+            if (rec_restarted(mine.y)) pred[0] = pred[1] = pred[2] = 0;
             pred[0] += sx16(mine.z); pred[1] += sx16(mine.z >> 16); pred[2] += sx16(mine.w);
         }
     }

@@ -96,6 +96,55 @@ def test_sync_records_are_the_sequential_decoder_states():
         assert np.array_equal(rec["dcsum"][live].astype(np.int16), bs["dcsum"][live].astype(np.int16))
 
 
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_restart_intervals_all_layouts(sub):
+    """Scans with restart intervals (DRI / RSTm): one MCU per interval up to one interval for the whole
+    image, standard and optimised tables, every subsequence size, with and without sequence overlap."""
+    for seed, (h, w), q, opt in [(5, (37, 51), 85, False), (6, (200, 333), 94, True), (7, (129, 70), 60, False)]:
+        px = small_image(seed, h, w, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+        for ri in (1, 2, 5, 21, 100000):
+            data = encode_jpeg(px, q, sub, opt, restart_interval=ri).data
+            for L, H in [(128, 0), (128, 32), (512, 16), (1024, 0), (2048, 8)]:
+                batch, rep = _decode([data], subseq_bits=L, overlap=H)
+                _check_image(batch, 0, data)
+
+
+def test_restart_sync_records_and_mixed_batch():
+    """s_info of a scan with restart intervals (state never inside padding, restart flag, DC sums counted
+    from the interval start), and a batch that mixes images with and without restart intervals."""
+    px = small_image(33, 480, 640, sigma=12.0)
+    data = encode_jpeg(px, 93, "420", False, restart_interval=40).data       # one MCU row per interval
+    for L in (128, 1024):
+        batch, rep = _decode([data], subseq_bits=L)
+        _check_image(batch, 0, data)
+        rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
+        o = OracleImage(data)
+        bs = o.boundary_states(L)
+        live = np.cumsum(bs["units"]) < o.total_units
+        assert np.array_equal(rec["p"][live].astype(np.int64), bs["p"][live])
+        assert np.array_equal(rec["u"][live], bs["u"][live]) and np.array_equal(rec["z"][live], bs["z"][live])
+        assert np.array_equal(rec["units"][live], bs["units"][live])
+        assert np.array_equal(rec["restart"][live], bs["restart"][live])
+        assert np.array_equal(rec["dcsum"][live].astype(np.int16), bs["dcsum"][live].astype(np.int16))
+    files = [encode_jpeg(small_image(41, 96, 128), 80, "420", restart_interval=3).data,
+             encode_jpeg(small_image(42, 64, 200), 90, "444", True).data,
+             encode_jpeg(small_image(43, 130, 90), 70, "422", restart_interval=1).data,
+             encode_jpeg(small_image(44, 40, 40, ncomp=1), 95, restart_interval=5).data,
+             encode_jpeg(small_image(45, 256, 256, sigma=20), 97, "420", True, restart_interval=16).data]
+    for L in (256, 1024):
+        batch, rep = _decode(files, subseq_bits=L)
+        for i, f in enumerate(files):
+            _check_image(batch, i, f)
+    # a missing marker (two intervals fused) must be reported, not decoded silently
+    enc = encode_jpeg(small_image(46, 64, 64), 85, "444", restart_interval=4)
+    raw = bytearray(enc.data.tobytes())
+    k = raw.index(b"\xFF\xD1")
+    del raw[k:k + 2]
+    with pytest.raises(J.JpgdError) as e:
+        _decode([np.frombuffer(bytes(raw), np.uint8).copy()])
+    assert e.value.name == "CORRUPT"
+
+
 def test_unstuff_kernel_alone():
     import torch
     rng = np.random.default_rng(9)

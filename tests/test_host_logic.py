@@ -94,7 +94,7 @@ def test_parse_rejections():
     Image.fromarray(small_image(3, 24, 24)).save(prog, "JPEG", progressive=True)
     _expect(np.frombuffer(prog.getvalue(), np.uint8), "UNSUPPORTED")
     rst = encode_jpeg(small_image(3, 24, 24), quality=80, subsampling="420", restart_interval=2).data
-    _expect(rst, "UNSUPPORTED")
+    assert J.jpgd_parse(rst).restart_interval == 2       # restart intervals are part of the accepted subset
     q = [1] * 64
     std_dc = ([0, 1, 5, 1, 1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0, 0], list(range(12)))
     ac = ([0, 2] + [0] * 14, [0, 1])
@@ -263,6 +263,34 @@ def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H):
     assert np.array_equal(sinfo[keep, 1], bs["units"][keep])
     dc0 = (sinfo[:, 2] & 0xFFFF).astype(np.uint16).view(np.int16)
     assert np.array_equal(dc0[keep], bs["dcsum"][keep, 0].astype(np.int16))
+
+
+@pytest.mark.parametrize("sub,opt,q,shape", CASES)
+@pytest.mark.parametrize("L,H,ri", [(128, 0, 1), (128, 16, 3), (256, 0, 2), (1024, 32, 1), (1024, 0, 7), (512, 16, 1000)])
+def test_host_walkthrough_with_restart_intervals(emul, sub, opt, q, shape, L, H, ri):
+    """Scans with restart intervals: markers leave the stream, every interval start is marked, decoders of
+    any state fall into step at the next interval, DC sums and predictors start afresh there."""
+    px = small_image(19, *shape, ncomp=1 if sub == "gray" else 3, sigma=11.0)
+    data = encode_jpeg(px, q, sub, opt, restart_interval=ri).data
+    rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
+    assert rc == 0 and stats[3] == 0
+    assert o.restart_interval == ri
+    assert np.array_equal(stream, o.unstuffed())
+    ref = o.coefficients()
+    assert np.array_equal(coef, ref)
+    refpix = o.pixels(ref).reshape(pix.shape).astype(int)
+    assert np.abs(pix.astype(int) - refpix).max() <= 1
+    bs = o.boundary_states(L)
+    n = len(bs["p"])
+    assert n == len(sinfo)
+    keep = ~(np.cumsum(bs["units"]) >= o.total_units)
+    x = sinfo[:, 0]
+    assert np.array_equal(((np.arange(n) + 1) * L + (x & 63))[keep], bs["p"][keep])
+    assert np.array_equal(((x >> 6) & 63)[keep], bs["z"][keep]) and np.array_equal((x >> 12)[keep], bs["u"][keep])
+    assert np.array_equal((sinfo[:, 1] & 0x7FFFFFFF)[keep], bs["units"][keep])
+    assert np.array_equal((sinfo[:, 1] >> 31)[keep], bs["restart"][keep])
+    for c, col in ((0, sinfo[:, 2] & 0xFFFF), (1, sinfo[:, 2] >> 16), (2, sinfo[:, 3] & 0xFFFF)):
+        assert np.array_equal(col.astype(np.uint16).view(np.int16)[keep], bs["dcsum"][keep, c].astype(np.int16))
 
 
 def test_host_walkthrough_dense_ff_and_tiny_streams(emul):
