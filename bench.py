@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=-1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing; 0 skips it")
     ap.add_argument("--limit", type=int, default=0, help="images of the batch config to use (0 = all)")
+    ap.add_argument("--restart-interval", type=int, default=0, metavar="MCUS",
+                    help="encode the workload with restart markers every MCUS MCUs (-1 = one MCU row); the "
+                         "configurations themselves have none")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of decoding, run plain device copies of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -92,7 +95,11 @@ def main() -> int:
 
     c = args.config
     wl = CONFIGS[c]
-    enc = config_jpeg(c, limit=args.limit or None) if c == 4 else config_jpeg(c)
+    ri = args.restart_interval
+    if ri < 0:
+        mcu_w = 8 if wl["subsampling"] in ("gray", "444") else 16
+        ri = (wl["width"] + mcu_w - 1) // mcu_w
+    enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri) if c == 4 else config_jpeg(c, restart_interval=ri)
     files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
     cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap)
     batch = J.prepare_batch(files, cfg, device="cuda:0")
@@ -192,12 +199,12 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "configs[%d] %s: %d image(s) %dx%d %s q%s%s, %d compressed bytes" % (
             c - 1, wl["name"], len(files), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
-            " optimized Huffman" if wl["optimize"] else "", Bs),
+            (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % ri if ri else ""), Bs),
             "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
             "inter_rounds": rep.inter_rounds, "redo": rep.redo},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not args.subseq_bits else None,
+                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri) else None,
                      "avg_launch_ms": round(dom_avg_ms, 5), "timed_launches": dom_launches,
                      "alg_bytes_per_launch": alg},
         "cpu_baseline": cpu,

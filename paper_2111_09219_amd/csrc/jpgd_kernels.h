@@ -175,10 +175,18 @@ __device__ __forceinline__ void stage_stream(const uint8_t* stream_img, uint32_t
 
 // LDS copy of the part of an image's interval-start bitmap that covers stream words first_word .. +nwords;
 // word k of the bitmap is then bm_s[k - (first_word >> 3)]
-__device__ __forceinline__ void stage_bitmap(const uint32_t* bmap_img, uint32_t first_word, uint32_t nwords, uint32_t* bm_s) {
+// Returns the OR of the words this lane copied: most workgroups of a scan with long intervals find no interval
+// start at all in their stretch and can run the plain loops.
+__device__ __forceinline__ uint32_t stage_bitmap(const uint32_t* bmap_img, uint32_t first_word, uint32_t nwords, uint32_t* bm_s) {
     const uint32_t k0 = first_word >> 3;
     const uint32_t n = ((first_word + nwords + 7u) >> 3) - k0 + 1u;
-    for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) bm_s[k] = bmap_img[k0 + k];
+    uint32_t seen = 0u;
+    for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) {
+        const uint32_t v = bmap_img[k0 + k];
+        bm_s[k] = v;
+        seen |= v;
+    }
+    return seen;
 }
 
 __device__ __forceinline__ uint32_t pack_dc01(int64_t acc) {
@@ -394,12 +402,12 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
     // scans with restart intervals: the bitmap of interval starts, for the bytes staged above
-    const bool restart = D.restart != 0u;
     uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
     const uint32_t bm_k0 = first_word >> 3;
-    if (restart) stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
+    uint32_t seen = 0u;
+    if (D.restart) seen = stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
     auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
-    __syncthreads();
+    const bool restart = __syncthreads_or(seen != 0u) != 0;  // also: staged tables and stream are complete
 
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     // cursor = word index inside the workgroup's window
@@ -601,11 +609,12 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
-    const bool restart = D.restart != 0u;
     uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
     const uint32_t bm_k0 = first_word >> 3;
-    if (restart) stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
+    uint32_t seen = 0u;
+    if (D.restart) seen = stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
     auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
+    const bool restart = __syncthreads_or(seen != 0u) != 0;  // interval starts in this group's stretch of the stream?
 
     const uint32_t t = threadIdx.x;
     const uint32_t i = i0 + t;
@@ -681,7 +690,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
         else decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
     // all restart markers must have been there (the first lane of the image speaks for it)
-    if (restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
+    if (D.restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
     // every lane checks the chain: unless the image is complete it must end in the recorded state
     if (unit < total) {
         if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;

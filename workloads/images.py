@@ -153,11 +153,12 @@ def _cache_dir():
     return d or None
 
 
-def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None):
+def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None, restart_interval: int = 0):
     """Encoded file(s) of configuration c: an EncodedJpeg, or for the batch config a list of them.
 
-    `limit` truncates the batch (tests use a few images of it).  If JPGD_WORKLOAD_CACHE names a
-    directory, files are kept there between runs, keyed by the encoder source's hash.
+    `limit` truncates the batch (tests use a few images of it).  `restart_interval` (MCUs; 0 = none, as the
+    configurations are defined) encodes the same pixels with restart markers.  If JPGD_WORKLOAD_CACHE names
+    a directory, files are kept there between runs, keyed by the encoder source's hash.
     """
     cfg = CONFIGS[c]
     if c == 4:
@@ -165,7 +166,8 @@ def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None):
         out = []
         for j in range(n):
             px, q = batch_image(j)
-            out.append(encode_jpeg(px, quality=q, subsampling=cfg["subsampling"], optimize=False, want_coef=want_coef))
+            out.append(encode_jpeg(px, quality=q, subsampling=cfg["subsampling"], optimize=False, want_coef=want_coef,
+                                   restart_interval=restart_interval))
         return out
     cache = _cache_dir()
     path = None
@@ -175,13 +177,14 @@ def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None):
         for fn in ("jpeg_encoder.c", "images.py"):
             with open(os.path.join(here, fn), "rb") as f:
                 hsh.update(f.read())
-        path = os.path.join(cache, "cfg%d_%s.npz" % (c, hsh.hexdigest()[:16]))
+        path = os.path.join(cache, "cfg%d%s_%s.npz" % (c, "_ri%d" % restart_interval if restart_interval else "",
+                                                       hsh.hexdigest()[:16]))
         if os.path.exists(path):
             z = np.load(path)
             return EncodedJpeg(z["data"], None, int(z["scan_offset"]), int(z["scan_len"]), cfg["width"],
                                cfg["height"], cfg["ncomp"], cfg["subsampling"])
     enc = encode_jpeg(config_image(c), quality=cfg["quality"], subsampling=cfg["subsampling"],
-                      optimize=cfg["optimize"], want_coef=want_coef)
+                      optimize=cfg["optimize"], want_coef=want_coef, restart_interval=restart_interval)
     if path:
         os.makedirs(cache, exist_ok=True)
         tmp = path + ".tmp%d.npz" % os.getpid()
