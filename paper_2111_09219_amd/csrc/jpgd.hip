@@ -23,7 +23,7 @@ constexpr uint32_t kMagic = 0x4A504744u;  // "JPGD"
 struct WsHeader {
     uint32_t magic, nimg, logL, overlap;
     uint64_t off_status, off_state, off_img, off_lut, off_qt;       // uploaded region
-    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref, off_bmap; // device-written regions
+    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref, off_bmap, off_warm; // device-written regions
     uint64_t upload_bytes, total_bytes;
 };
 
@@ -185,6 +185,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     h.off_gtot = off;   off = up256(off + (size_t)pl.grps * 16);
     h.off_gpref = off;  off = up256(off + (size_t)pl.grps * 16);
     h.off_bmap = off;   off = up256(off + (size_t)pl.bmap_words * 4);
+    h.off_warm = off;   off = up256(off + (size_t)pl.seqs * 4);
     h.total_bytes = off;
     return JPGD_OK;
 }
@@ -436,6 +437,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.grp_tot = (int4*)(ws + pl.h.off_gtot);
     P.grp_pref = (int4*)(ws + pl.h.off_gpref);
     P.bmap = (uint32_t*)(ws + pl.h.off_bmap);
+    P.warm_x = (uint32_t*)(ws + pl.h.off_warm);
     P.luts = (const uint16_t*)(ws + pl.h.off_lut);
     P.qts = (const uint16_t*)(ws + pl.h.off_qt);
     P.coef = d_coef;

@@ -23,6 +23,8 @@ struct Params {
     int4* grp_tot;          // per group of kWG subsequences: (units, dc0, dc1, dc2) totals
     int4* grp_pref;         // exclusive prefix of grp_tot inside the image
     uint32_t* bmap;         // interval-start bitmaps of images with restart intervals (ImgDesc::bmap_off)
+    uint32_t* warm_x;       // per sequence: the state at its first subsequence's start that its records continue
+                            // (packed like SInfo::x; 0xFFFFFFFF = none)
     const uint16_t* luts;
     const uint16_t* qts;
     int16_t* coef;
@@ -492,6 +494,10 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         r.x = sw[t]; r.y = pnb[t]; r.z = pdc01[t]; r.w = pdc2[t];
         P.sinfo[D.sub0 + (uint32_t)(base + (int32_t)t)] = r;
     }
+    // The published records continue the state the last warm-up lane ended in.  If the previous sequence ends
+    // in that very state, the two sequences already form one chain and the inter-sequence kernel has nothing
+    // to decode at this boundary.
+    if (t == 0u) P.warm_x[wg] = (P.overlap > 0u && P.overlap - 1u >= t0) ? sw[P.overlap - 1u] : 0xFFFFFFFFu;
 }
 
 // ---- synchronisation, inter-sequence (paper, Algorithm 3, second loop) ------------------------------
@@ -504,22 +510,30 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.bnd0; });
     const ImgDesc D = image_desc(P, ii);
     const uint32_t nsub = P.st[ii].nsub;
+    const uint32_t b = (wg - D.bnd0) * 64u + threadIdx.x;
+    const uint64_t gfirst = (uint64_t)(b + 1u) * P.seq_len;
+    SInfo* rec = P.sinfo + D.sub0;
+    uint32_t* warm = P.warm_x + D.seq0 + b + 1u;  // of the sequence that starts at this boundary
+    // nothing to do where the sequence behind the boundary already continues the state the one before ends in
+    uint32_t g = 0u, x0 = 0u;
+    bool work = false;
+    if (gfirst < nsub) {
+        g = (uint32_t)gfirst;
+        x0 = rec[g - 1u].x;
+        work = *warm != x0;
+    }
+    if (!__syncthreads_or(work)) return;
     uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
     __shared__ UnitRow rows[8];
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     __syncthreads();
-    const uint32_t b = (wg - D.bnd0) * 64u + threadIdx.x;
-    const uint64_t gfirst = (uint64_t)(b + 1u) * P.seq_len;
-    if (gfirst >= nsub) return;
-    uint32_t g = (uint32_t)gfirst;
+    if (!work) return;
     const uint32_t gend = min(nsub, g + P.seq_len);
     const uint32_t* words = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off);
     auto fetch = [&](uint32_t w) { return __builtin_bswap32(words[w]); };
     const uint32_t* bmap_img = P.bmap + D.bmap_off;
     auto bword = [&](uint32_t k) { return bmap_img[k]; };
-    SInfo* rec = P.sinfo + D.sub0;
-    const uint32_t x0 = rec[g - 1u].x;
     Lane l;
     BitWin w;
     l.p = (g << P.logL) + state_prel(x0);
@@ -547,6 +561,7 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
         ++g;
         if (synced || g >= gend) break;
     }
+    *warm = x0;  // the sequence's records now continue this state
 }
 
 // ---- exclusive scan over s_info (paper, Algorithm 1: prefix sum on s_info.n) ---------------------------

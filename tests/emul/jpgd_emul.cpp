@@ -118,6 +118,7 @@ struct Emul {
     Image im;
     uint32_t logL, H, seq_len;
     std::vector<SInfo> sinfo;
+    std::vector<uint32_t> warm;  // per sequence: the state its records continue (0xFFFFFFFF = none)
     UnitRow rows[8];
     Syntax sx;
     uint32_t inter_changed = 0, rounds_max = 0, flags = 0;
@@ -199,6 +200,7 @@ void sync_intra(Emul& E) {
             }
         }
         E.rounds_max = std::max(E.rounds_max, rounds);
+        E.warm[wg] = (E.H > 0 && E.H - 1 >= t0) ? sw[E.H - 1] : 0xFFFFFFFFu;
         for (uint32_t t = std::max(t0, E.H); t < t1; ++t) {
             SInfo r = {sw[t], pnb[t], pdc01[t], pdc2[t]};
             E.sinfo[(uint32_t)(base + (int32_t)t)] = r;
@@ -219,6 +221,7 @@ void sync_inter(Emul& E) {
         if (gfirst >= nsub) break;
         uint32_t g = (uint32_t)gfirst, gend = std::min(nsub, g + E.seq_len);
         uint32_t x0 = E.sinfo[g - 1].x;
+        if (E.warm[b + 1] == x0) continue;  // the two sequences already form one chain
         Lane l;
         BitWin w;
         l.p = (g << logL) + state_prel(x0); l.z = state_z(x0); l.u = state_u(x0);
@@ -240,6 +243,7 @@ void sync_inter(Emul& E) {
             ++g;
             if (synced || g >= gend) break;
         }
+        E.warm[b + 1] = x0;
     }
 }
 
@@ -384,9 +388,10 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
     E.sx.upm = E.im.in.units_per_mcu;
     unstuff(file + E.im.in.scan_offset, (uint32_t)E.im.in.scan_bytes, E.logL, E.im);
     E.sinfo.assign(E.im.nsub, SInfo{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu});
+    const uint32_t nseq = (E.im.nsub + E.seq_len - 1) / E.seq_len;
+    E.warm.assign(nseq + 1, 0xFFFFFFFFu);
     sync_intra(E);
     uint32_t rounds = 0;
-    const uint32_t nseq = (E.im.nsub + E.seq_len - 1) / E.seq_len;
     for (;;) {
         if (nseq > 1) { sync_inter(E); ++rounds; }
         scan_and_write(E, coef);
