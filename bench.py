@@ -64,6 +64,8 @@ def main() -> int:
     ap.add_argument("--restart-interval", type=int, default=0, metavar="MCUS",
                     help="encode the workload with restart markers every MCUS MCUs (-1 = one MCU row); the "
                          "configurations themselves have none")
+    ap.add_argument("--quality", type=int, default=0,
+                    help="encode the (single-image) workload at this quality instead of the configuration's")
     ap.add_argument("--include-h2d", action="store_true",
                     help="also time steps that first copy the compressed bytes from pinned host memory (reported as "
                          "'with_h2d'; never as 'value')")
@@ -102,7 +104,7 @@ def main() -> int:
     if ri < 0:
         mcu_w = 8 if wl["subsampling"] in ("gray", "444") else 16
         ri = (wl["width"] + mcu_w - 1) // mcu_w
-    enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri) if c == 4 else config_jpeg(c, restart_interval=ri)
+    enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri) if c == 4 else config_jpeg(c, restart_interval=ri, quality=args.quality or None)
     files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
     cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap)
     batch = J.prepare_batch(files, cfg, device="cuda:0")
@@ -218,12 +220,12 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "configs[%d] %s: %d image(s) %dx%d %s q%s%s, %d compressed bytes" % (
             c - 1, wl["name"], len(files), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
-            (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % ri if ri else ""), Bs),
+            (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % ri if ri else "") + (" re-encoded at q%d" % args.quality if args.quality else ""), Bs),
             "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
             "inter_rounds": rep.inter_rounds, "redo": rep.redo},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri) else None,
+                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,
                      "avg_launch_ms": round(dom_avg_ms, 5), "timed_launches": dom_launches,
                      "alg_bytes_per_launch": alg},
         "cpu_baseline": cpu,

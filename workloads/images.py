@@ -153,11 +153,13 @@ def _cache_dir():
     return d or None
 
 
-def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None, restart_interval: int = 0):
+def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None, restart_interval: int = 0,
+                quality: int | None = None):
     """Encoded file(s) of configuration c: an EncodedJpeg, or for the batch config a list of them.
 
     `limit` truncates the batch (tests use a few images of it).  `restart_interval` (MCUs; 0 = none, as the
-    configurations are defined) encodes the same pixels with restart markers.  If JPGD_WORKLOAD_CACHE names
+    configurations are defined) encodes the same pixels with restart markers; `quality` overrides the
+    configuration's quality (single-image configurations only).  If JPGD_WORKLOAD_CACHE names
     a directory, files are kept there between runs, keyed by the encoder source's hash.
     """
     cfg = CONFIGS[c]
@@ -177,13 +179,13 @@ def config_jpeg(c: int, want_coef: bool = False, limit: int | None = None, resta
         for fn in ("jpeg_encoder.c", "images.py"):
             with open(os.path.join(here, fn), "rb") as f:
                 hsh.update(f.read())
-        path = os.path.join(cache, "cfg%d%s_%s.npz" % (c, "_ri%d" % restart_interval if restart_interval else "",
-                                                       hsh.hexdigest()[:16]))
+        tag = ("_ri%d" % restart_interval if restart_interval else "") + ("_q%d" % quality if quality else "")
+        path = os.path.join(cache, "cfg%d%s_%s.npz" % (c, tag, hsh.hexdigest()[:16]))
         if os.path.exists(path):
             z = np.load(path)
             return EncodedJpeg(z["data"], None, int(z["scan_offset"]), int(z["scan_len"]), cfg["width"],
                                cfg["height"], cfg["ncomp"], cfg["subsampling"])
-    enc = encode_jpeg(config_image(c), quality=cfg["quality"], subsampling=cfg["subsampling"],
+    enc = encode_jpeg(config_image(c), quality=quality or cfg["quality"], subsampling=cfg["subsampling"],
                       optimize=cfg["optimize"], want_coef=want_coef, restart_interval=restart_interval)
     if path:
         os.makedirs(cache, exist_ok=True)
