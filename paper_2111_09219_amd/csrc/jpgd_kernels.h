@@ -701,7 +701,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     if (unit < total) {
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
         prime(l, w, sx, lut_s);
-        if (restart) decode_span_write_rst(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags, bword);
+        if (restart) decode_span_write_rst(l, w, limit, unit, total, D.restart * D.upm, pred0, pred1, pred2, sx, fetch, lut_s, store, flags, bword);
         else decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
     // all restart markers must have been there (the first lane of the image speaks for it)

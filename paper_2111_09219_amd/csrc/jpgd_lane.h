@@ -330,10 +330,12 @@ JPGD_HD void decode_span_sync_rst(Lane& l, BitWin& w, uint32_t limit, int64_t& d
 }
 
 // Write pass over a stream with restart intervals: the predictors return to zero where an interval starts.
+// An interval holds units_per_interval data units (all but the last of the scan): a start reached at any
+// other unit count means damaged data and is flagged.
 template <class Fetch, class LutPtr, class Store, class BWord>
 JPGD_HD void decode_span_write_rst(Lane& l, BitWin& w, uint32_t limit, uint32_t& unit, uint32_t total_units,
-                                   int32_t& pred0, int32_t& pred1, int32_t& pred2, const Syntax& sx, Fetch fetch,
-                                   LutPtr lut, Store store, uint32_t& flags, BWord bword) {
+                                   uint32_t units_per_interval, int32_t& pred0, int32_t& pred1, int32_t& pred2,
+                                   const Syntax& sx, Fetch fetch, LutPtr lut, Store store, uint32_t& flags, BWord bword) {
     uint32_t from = win_pos(w);
     for (;;) {
         const uint32_t B = next_boundary(from, limit + 64u, bword);
@@ -350,6 +352,7 @@ JPGD_HD void decode_span_write_rst(Lane& l, BitWin& w, uint32_t limit, uint32_t&
         while (pos < limit && unit < total_units) {
             if (pos == B) {
                 pred0 = pred1 = pred2 = 0;
+                if (unit % units_per_interval != 0u) flags |= kStInvalid;
                 from = B + 1u;
                 next_interval = true;
                 break;

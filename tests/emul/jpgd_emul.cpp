@@ -307,7 +307,7 @@ void scan_and_write(Emul& E, int16_t* coef) {
             if (unit < total) {
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
                 prime(l, w, E.sx, im.lut.data());
-                if (restart) decode_span_write_rst(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags, bword);
+                if (restart) decode_span_write_rst(l, w, limit, unit, total, im.in.restart_interval * im.in.units_per_mcu, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags, bword);
                 else decode_span_write(l, w, limit, unit, total, p0, p1, p2, E.sx, fetch, im.lut.data(), store, flags);
             }
             if (restart && i == 0) {

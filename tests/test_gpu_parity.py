@@ -135,14 +135,19 @@ def test_restart_sync_records_and_mixed_batch():
         batch, rep = _decode(files, subseq_bits=L)
         for i, f in enumerate(files):
             _check_image(batch, i, f)
-    # a missing marker (two intervals fused) must be reported, not decoded silently
-    enc = encode_jpeg(small_image(46, 64, 64), 85, "444", restart_interval=4)
-    raw = bytearray(enc.data.tobytes())
+    # a missing marker (two intervals fused), or most of an interval missing, must be reported, not decoded
+    # silently
+    enc = encode_jpeg(small_image(46, 64, 96, sigma=14.0), 85, "444", restart_interval=4)
+    raw = enc.data.tobytes()
     k = raw.index(b"\xFF\xD1")
-    del raw[k:k + 2]
-    with pytest.raises(J.JpgdError) as e:
-        _decode([np.frombuffer(bytes(raw), np.uint8).copy()])
-    assert e.value.name == "CORRUPT"
+    a, b = raw.index(b"\xFF\xD2") + 2, raw.index(b"\xFF\xD3")
+    stop = a + 4 + (b - a) * 2 // 3                    # two thirds of an interval cut out
+    while b"\xFF" in raw[stop - 1:stop + 1]:
+        stop -= 1
+    for bad in (raw[:k] + raw[k + 2:], raw[:a + 4] + raw[stop:]):
+        with pytest.raises(J.JpgdError) as e:
+            _decode([np.frombuffer(bad, np.uint8).copy()])
+        assert e.value.name == "CORRUPT"
 
 
 def test_unstuff_kernel_alone():

@@ -311,3 +311,27 @@ def test_host_walkthrough_flags_corrupt_streams(emul):
     assert rc == -6
     with pytest.raises(OracleError):
         OracleImage(short).coefficients()
+
+
+def _damaged_restart_files():
+    """A scan with restart intervals from which (a) one marker, (b) most of one interval's bytes are missing.
+    (A few missing bytes need not be noticed: the decoder falls back into step and the interval still ends
+    where it should -- that is the self-synchronisation the whole method rests on.)"""
+    enc = encode_jpeg(small_image(46, 64, 96, sigma=14.0), 85, "444", restart_interval=4)
+    raw = enc.data.tobytes()
+    k = raw.index(b"\xFF\xD1")
+    no_marker = raw[:k] + raw[k + 2:]
+    a, b = raw.index(b"\xFF\xD2") + 2, raw.index(b"\xFF\xD3")
+    cut = slice(a + 4, a + 4 + (b - a) * 2 // 3)     # two thirds of the interval: its data units cannot all be there
+    while b"\xFF" in raw[cut.stop - 1:cut.stop + 1]:
+        cut = slice(cut.start, cut.stop - 1)
+    short_interval = raw[:cut.start] + raw[cut.stop:]
+    return [np.frombuffer(x, np.uint8).copy() for x in (no_marker, short_interval)]
+
+
+def test_host_walkthrough_flags_damaged_restart_streams(emul):
+    for bad in _damaged_restart_files():
+        rc, *_ = _emul_run(emul, bad, 128, 16)
+        assert rc == -6
+        with pytest.raises(OracleError):
+            OracleImage(bad).coefficients()
