@@ -150,6 +150,38 @@ def test_restart_sync_records_and_mixed_batch():
         assert e.value.name == "CORRUPT"
 
 
+def test_seeded_random_cases():
+    """Sixty cases drawn from a seeded generator: sizes (also far from MCU multiples), layouts, qualities from
+    very low to 100, standard or optimised tables, restart intervals from one MCU upwards or none, every
+    subsequence size and overlap the configuration accepts; a few of them decoded together as one batch."""
+    rng = np.random.default_rng(20211109)
+    subs = ["gray", "444", "422", "420"]
+    pending = []
+    for case in range(60):
+        sub = subs[int(rng.integers(0, 4))]
+        h, w = int(rng.integers(1, 420)), int(rng.integers(1, 420))
+        q = int(rng.choice([5, 20, 35, 50, 75, 90, 97, 100]))
+        opt = bool(rng.integers(0, 2))
+        ri = int(rng.choice([0, 0, 1, 2, 3, 8, 17, 50, 400]))
+        sigma = float(rng.choice([0.0, 2.0, 9.0, 40.0]))
+        L = int(rng.choice([128, 256, 512, 1024, 2048]))
+        H = int(rng.choice([0, 1, 8, 16, 32, 100, 191]))
+        px = small_image(1000 + case, h, w, ncomp=1 if sub == "gray" else 3, sigma=sigma, shapes=int(rng.integers(0, 6)))
+        data = encode_jpeg(px, q, sub, opt, restart_interval=ri).data
+        try:
+            batch, rep = _decode([data], subseq_bits=L, overlap=H)
+            _check_image(batch, 0, data)
+        except Exception as e:
+            raise AssertionError("case %d: %s %dx%d q%d opt=%s ri=%d sigma=%g L=%d H=%d: %r" % (
+                case, sub, w, h, q, opt, ri, sigma, L, H, e))
+        pending.append(data)
+        if len(pending) == 12:
+            batch, rep = _decode(pending)
+            for i, f in enumerate(pending):
+                _check_image(batch, i, f)
+            pending = []
+
+
 def test_unstuff_kernel_alone():
     import torch
     rng = np.random.default_rng(9)
