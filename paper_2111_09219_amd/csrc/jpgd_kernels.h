@@ -724,8 +724,7 @@ __device__ __constant__ uint8_t c_zigzag[64] = JPGD_ZIGZAG_LITERAL;
 
 __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     __shared__ float blk[kPixBlocks * kBlkStride];
-    __shared__ float qf[3 * 64];
-    __shared__ uint8_t zoff[64];
+    __shared__ __attribute__((aligned(16))) float qf[3 * 64];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.pix_wg0; });
     const ImgDesc D = image_desc(P, ii);
@@ -737,23 +736,36 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     const uint32_t nm = min(M, D.mcus_x - m0);
     const uint32_t nblk = nm * upm;
     const uint32_t t = threadIdx.x;
-    if (t < 64u) zoff[t] = (uint8_t)((c_zigzag[t] >> 3) * 9u + (c_zigzag[t] & 7u));
     if (t < 3u * 64u) qf[t] = (float)P.qts[D.qt_off + t];
+    // A lane always handles the same eighth of a data unit (256 is a multiple of 8): where its 8 coefficients
+    // go inside the 8x9 tile is fixed, and is kept in registers.
+    const uint32_t part = t & 7u;
+    uint32_t zo[8];
+#pragma unroll
+    for (uint32_t e = 0; e < 8u; ++e) {
+        const uint32_t rc = c_zigzag[part * 8u + e];
+        zo[e] = (rc >> 3) * 9u + (rc & 7u);
+    }
     __syncthreads();
 
     // load + dequantise + de-zigzag: 8 coefficients (16 bytes) per lane and step
     const int16_t* coef = P.coef + D.coef_off + (size_t)((size_t)mrow * D.mcus_x + m0) * upm * 64u;
     for (uint32_t j = t; j < nblk * 8u; j += kWG) {
-        const uint32_t k = j >> 3, part = j & 7u;
-        const uint32_t comp = (D.sched_comp >> ((k % upm) * 4u)) & 15u;
-        uint4 raw = *reinterpret_cast<const uint4*>(coef + (size_t)j * 8u);
-        const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-        for (uint32_t e = 0; e < 8u; ++e) {
-            const int32_t c = (int32_t)(int16_t)(v[e >> 1] >> (16u * (e & 1u)));
-            const uint32_t zi = part * 8u + e;
-            blk[k * kBlkStride + zoff[zi]] = (float)c * qf[comp * 64u + zi];
-        }
+        const uint32_t k = j >> 3;
+        const uint32_t ku = upm == 1u ? 0u : (upm == 3u ? k % 3u : (upm == 4u ? (k & 3u) : k % 6u));
+        const uint32_t comp = (D.sched_comp >> (ku * 4u)) & 15u;
+        const uint4 raw = *reinterpret_cast<const uint4*>(coef + (size_t)j * 8u);
+        const float4 qa = *reinterpret_cast<const float4*>(qf + comp * 64u + part * 8u);
+        const float4 qb = *reinterpret_cast<const float4*>(qf + comp * 64u + part * 8u + 4u);
+        float* tile = blk + k * kBlkStride;
+        tile[zo[0]] = (float)(int16_t)(raw.x) * qa.x;
+        tile[zo[1]] = (float)((int32_t)raw.x >> 16) * qa.y;
+        tile[zo[2]] = (float)(int16_t)(raw.y) * qa.z;
+        tile[zo[3]] = (float)((int32_t)raw.y >> 16) * qa.w;
+        tile[zo[4]] = (float)(int16_t)(raw.z) * qb.x;
+        tile[zo[5]] = (float)((int32_t)raw.z >> 16) * qb.y;
+        tile[zo[6]] = (float)(int16_t)(raw.w) * qb.z;
+        tile[zo[7]] = (float)((int32_t)raw.w >> 16) * qb.w;
     }
     __syncthreads();
     // columns, then rows
@@ -774,29 +786,33 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     __syncthreads();
 
     // output: groups of 4 horizontally adjacent pixels
+    // (sampling factors are 1 or 2: shifts instead of divisions; the one division by a free number, the
+    // groups per row, goes through a reciprocal that is exact for the few hundred items of a workgroup)
     const uint32_t hs = D.hs, vs = D.vs, ncomp = D.ncomp;
-    const uint32_t mcu_w = 8u * hs, mcu_h = 8u * vs;
+    const uint32_t lhs = hs >> 1, lvs = vs >> 1;          // log2 of 1 or 2
+    const uint32_t mcu_w = 8u * hs, mcu_h = 8u * vs, lmw = 3u + lhs;
     const uint32_t region_w = nm * mcu_w;
     const uint32_t groups_per_row = region_w >> 2;
+    const float inv_gpr = 1.0f / (float)groups_per_row;
     uint8_t* pix = P.pixels + D.pix_off;
     const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
     const uint32_t x_base = m0 * mcu_w, y_base = mrow * mcu_h;
     for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
-        const uint32_t py = j / groups_per_row, px0 = (j % groups_per_row) * 4u;
+        const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - py * groups_per_row) * 4u;
         const uint32_t gy = y_base + py, gx0 = x_base + px0;
         if (gy >= D.height || gx0 >= D.width) continue;
-        const uint32_t m = px0 / mcu_w, xin = px0 % mcu_w;  // the 4 pixels share MCU and luma unit
+        const uint32_t m = px0 >> lmw, xin = px0 & (mcu_w - 1u);  // the 4 pixels share MCU and luma unit
         const float* yb = blk + (m * upm + (py >> 3) * hs + (xin >> 3)) * kBlkStride + (py & 7u) * 9u + (xin & 7u);
         uint32_t out[4];
         if (ncomp == 1u) {
 #pragma unroll
             for (uint32_t e = 0; e < 4u; ++e) out[e] = to_u8(yb[e]);
         } else {
-            const float* cbb = blk + (m * upm + hs * vs) * kBlkStride + (py / vs) * 9u;
+            const float* cbb = blk + (m * upm + hs * vs) * kBlkStride + (py >> lvs) * 9u;
             const float* crb = cbb + kBlkStride;
 #pragma unroll
             for (uint32_t e = 0; e < 4u; ++e) {
-                const uint32_t cx = (xin + e) / hs;
+                const uint32_t cx = (xin + e) >> lhs;
                 out[e] = ycc_to_rgb(yb[e], cbb[cx], crb[cx]);
             }
         }
