@@ -31,9 +31,14 @@ JPGD_HD void idct8(float& v0, float& v1, float& v2, float& v3, float& v4, float&
 
 JPGD_HD uint32_t to_u8(float v) {
     // round half up, then clamp: floor(v + 0.5) limited to [0, 255]
+#if defined(__HIP_DEVICE_COMPILE__)
+    // the same in three instructions: clamp v + 0.5 to [0, 255.5], then truncate
+    return (uint32_t)__builtin_amdgcn_fmed3f(v + 0.5f, 0.0f, 255.5f);
+#else
     float r = __builtin_floorf(v + 0.5f);
     r = r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r);
     return (uint32_t)r;
+#endif
 }
 
 // JFIF YCbCr -> RGB on unrounded samples (level shift already applied), packed as R | G<<8 | B<<16
