@@ -728,3 +728,49 @@ int orc_decode_pixels(const orc_image* im, const int16_t* coef, uint8_t* pixels)
     if (!im) return ORC_E_ARG;
     return orc_decode_pixels_mcus(im, coef, pixels, 0, im->info.mcus_x, 0, im->info.mcus_y);
 }
+
+/*
+ * The decoder's output as the paper defines it (Section 3, problem statement: one array per colour channel;
+ * Section 4.3: the inverse DCT is the last step when no upsampling or colour conversion is applied): the
+ * samples of every component at the component's own resolution, level-shifted, rounded once and clamped.
+ * Component c is plane_w[c] x plane_h[c] samples, ceil(width * hs[c] / hmax) by ceil(height * vs[c] / vmax)
+ * (T.81 A.1.1); the planes are stored one after the other in `planes`.
+ */
+int orc_plane_size(const orc_image* im, int c, int32_t* w, int32_t* h) {
+    if (!im || c < 0 || c >= im->info.ncomp) return ORC_E_ARG;
+    const orc_info* in = &im->info;
+    *w = (in->width * in->hs[c] + in->hmax - 1) / in->hmax;
+    *h = (in->height * in->vs[c] + in->vmax - 1) / in->vmax;
+    return ORC_OK;
+}
+
+int orc_decode_planes(const orc_image* im, const int16_t* coef, uint8_t* planes) {
+    if (!im || !coef || !planes) return ORC_E_ARG;
+    init_tables();
+    const orc_info* in = &im->info;
+    size_t base[3] = {0, 0, 0};
+    int32_t pw[3], ph[3];
+    size_t off = 0;
+    for (int c = 0; c < in->ncomp; ++c) {
+        orc_plane_size(im, c, &pw[c], &ph[c]);
+        base[c] = off;
+        off += (size_t)pw[c] * ph[c];
+    }
+    double blk[64];
+    for (int my = 0; my < in->mcus_y; ++my)
+        for (int mx = 0; mx < in->mcus_x; ++mx) {
+            int64_t k0 = ((int64_t)my * in->mcus_x + mx) * in->units_per_mcu;
+            for (int u = 0; u < in->units_per_mcu; ++u) {
+                int c = im->unit_comp[u];
+                unit_samples(im, coef, k0 + u, blk);
+                for (int y = 0; y < 8; ++y)
+                    for (int x = 0; x < 8; ++x) {
+                        int gx = (mx * in->hs[c] + im->unit_bx[u]) * 8 + x;
+                        int gy = (my * in->vs[c] + im->unit_by[u]) * 8 + y;
+                        if (gx >= pw[c] || gy >= ph[c]) continue;
+                        planes[base[c] + (size_t)gy * pw[c] + gx] = to_u8(blk[y * 8 + x]);
+                    }
+            }
+        }
+    return ORC_OK;
+}

@@ -81,6 +81,8 @@ def _load():
         lib.orc_idct8x8.restype = None
         lib.orc_decode_pixels_mcus.argtypes = [vp, vp, vp, i32, i32, i32, i32]
         lib.orc_decode_pixels.argtypes = [vp, vp, vp]
+        lib.orc_decode_planes.argtypes = [vp, vp, vp]
+        lib.orc_plane_size.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         _lib = lib
     return _lib
 
@@ -183,6 +185,29 @@ class OracleImage:
             _check(self._lib.orc_decode_pixels(self._h, coef.ctypes.data, out.ctypes.data))
         else:
             _check(self._lib.orc_decode_pixels_mcus(self._h, coef.ctypes.data, out.ctypes.data, *map(int, mcu_rect)))
+        return out
+
+    def plane_shapes(self):
+        """(height, width) of every component's plane."""
+        out = []
+        for c in range(self.ncomp):
+            w, h = ctypes.c_int32(), ctypes.c_int32()
+            _check(self._lib.orc_plane_size(self._h, c, ctypes.byref(w), ctypes.byref(h)))
+            out.append((h.value, w.value))
+        return out
+
+    def planes(self, coef: np.ndarray | None = None):
+        """The components' samples at their own resolution (no upsampling, no colour conversion), uint8."""
+        if coef is None:
+            coef = self.coefficients()
+        coef = np.ascontiguousarray(coef, dtype=np.int16)
+        shapes = self.plane_shapes()
+        buf = np.zeros(sum(h * w for h, w in shapes), dtype=np.uint8)
+        _check(self._lib.orc_decode_planes(self._h, coef.ctypes.data, buf.ctypes.data))
+        out, off = [], 0
+        for h, w in shapes:
+            out.append(buf[off:off + h * w].reshape(h, w))
+            off += h * w
         return out
 
     def trace(self, bits: np.ndarray, nbits: int, start_bit: int, u: int = 0, z: int = 0, max_symbols: int = 4096):

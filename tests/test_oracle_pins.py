@@ -553,3 +553,47 @@ def test_boundary_states_with_restart_intervals(sub, L, ri):
     for i in range(0, n, max(1, n // 40)):
         p = int(bs["p"][i])
         assert p >= (i + 1) * L or unit >= img.total_units
+
+
+# ------------------------------------------------------------------ planar output (the paper's own output format)
+
+def test_planes_gray_equals_pixels_and_shapes():
+    """One component: the plane is the picture.  Plane sizes follow ceil(size * factor / max factor)."""
+    px = small_image(51, 37, 51, ncomp=1)
+    o = OracleImage(encode_jpeg(px, 85).data)
+    assert np.array_equal(o.planes()[0], o.pixels())
+    for sub, want in (("444", [(37, 51)] * 3), ("422", [(37, 51), (37, 26), (37, 26)]), ("420", [(37, 51), (19, 26), (19, 26)])):
+        o = OracleImage(encode_jpeg(small_image(52, 37, 51), 85, sub).data)
+        assert o.plane_shapes() == want
+        assert [p.shape for p in o.planes()] == want
+
+
+@pytest.mark.parametrize("q", [60, 95])
+def test_planes_against_libjpeg_ycbcr_output(q):
+    """libjpeg asked for YCbCr output (no colour conversion) on a 4:4:4 file: its three channels are the
+    components' samples, computed with its integer IDCT -- within 1 level of the double-precision planes.
+    On a 4:2:0 file the luma channel is still the plain plane."""
+    px = small_image(53, 80, 104, sigma=9.0)
+    for subsampling in (0, 2):
+        data = _pillow_jpeg(px, quality=q, subsampling=subsampling)
+        im = Image.open(io.BytesIO(data.tobytes()))
+        im.draft("YCbCr", im.size)
+        assert im.mode == "YCbCr"
+        ref = np.asarray(im)
+        planes = OracleImage(data).planes()
+        assert np.abs(planes[0].astype(int) - ref[..., 0].astype(int)).max() <= 1
+        if subsampling == 0:
+            for c in (1, 2):
+                assert np.abs(planes[c].astype(int) - ref[..., c].astype(int)).max() <= 1
+
+
+def test_planes_and_rgb_agree():
+    """The RGB picture is the JFIF matrix applied to the (replicated) planes: recomputed from the rounded
+    planes it can differ from the single-rounding path by rounding only."""
+    o = OracleImage(encode_jpeg(small_image(54, 64, 96, sigma=5.0), 92, "420").data)
+    y, cb, cr = [p.astype(np.float64) for p in o.planes()]
+    cb = np.repeat(np.repeat(cb, 2, 0), 2, 1)[:64, :96] - 128.0
+    cr = np.repeat(np.repeat(cr, 2, 0), 2, 1)[:64, :96] - 128.0
+    rgb = np.stack([y + 1.402 * cr, y - 0.344136 * cb - 0.714136 * cr, y + 1.772 * cb], -1)
+    rgb = np.clip(np.floor(rgb + 0.5), 0, 255)
+    assert np.abs(rgb - o.pixels().astype(np.float64)).max() <= 2
