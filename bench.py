@@ -66,6 +66,8 @@ def main() -> int:
                          "configurations themselves have none")
     ap.add_argument("--quality", type=int, default=0,
                     help="encode the (single-image) workload at this quality instead of the configuration's")
+    ap.add_argument("--planar", action="store_true",
+                    help="component planes instead of RGB (JPGD_F_PLANAR): the paper's own output format")
     ap.add_argument("--include-h2d", action="store_true",
                     help="also time steps that first copy the compressed bytes from pinned host memory (reported as "
                          "'with_h2d'; never as 'value')")
@@ -106,16 +108,21 @@ def main() -> int:
         ri = (wl["width"] + mcu_w - 1) // mcu_w
     enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri) if c == 4 else config_jpeg(c, restart_interval=ri, quality=args.quality or None)
     files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
-    cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap)
+    flags = J.F_PLANAR if args.planar else 0
+    cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap, flags=flags)
     batch = J.prepare_batch(files, cfg, device="cuda:0")
     Bs = batch.compressed_bytes
     pixels = batch.pixels_total
     K = int(sum(i.total_units for i in batch.infos))
-    out_bytes = int(sum(i.width * i.height * i.ncomp for i in batch.infos))
+    if args.planar:   # luma plane plus (ncomp - 1) chroma planes at their own resolution
+        out_bytes = int(sum(i.width * i.height + (i.ncomp - 1) * (-(-i.width // i.hsamp[0])) * (-(-i.height // i.vsamp[0]))
+                            for i in batch.infos))
+    else:
+        out_bytes = int(sum(i.width * i.height * i.ncomp for i in batch.infos))
 
     # warm-up; its last steps time every kernel to find the dominant one
     cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            timing_mask=(1 << len(J.KERNELS)) - 1)
+                            flags=flags, timing_mask=(1 << len(J.KERNELS)) - 1)
     split = np.zeros(len(J.KERNELS))
     nsplit = max(1, min(5, args.warmup))
     rep = None
@@ -132,7 +139,7 @@ def main() -> int:
     B = Bs  # unstuffed length is within 0.5 % of the stuffed one; the bound is used for the byte counts
 
     cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            timing_mask=1 << dominant)
+                            flags=flags, timing_mask=1 << dominant)
     dom_ms = 0.0
     dom_launches = 0
     torch.cuda.synchronize()
@@ -255,7 +262,7 @@ def main() -> int:
             c - 1, wl["name"], len(files), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
             (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % ri if ri else "") + (" re-encoded at q%d" % args.quality if args.quality else ""), Bs),
             "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
-            "inter_rounds": rep.inter_rounds, "redo": rep.redo},
+            "inter_rounds": rep.inter_rounds, "redo": rep.redo, "output": "planes" if args.planar else "rgb"},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
                      "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,

@@ -86,6 +86,12 @@ typedef struct {
 } jpgd_config;
 
 #define JPGD_F_NO_PIXELS 1u /* stop after the coefficients even if a pixel buffer is given */
+#define JPGD_F_PLANAR 2u    /* d_pixels receives the component planes instead of interleaved RGB: the paper's own
+                               output (Section 3: one array per colour channel; Section 4.3: the IDCT is the last
+                               step).  Per image, at pixel_offsets[i]: the luma plane (height x width), then, for
+                               3 components, Cb and Cr, each ceil(height / v) x ceil(width / h) for luma sampling
+                               factors h x v; samples rounded once and clamped, no upsampling, no colour
+                               conversion.  The planes never take more than height x width x ncomp bytes. */
 
 /* kernels of the pipeline, in launch order */
 enum {

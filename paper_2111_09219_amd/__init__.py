@@ -4,11 +4,11 @@
 The package is a thin binding over the C ABI of include/jpgd.h; all decoding runs in the gfx950
 kernels of csrc/.  Names follow the header.
 """
-from .binding import (Batch, Config, F_NO_PIXELS, KERNELS, Info, JpgdError, Report, EXPORTS, jpgd_decode, jpgd_decode_batch,
+from .binding import (Batch, Config, F_NO_PIXELS, F_PLANAR, KERNELS, Info, JpgdError, Report, EXPORTS, jpgd_decode, jpgd_decode_batch,
                       jpgd_parse, jpgd_read_sync_info, jpgd_unstuff, jpgd_workspace_bytes, library_path,
                       prepare_batch)
 from .build import build
 
-__all__ = ["Batch", "Config", "F_NO_PIXELS", "KERNELS", "Info", "JpgdError", "Report", "EXPORTS", "jpgd_decode",
+__all__ = ["Batch", "Config", "F_NO_PIXELS", "F_PLANAR", "KERNELS", "Info", "JpgdError", "Report", "EXPORTS", "jpgd_decode",
            "jpgd_decode_batch", "jpgd_parse", "jpgd_read_sync_info", "jpgd_unstuff", "jpgd_workspace_bytes",
            "library_path", "prepare_batch", "build"]

@@ -20,6 +20,7 @@ STATUS = {0: "OK", -1: "ARG", -2: "TRUNCATED", -3: "MARKER", -4: "UNSUPPORTED", 
           -7: "WORKSPACE", -8: "HIP"}
 
 F_NO_PIXELS = 1
+F_PLANAR = 2
 
 
 class JpgdError(RuntimeError):
@@ -279,6 +280,19 @@ class Batch:
         """int16 tensor [units, 64] of image i (a view of d_coef)."""
         n = self.infos[i].total_units
         return self.d_coef[self.coef_offsets[i]:self.coef_offsets[i] + 64 * n].view(n, 64)
+
+    def planes(self, i: int = 0):
+        """Component planes of image i after a decode with the JPGD_F_PLANAR flag (views of d_pixels): luma
+        height x width, then Cb and Cr at their own resolution."""
+        info = self.infos[i]
+        off = self.pixel_offsets[i]
+        out = []
+        for c in range(info.ncomp):
+            h = info.height if c == 0 else -(-info.height // info.vsamp[0])
+            w = info.width if c == 0 else -(-info.width // info.hsamp[0])
+            out.append(self.d_pixels[off:off + h * w].view(h, w))
+            off += h * w
+        return out
 
     def pixels(self, i: int = 0):
         info = self.infos[i]

@@ -34,6 +34,7 @@ struct Params {
     uint32_t overlap;       // H: warm-up lanes in front of each sequence
     uint32_t seq_len;       // kWG - H: subsequences a sequence owns
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
+    uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     // A call with one image carries its descriptor in the kernel arguments: every workgroup of every kernel
     // starts by reading the descriptor, and when all of them ask memory for the same freshly written line
     // that read alone was measured at 1 to 11 microseconds per kernel.
@@ -795,8 +796,49 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     const uint32_t groups_per_row = region_w >> 2;
     const float inv_gpr = 1.0f / (float)groups_per_row;
     uint8_t* pix = P.pixels + D.pix_off;
-    const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
     const uint32_t x_base = m0 * mcu_w, y_base = mrow * mcu_h;
+    if (P.planar) {
+        // The paper's own output (Section 3: one array per colour channel): every component at its own
+        // resolution, rounded and clamped.  Luma plane first, then Cb, then Cr.
+        auto put4 = [&](uint8_t* dst, const float* src, uint32_t left, bool word_ok) {
+            const uint32_t o0 = to_u8(src[0]), o1 = to_u8(src[1]), o2 = to_u8(src[2]), o3 = to_u8(src[3]);
+            if (left >= 4u && word_ok) {
+                *reinterpret_cast<uint32_t*>(dst) = o0 | (o1 << 8) | (o2 << 16) | (o3 << 24);
+            } else {
+                dst[0] = (uint8_t)o0;
+                if (left > 1u) dst[1] = (uint8_t)o1;
+                if (left > 2u) dst[2] = (uint8_t)o2;
+                if (left > 3u) dst[3] = (uint8_t)o3;
+            }
+        };
+        const bool y_words = (D.width & 3u) == 0u && (reinterpret_cast<size_t>(pix) & 3u) == 0u;
+        for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
+            const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - py * groups_per_row) * 4u;
+            const uint32_t gy = y_base + py, gx0 = x_base + px0;
+            if (gy >= D.height || gx0 >= D.width) continue;
+            const uint32_t m = px0 >> lmw, xin = px0 & (mcu_w - 1u);
+            const float* yb = blk + (m * upm + (py >> 3) * hs + (xin >> 3)) * kBlkStride + (py & 7u) * 9u + (xin & 7u);
+            put4(pix + (size_t)gy * D.width + gx0, yb, D.width - gx0, y_words);
+        }
+        if (ncomp == 3u) {
+            const uint32_t cw = (D.width + hs - 1u) >> lhs, ch = (D.height + vs - 1u) >> lvs;  // chroma plane size
+            uint8_t* cplane = pix + (size_t)D.width * D.height;
+            const bool c_words = (cw & 3u) == 0u && (reinterpret_cast<size_t>(cplane) & 3u) == 0u && (((size_t)cw * ch) & 3u) == 0u;
+            const uint32_t gpr_c = nm * 2u;  // groups of 4 samples per chroma row of this workgroup
+            for (uint32_t j = t; j < gpr_c * 16u; j += kWG) {
+                const uint32_t c = j >= gpr_c * 8u ? 1u : 0u;
+                const uint32_t r = j - c * gpr_c * 8u;
+                const uint32_t py = (uint32_t)(((float)r + 0.5f) / (float)gpr_c), g = r - py * gpr_c;
+                const uint32_t m = g >> 1, xin = (g & 1u) * 4u;
+                const uint32_t gy = mrow * 8u + py, gx0 = (m0 + m) * 8u + xin;
+                if (gy >= ch || gx0 >= cw) continue;
+                const float* cb = blk + (m * upm + hs * vs + c) * kBlkStride + py * 9u + xin;
+                put4(cplane + (size_t)c * cw * ch + (size_t)gy * cw + gx0, cb, cw - gx0, c_words);
+            }
+        }
+        return;
+    }
+    const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
     for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
         const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - py * groups_per_row) * 4u;
         const uint32_t gy = y_base + py, gx0 = x_base + px0;

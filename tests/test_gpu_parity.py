@@ -182,6 +182,34 @@ def test_seeded_random_cases():
             pending = []
 
 
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_planar_output(sub):
+    """JPGD_F_PLANAR: the components at their own resolution, as the paper's decoder delivers them; odd sizes
+    (ragged planes, byte stores) and sizes that allow word stores; also inside a batch."""
+    files = []
+    for seed, (h, w), q in [(61, (37, 51), 85), (62, (200, 336), 94), (63, (8, 8), 40), (64, (129, 70), 75), (65, (64, 64), 90)]:
+        px = small_image(seed, h, w, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+        files.append(encode_jpeg(px, q, sub).data)
+    for group in ([f] for f in files), [files]:
+        for fs in group:
+            batch = J.prepare_batch(fs, J.Config.make(flags=J.F_PLANAR))
+            batch.d_pixels.fill_(0x5A)
+            batch.decode()
+            for i, f in enumerate(fs):
+                o = OracleImage(f)
+                want = o.planes()
+                got = [p.cpu().numpy() for p in batch.planes(i)]
+                assert [g.shape for g in got] == [x.shape for x in want]
+                for g, x in zip(got, want):
+                    assert np.abs(g.astype(np.int16) - x.astype(np.int16)).max() <= PIXEL_TOL
+                # nothing written behind the planes of this image
+                info = batch.infos[i]
+                used = sum(x.size for x in want)
+                room = info.width * info.height * info.ncomp
+                tail = batch.d_pixels[batch.pixel_offsets[i] + used:batch.pixel_offsets[i] + room].cpu().numpy()
+                assert (tail == 0x5A).all()
+
+
 def test_unstuff_kernel_alone():
     import torch
     rng = np.random.default_rng(9)
