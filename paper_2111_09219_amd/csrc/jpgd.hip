@@ -448,6 +448,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.seq_len = kWG - pl.h.overlap;
     P.lut_slots = pl.lut_slots;
     P.planar = (cfg && (cfg->flags & JPGD_F_PLANAR)) ? 1u : 0u;
+    P.coop_max = kCoopMax;
     P.img0 = pl.img[0];
 
     // optional bracketing of single kernels with events (jpgd_config.timing_mask)

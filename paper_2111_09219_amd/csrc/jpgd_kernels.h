@@ -35,6 +35,7 @@ struct Params {
     uint32_t seq_len;       // kWG - H: subsequences a sequence owns
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
+    uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
     // A call with one image carries its descriptor in the kernel arguments: every workgroup of every kernel
     // starts by reading the descriptor, and when all of them ask memory for the same freshly written line
     // that read alone was measured at 1 to 11 microseconds per kernel.
@@ -366,6 +367,118 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     }
 }
 
+// ---- one chain decoded by a whole wavefront -----------------------------------------------------------
+// The last overflow rounds of a sequence have a handful of chains left, and a lane that decodes one symbol
+// after the other spends some fifty dependent instructions on each.  So when few chains remain, each goes to a
+// wavefront of its own: lane j looks up the symbol that WOULD start j bits after the chain's position, in every
+// table of the image at once, and the chain is then followed through those 64 answers with scalar code (a
+// readlane and a few scalar operations per symbol) until it leaves the 64-bit window.  The synchronisation pass
+// only needs (p, u, z), the count of completed units and the DC sums, so a symbol's value bits matter only for
+// DC symbols.  Results are those of decode_span_sync, symbol by symbol.
+
+// lane i < upm describes data unit i of the MCU: slot of its AC table (bits 0-2), slot of the DC table of the
+// unit that follows (3-5), index of that unit (6-9), bit offset of its component's field in the DC sums (10-14)
+__device__ __forceinline__ uint32_t coop_unit_word(const Syntax& sx, uint32_t lane) {
+    if (lane >= sx.upm) return 0u;
+    const UnitRow r = sx.rows[lane];
+    return (r.tb_ac / (uint32_t)kLutEntries) | ((r.tb_dc_next / (uint32_t)kLutEntries) << 3) | (r.next << 6) |
+           (((uint32_t)__ffs((int)r.dcmul) - 1u) << 10);
+}
+
+// second-level entry of a codeword longer than the first-level index, asked for by the whole wavefront at once
+template <class LutPtr>
+__device__ __forceinline__ uint32_t coop_resolve(LutPtr lut, uint32_t slot, uint32_t e, uint32_t peek) {
+    const uint32_t nb2 = lut_esc_bits(e);
+    const uint32_t at = slot * (uint32_t)kLutEntries + (uint32_t)kLutL1 + lut_esc_offset(e) +
+                        ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
+    return __builtin_amdgcn_readfirstlane((uint32_t)lut[at]);
+}
+
+// p, u, z: wave-uniform state of the chain, advanced until p >= limit.  org_word: stream word with cursor 0 of
+// `fetch`; cursors from nwords on are not read.  1 <= nslots <= 4 tables.
+template <class Fetch, class LutPtr>
+__device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, uint32_t& z_io, uint32_t& nb_out,
+                                               int64_t& dc_out, uint32_t limit, uint32_t org_word, uint32_t nwords,
+                                               uint32_t unit_word, uint32_t upm, uint32_t nslots, Fetch fetch,
+                                               LutPtr lut) {
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t p = __builtin_amdgcn_readfirstlane(p_io);
+    uint32_t u = __builtin_amdgcn_readfirstlane(u_io);
+    uint32_t z = __builtin_amdgcn_readfirstlane(z_io);
+    uint32_t nb = 0u;
+    int64_t dc = 0;
+    uint32_t cur = __builtin_amdgcn_readlane(unit_word, u);
+    // slots of the current unit's AC table and of the table of the DC symbol that starts it
+    uint32_t ac_slot = cur & 7u;
+    uint32_t dc_slot = (__builtin_amdgcn_readlane(unit_word, u == 0u ? upm - 1u : u - 1u) >> 3) & 7u;
+    // 64 consecutive stream words, one per lane, reloaded when the chain has walked through them
+    uint32_t w0 = 0u, held = 0u;
+    bool have = false;
+    while (p < limit) {
+        uint32_t wb = (p >> 5) - w0;
+        if (!have || wb + 3u > 63u) {
+            w0 = p >> 5;
+            const uint32_t c = w0 - org_word + lane;
+            held = c < nwords ? fetch(c) : 0u;
+            wb = 0u;
+            have = true;
+        }
+        const uint32_t s0 = __builtin_amdgcn_readlane(held, wb), s1 = __builtin_amdgcn_readlane(held, wb + 1u);
+        const uint32_t s2 = __builtin_amdgcn_readlane(held, wb + 2u), s3 = __builtin_amdgcn_readlane(held, wb + 3u);
+        const uint32_t bit = (p & 31u) + lane;  // < 95
+        const uint32_t off = bit >> 5;
+        const uint32_t hi = off == 0u ? s0 : (off == 1u ? s1 : s2);
+        const uint32_t lo = off == 0u ? s1 : (off == 1u ? s2 : s3);
+        const uint32_t peek = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (bit & 31u)) >> 32);
+        // first-level entries of all tables (a table the image does not have is asked as the last one it has);
+        // escapes are followed up in the walk, where only those on the chain matter
+        const uint32_t idx = peek >> (32 - kLutK);
+        uint32_t e[4];
+#pragma unroll
+        for (uint32_t s = 0u; s < 4u; ++s) e[s] = lut[min(s, nslots - 1u) * (uint32_t)kLutEntries + idx];
+        const uint32_t e01 = e[0] | (e[1] << 16), e23 = e[2] | (e[3] << 16);
+        uint32_t acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);  // the AC entry in the low 16 bits
+        // follow the chain through the window: symbols that start before bit jmax of it
+        const uint32_t jmax = min(64u, limit - p);
+        uint32_t j = 0u;
+        for (;;) {
+            if (z == 0u) {  // DC symbol
+                const uint32_t pair = __builtin_amdgcn_readlane((dc_slot & 2u) ? e23 : e01, j);
+                const uint32_t pk = __builtin_amdgcn_readlane(peek, j);
+                uint32_t r = pair >> ((dc_slot & 1u) << 4);
+                if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, pk);
+                const uint32_t total = lut_total(r);
+                const int32_t v = symbol_value(pk, total, lut_size(r));
+                dc += (int64_t)v * (int64_t)(1u << ((cur >> 10) & 31u));
+                z = lut_adv(r);  // 1, or 0 where no codeword starts
+                j += max(total, 1u);
+                if (j >= jmax) break;
+                if (z == 0u) continue;
+            }
+            // AC symbols up to the end of the unit or of the window; only j and z change in here
+            // (one test for both ends: z > 63 or j + 64 - jmax > 63)
+            do {
+                uint32_t r = __builtin_amdgcn_readlane(acv, j);
+                if (r & 0x8000u) r = coop_resolve(lut, ac_slot, r, (uint32_t)__builtin_amdgcn_readlane(peek, j));
+                j += max(lut_total(r), 1u);  // every table entry takes at least one bit; the loop must end even if one did not
+                z += lut_adv(r);
+            } while (max(z, j + (64u - jmax)) < 64u);
+            if (z >= 64u) {
+                ++nb;
+                z = 0u;
+                u = (cur >> 6) & 15u;
+                dc_slot = (cur >> 3) & 7u;
+                cur = __builtin_amdgcn_readlane(unit_word, u);
+                ac_slot = cur & 7u;
+                acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);
+            }
+            if (j >= jmax) break;
+        }
+        p += j;
+    }
+    p_io = p; u_io = u; z_io = z; nb_out = nb; dc_out = dc;
+}
+
 // ---- synchronisation, intra-sequence (paper, Algorithm 3, first loop) --------------------------------
 // Workgroup w of an image covers the kWG subsequences base .. base+kWG-1, base = w*seq_len - overlap, and
 // publishes the records of the last seq_len of them; the first `overlap` lanes only warm the chain up.
@@ -443,6 +556,9 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     bool active = valid && (t + 1u < t1);
     uint32_t tt = t + 1u;
     uint32_t waves_used = kWG / 64u;
+    // the wavefront-per-chain code knows neither restart intervals nor more than four tables
+    const uint32_t coop_max = (restart || P.lut_slots > 4u) ? 0u : P.coop_max;
+    uint32_t coop_n = 0u;
     for (uint32_t round = 0u;; ++round) {
         const uint64_t bal = __ballot(active);
         uint32_t* cnt = scratch + ((round & 1u) << 2);
@@ -451,6 +567,19 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         const uint32_t c0 = cnt[0], c1 = cnt[1], c2 = cnt[2], c3 = cnt[3];
         const uint32_t now = c0 + c1 + c2 + c3;
         if (now == 0u) break;
+        if (now <= coop_max) {  // few chains left: hand them to whole wavefronts (below)
+            const uint32_t wave = t >> 6;
+            const uint32_t before = wave == 0u ? 0u : wave == 1u ? c0 : wave == 2u ? c0 + c1 : c0 + c1 + c2;
+            const uint32_t rank = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            if (active) {
+                mv_p[rank] = l.p;
+                mv_uz[rank] = (l.u << 8) | l.z;
+                mv_tt[rank] = tt;
+            }
+            coop_n = now;
+            __syncthreads();
+            break;
+        }
         if (((now + 63u) >> 6) < waves_used) {
             const uint32_t wave = t >> 6;
             const uint32_t before = wave == 0u ? 0u : wave == 1u ? c0 : wave == 2u ? c0 + c1 : c0 + c1 + c2;
@@ -488,6 +617,53 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
             pdc2[tt] = pack_dc2(dcacc);
             ++tt;
             active = !synced && tt < t1;
+        }
+    }
+    // The same rounds with one chain per wavefront.  The chains keep their slot k < coop_n in a list held twice
+    // (read from one copy, written to the other, swapped every round; mv_tt = kCoopDone once a chain has
+    // synchronised or reached the end of the sequence).  Every wavefront reads the whole list and takes the
+    // running chains whose rank among them is its own number modulo four, so the work stays spread as chains
+    // drop out; wavefront 0 carries the finished slots over.  One barrier per round.
+    if (coop_n) {
+        constexpr uint32_t kCoopDone = 0xFFFFFFFFu;
+        // the compiler cannot know that these are the same in every lane (they come from the image descriptor and
+        // the thread index); saying so keeps the chain's state in scalar registers
+        const uint32_t wave = __builtin_amdgcn_readfirstlane(t >> 6), lane = t & 63u;
+        const uint32_t u_n = __builtin_amdgcn_readfirstlane(coop_n), u_t1 = __builtin_amdgcn_readfirstlane(t1);
+        const uint32_t u_first = __builtin_amdgcn_readfirstlane(first_word), u_nwords = __builtin_amdgcn_readfirstlane(nwords);
+        const uint32_t u_upm = __builtin_amdgcn_readfirstlane(sx.upm);
+        const int32_t u_base = (int32_t)__builtin_amdgcn_readfirstlane((uint32_t)base);
+        const uint32_t unit_word = coop_unit_word(sx, lane);
+        for (uint32_t par = 0u;; par ^= 1u) {
+            const uint32_t rd = par << 6, wr = (par ^ 1u) << 6;
+            const uint32_t mine = lane < u_n ? mv_tt[rd + lane] : kCoopDone;
+            const uint64_t running = __ballot(mine != kCoopDone);
+            if (running == 0ull) break;
+            if (wave == 0u && lane < u_n && mine == kCoopDone) mv_tt[wr + lane] = kCoopDone;
+            uint32_t rank = 0u;
+            for (uint64_t m = running; m; m &= m - 1ull, ++rank) {
+                if ((rank & 3u) != wave) continue;
+                const uint32_t k = (uint32_t)__ffsll((long long)m) - 1u;
+                uint32_t cp = mv_p[rd + k];
+                const uint32_t uz = mv_uz[rd + k];
+                uint32_t cu = uz >> 8, cz = uz & 255u, cnb = 0u;
+                const uint32_t ctt = __builtin_amdgcn_readfirstlane(mv_tt[rd + k]);
+                int64_t cdc = 0;
+                const uint32_t limit = ((uint32_t)(u_base + (int32_t)ctt) + 1u) << P.logL;
+                coop_span_sync(cp, cu, cz, cnb, cdc, limit, u_first, u_nwords, unit_word, u_upm, P.lut_slots, fetch, lut_s);
+                const uint32_t x = pack_state(cp - limit, cz, cu);
+                const bool synced = x == sw[ctt];
+                if (lane == 0u) {
+                    sw[ctt] = x;
+                    pnb[ctt] = cnb;
+                    pdc01[ctt] = pack_dc01(cdc);
+                    pdc2[ctt] = pack_dc2(cdc);
+                    mv_p[wr + k] = cp;
+                    mv_uz[wr + k] = (cu << 8) | cz;
+                    mv_tt[wr + k] = (synced || ctt + 1u >= u_t1) ? kCoopDone : ctt + 1u;
+                }
+            }
+            __syncthreads();
         }
     }
     if (valid && t >= P.overlap) {

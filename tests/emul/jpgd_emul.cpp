@@ -124,6 +124,91 @@ struct Emul {
     uint32_t inter_changed = 0, rounds_max = 0, flags = 0;
 };
 
+// The wavefront-per-chain decoder of jpgd_kernels.h (coop_unit_word, coop_span_sync) with its 64 lanes run
+// one after another: the same table words, the same 64-word stretch held by the lanes, the same four answers
+// per lane and the same walk through them.
+uint32_t g_coop_max = kCoopMax;  // as the library sets it; the tests also run with 0 (never), 8 and 64
+
+uint32_t coop_unit_word(const Syntax& sx, uint32_t lane) {
+    if (lane >= sx.upm) return 0u;
+    const UnitRow r = sx.rows[lane];
+    return (r.tb_ac / (uint32_t)kLutEntries) | ((r.tb_dc_next / (uint32_t)kLutEntries) << 3) | (r.next << 6) |
+           (((uint32_t)__builtin_ffs((int)r.dcmul) - 1u) << 10);
+}
+
+uint32_t coop_resolve(const uint16_t* lut, uint32_t slot, uint32_t e, uint32_t peek) {
+    const uint32_t nb2 = lut_esc_bits(e);
+    return lut[slot * (uint32_t)kLutEntries + (uint32_t)kLutL1 + lut_esc_offset(e) +
+               ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u))];
+}
+
+template <class Fetch>
+void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t& dc, uint32_t limit, uint32_t org_word,
+                    uint32_t nwords, const uint32_t unit_word[64], uint32_t upm, uint32_t nslots, Fetch fetch,
+                    const uint16_t* lut) {
+    nb = 0;
+    dc = 0;
+    uint32_t cur = unit_word[u];
+    uint32_t ac_slot = cur & 7u;
+    uint32_t dc_slot = (unit_word[u == 0u ? upm - 1u : u - 1u] >> 3) & 7u;
+    uint32_t w0 = 0, held[64];
+    bool have = false;
+    while (p < limit) {
+        uint32_t wb = (p >> 5) - w0;
+        if (!have || wb + 3u > 63u) {
+            w0 = p >> 5;
+            for (uint32_t lane = 0; lane < 64; ++lane) {
+                const uint32_t c = w0 - org_word + lane;
+                held[lane] = c < nwords ? fetch(c) : 0u;
+            }
+            wb = 0;
+            have = true;
+        }
+        uint32_t peek[64], e01[64], e23[64];
+        for (uint32_t lane = 0; lane < 64; ++lane) {
+            const uint32_t bit = (p & 31u) + lane, off = bit >> 5;
+            const uint32_t hi = held[wb + off], lo = held[wb + off + 1u];
+            peek[lane] = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (bit & 31u)) >> 32);
+            const uint32_t idx = peek[lane] >> (32 - kLutK);
+            uint32_t e[4];
+            for (uint32_t s = 0; s < 4u; ++s) e[s] = lut[std::min(s, nslots - 1u) * (uint32_t)kLutEntries + idx];
+            e01[lane] = e[0] | (e[1] << 16);
+            e23[lane] = e[2] | (e[3] << 16);
+        }
+        auto entry = [&](uint32_t slot, uint32_t j) { return ((slot & 2u) ? e23[j] : e01[j]) >> ((slot & 1u) << 4); };
+        const uint32_t jmax = std::min(64u, limit - p);
+        uint32_t j = 0;
+        for (;;) {
+            if (z == 0u) {
+                uint32_t r = entry(dc_slot, j);
+                if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, peek[j]);
+                const uint32_t total = lut_total(r);
+                dc += (int64_t)symbol_value(peek[j], total, lut_size(r)) * (int64_t)(1u << ((cur >> 10) & 31u));
+                z = lut_adv(r);
+                j += std::max(total, 1u);
+                if (j >= jmax) break;
+                if (z == 0u) continue;
+            }
+            do {
+                uint32_t r = entry(ac_slot, j);
+                if (r & 0x8000u) r = coop_resolve(lut, ac_slot, r, peek[j]);
+                j += std::max(lut_total(r), 1u);
+                z += lut_adv(r);
+            } while (std::max(z, j + (64u - jmax)) < 64u);
+            if (z >= 64u) {
+                ++nb;
+                z = 0u;
+                u = (cur >> 6) & 15u;
+                dc_slot = (cur >> 3) & 7u;
+                cur = unit_word[u];
+                ac_slot = cur & 7u;
+            }
+            if (j >= jmax) break;
+        }
+        p += j;
+    }
+}
+
 void sync_intra(Emul& E) {
     const Image& im = E.im;
     const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5;
@@ -180,8 +265,27 @@ void sync_intra(Emul& E) {
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) any = any || active[t];
             if (!any) break;
             ++rounds;
+            uint32_t now = 0;
+            for (uint32_t t = 0; t < (uint32_t)kWG; ++t) now += active[t] ? 1u : 0u;
+            const bool coop = !restart && im.nslots <= 4u && now <= g_coop_max;  // stays true once it is
+            uint32_t unit_word[64];
+            for (uint32_t lane = 0; lane < 64; ++lane) unit_word[lane] = coop_unit_word(E.sx, lane);
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
                 if (!active[t]) continue;
+                if (coop) {
+                    const uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
+                    uint32_t nb;
+                    coop_span_sync(l[t].p, l[t].u, l[t].z, nb, dcacc[t], limit, first_word, nwords, unit_word, E.sx.upm,
+                                   im.nslots, fetch, im.lut.data());
+                    uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u);
+                    bool synced = x == sw[tt[t]];
+                    sw[tt[t]] = x; pnb[tt[t]] = nb;
+                    pdc01[tt[t]] = pack_dc01(dcacc[t]);
+                    pdc2[tt[t]] = pack_dc2(dcacc[t]);
+                    ++tt[t];
+                    active[t] = !synced && tt[t] < t1;
+                    continue;
+                }
                 l[t].nb = 0;
                 dcacc[t] = 0;
                 win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);  // a chain moved to another lane restarts its window
@@ -408,6 +512,9 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
     if (pix) pixels(E, coef, pix);
     return JPGD_OK;
 }
+
+// chains left at which the intra-sequence walk-through switches to the wavefront-per-chain decoder
+extern "C" void emul_set_coop_max(uint32_t n) { g_coop_max = n; }
 
 // the literal zig-zag table of jpgd_idct.h, for comparison with a generated one
 extern "C" void emul_zigzag(uint8_t out[64]) {

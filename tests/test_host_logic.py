@@ -152,6 +152,7 @@ def emul():
     vp, u32 = ctypes.c_void_p, ctypes.c_uint32
     lib.emul_decode.argtypes = [vp, ctypes.c_size_t, u32, u32, u32, vp, vp, vp, u32, vp, vp]
     lib.emul_zigzag.argtypes = [vp]
+    lib.emul_set_coop_max.argtypes = [u32]
     lib.emul_build_lut.argtypes = [vp, vp, ctypes.c_int, vp]
     return lib
 
@@ -241,10 +242,17 @@ CASES = [("gray", False, 75, (64, 64)), ("444", False, 90, (40, 104)), ("420", T
 
 @pytest.mark.parametrize("sub,opt,q,shape", CASES)
 @pytest.mark.parametrize("L,H", [(128, 0), (128, 48), (256, 0), (1024, 0)])
-def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H):
+@pytest.mark.parametrize("coop", [0, 8, 64])
+def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H, coop):
+    """coop: number of chains left at which the overflow rounds go over to one wavefront per chain (0 = never,
+    64 = from the first round that has so few); the records must not depend on it."""
     px = small_image(17, *shape, ncomp=1 if sub == "gray" else 3, sigma=11.0)
     data = encode_jpeg(px, q, sub, opt).data
-    rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
+    emul.emul_set_coop_max(coop)
+    try:
+        rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
+    finally:
+        emul.emul_set_coop_max(6)   # the library's value (kCoopMax)
     assert rc == 0 and stats[3] == 0
     assert np.array_equal(stream, o.unstuffed())
     ref = o.coefficients()
