@@ -449,6 +449,8 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.lut_slots = pl.lut_slots;
     P.planar = (cfg && (cfg->flags & JPGD_F_PLANAR)) ? 1u : 0u;
     P.coop_max = kCoopMax;
+    P.verdict = nullptr;
+    P.ticket = 0u;
     P.img0 = pl.img[0];
 
     // optional bracketing of single kernels with events (jpgd_config.timing_mask)
@@ -502,12 +504,18 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
         else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
         const uint32_t ticket = ++g_stage.ticket;
-        hipLaunchKernelGGL(k_verdict, dim3(1), dim3(64), 0, stream, (const Status*)(ws + pl.h.off_status),
-                           (volatile uint32_t*)g_stage.verdict_dev, ticket);
         // The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the
-        // verdict is bad its output is either redone below or reported as unspecified.  The host waits for
-        // the verdict alone; the pixels are complete in stream order, like the output of any kernel.
-        if (want_pixels) LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
+        // verdict is bad its output is either redone below or reported as unspecified.  Its first lane passes
+        // the verdict on before anything else; the host waits for the verdict alone, and the pixels are
+        // complete in stream order, like the output of any kernel.  Without pixels a one-lane kernel reports.
+        if (want_pixels) {
+            P.verdict = g_stage.verdict_dev;
+            P.ticket = ticket;
+            LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
+        } else {
+            hipLaunchKernelGGL(k_verdict, dim3(1), dim3(64), 0, stream, (const Status*)(ws + pl.h.off_status),
+                               (volatile uint32_t*)g_stage.verdict_dev, ticket);
+        }
         HIP_OK(hipGetLastError());
         if ((rc = wait_verdict(stream, ticket)) != JPGD_OK) return rc;
         flags = g_stage.verdict[0];

@@ -36,6 +36,10 @@ struct Params {
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
+    // pixel kernel: where its first lane reports the outcome of the write kernel before anything else (pinned host
+    // memory: flags, inter_changed, .., ticket in word 15; null = somebody else reports) and this call's ticket
+    uint32_t* verdict;
+    uint32_t ticket;
     // A call with one image carries its descriptor in the kernel arguments: every workgroup of every kernel
     // starts by reading the descriptor, and when all of them ask memory for the same freshly written line
     // that read alone was measured at 1 to 11 microseconds per kernel.
@@ -913,6 +917,15 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     const uint32_t nm = min(M, D.mcus_x - m0);
     const uint32_t nblk = nm * upm;
     const uint32_t t = threadIdx.x;
+    // The write kernel is complete when this kernel starts: its verdict goes to the waiting host from here, which
+    // saves the dispatch of a kernel that would do nothing else.
+    if (wg == 0u && t == 0u && P.verdict) {
+        volatile uint32_t* host = P.verdict;
+        host[0] = P.status->flags;
+        host[1] = P.status->inter_changed;
+        __threadfence_system();
+        host[15] = P.ticket;
+    }
     if (t < 3u * 64u) qf[t] = (float)P.qts[D.qt_off + t];
     // A lane always handles the same eighth of a data unit (256 is a multiple of 8): where its 8 coefficients
     // go inside the 8x9 tile is fixed, and is kept in registers.
