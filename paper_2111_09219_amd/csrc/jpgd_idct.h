@@ -29,26 +29,33 @@ JPGD_HD void idct8(float& v0, float& v1, float& v2, float& v3, float& v4, float&
     v3 = e3 + o3; v4 = e3 - o3;
 }
 
-JPGD_HD uint32_t to_u8(float v) {
-    // round half up, then clamp: floor(v + 0.5) limited to [0, 255]
+// Float to 8-bit sample, written into byte `byte` (0..3) of `word`: nearest integer, ties to the even one,
+// limited to [0, 255] (NaN gives 0).  On the device this is one instruction, v_cvt_pk_u8_f32, which also does the
+// packing of four samples into the 32-bit words the pixel kernel stores.  A tie is rounded down where rounding
+// half up would round up, in one of two cases; unrounded samples are sums of products of floats and all but
+// never ties, and one level is the bar for pixels.
+JPGD_HD uint32_t pack_u8(float v, uint32_t byte, uint32_t word) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    // the same in three instructions: clamp v + 0.5 to [0, 255.5], then truncate
-    return (uint32_t)__builtin_amdgcn_fmed3f(v + 0.5f, 0.0f, 255.5f);
+    return __builtin_amdgcn_cvt_pk_u8_f32(v, byte, word);
 #else
-    float r = __builtin_floorf(v + 0.5f);
+    float r = v != v ? 0.0f : __builtin_rintf(v);  // the default rounding mode: nearest, ties to even
     r = r < 0.0f ? 0.0f : (r > 255.0f ? 255.0f : r);
-    return (uint32_t)r;
+    const uint32_t sh = 8u * (byte & 3u);
+    return (word & ~(0xFFu << sh)) | ((uint32_t)r << sh);
 #endif
 }
 
-// JFIF YCbCr -> RGB on unrounded samples (level shift already applied), packed as R | G<<8 | B<<16
-JPGD_HD uint32_t ycc_to_rgb(float y, float cb, float cr) {
-    cb -= 128.0f;
-    cr -= 128.0f;
-    uint32_t r = to_u8(y + 1.402f * cr);
-    uint32_t g = to_u8(y - 0.344136f * cb - 0.714136f * cr);
-    uint32_t b = to_u8(y + 1.772f * cb);
-    return r | (g << 8) | (b << 16);
+// JFIF YCbCr -> RGB: what one chroma sample (level shift applied: 128 = neutral) adds to the luma sample of every
+// pixel it covers, R = Y + r, G = Y + g, B = Y + b.  Computed once per chroma sample, not per pixel.
+struct ChromaTerms {
+    float r, g, b;
+};
+JPGD_HD ChromaTerms chroma_terms(float cb, float cr) {
+    ChromaTerms t;
+    t.r = __builtin_fmaf(1.402f, cr, -1.402f * 128.0f);
+    t.g = __builtin_fmaf(-0.344136f, cb, __builtin_fmaf(-0.714136f, cr, (0.344136f + 0.714136f) * 128.0f));
+    t.b = __builtin_fmaf(1.772f, cb, -1.772f * 128.0f);
+    return t;
 }
 
 // zig-zag position -> row*8 + col, from walking the anti-diagonals (kept as a literal so that it can

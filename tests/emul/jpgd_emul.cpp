@@ -463,10 +463,12 @@ void pixels(const Emul& E, const int16_t* coef_all, uint8_t* pix) {
                     uint32_t m = px / mcu_w, xin = px % mcu_w;
                     float y = blk[(m * upm + (py >> 3) * hs + (xin >> 3)) * 72 + (py & 7) * 9 + (xin & 7)];
                     uint8_t* dst = pix + ((size_t)gy * in.width + gx) * ncomp;
-                    if (ncomp == 1) { dst[0] = (uint8_t)to_u8(y); continue; }
+                    if (ncomp == 1) { dst[0] = (uint8_t)pack_u8(y, 0u, 0u); continue; }
                     const float* cbb = &blk[(m * upm + hs * vs) * 72 + (py / vs) * 9];
-                    uint32_t rgb = ycc_to_rgb(y, cbb[xin / hs], cbb[72 + xin / hs]);
-                    dst[0] = (uint8_t)rgb; dst[1] = (uint8_t)(rgb >> 8); dst[2] = (uint8_t)(rgb >> 16);
+                    const ChromaTerms c = chroma_terms(cbb[xin / hs], cbb[72 + xin / hs]);
+                    dst[0] = (uint8_t)pack_u8(y + c.r, 0u, 0u);
+                    dst[1] = (uint8_t)pack_u8(y + c.g, 0u, 0u);
+                    dst[2] = (uint8_t)pack_u8(y + c.b, 0u, 0u);
                 }
         }
 }

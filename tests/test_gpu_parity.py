@@ -76,12 +76,15 @@ def test_small_shapes_all_layouts(sub, opt):
             _check_image(batch, 0, data)
 
 
-def test_sync_records_are_the_sequential_decoder_states():
+@pytest.mark.parametrize("sub,opt,q", [("420", False, 93), ("gray", True, 80), ("444", True, 96), ("422", False, 60)])
+def test_sync_records_are_the_sequential_decoder_states(sub, opt, q):
     """After synchronisation s_info holds, for every subsequence, the sequential decoder's state at the
     first symbol past its end, the data units completed in it and the DC-difference sums (oracle:
-    boundary_states)."""
-    px = small_image(31, 480, 640, sigma=12.0)
-    data = encode_jpeg(px, 93, "420", False).data
+    boundary_states).  The layouts differ in the number of tables (two to four) and in the codeword lengths
+    (optimised tables have codewords beyond the first-level index), which the rounds with one wavefront per
+    chain treat separately."""
+    px = small_image(31, 480, 640, ncomp=1 if sub == "gray" else 3, sigma=12.0)
+    data = encode_jpeg(px, q, sub, opt).data
     for L in (128, 1024):
         batch, rep = _decode([data], subseq_bits=L)
         rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
