@@ -29,6 +29,10 @@ JPGD_HD void idct8(float& v0, float& v1, float& v2, float& v3, float& v4, float&
     v3 = e3 + o3; v4 = e3 - o3;
 }
 
+// The first input of idct8 reaches every output multiplied by 1/(2 sqrt 2): adding 128 * 2 sqrt 2 to it adds the
+// level shift of 128 to all eight outputs.
+constexpr float kLevelShiftDc = 362.03867196751236f;
+
 // Float to 8-bit sample, written into byte `byte` (0..3) of `word`: nearest integer, ties to the even one,
 // limited to [0, 255] (NaN gives 0).  On the device this is one instruction, v_cvt_pk_u8_f32, which also does the
 // packing of four samples into the 32-bit words the pixel kernel stores.  A tie is rounded down where rounding

@@ -987,9 +987,9 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     for (uint32_t j = t; j < nblk * 8u; j += kWG) {
         float* b = blk + (j >> 3) * kBlkStride + (j & 7u) * 9u;
         float v0 = b[0], v1 = b[1], v2 = b[2], v3 = b[3], v4 = b[4], v5 = b[5], v6 = b[6], v7 = b[7];
+        v0 += kLevelShiftDc;  // the level shift of +128 on all eight outputs, as one addition to the row's DC term
         idct8(v0, v1, v2, v3, v4, v5, v6, v7);
-        b[0] = v0 + 128.0f; b[1] = v1 + 128.0f; b[2] = v2 + 128.0f; b[3] = v3 + 128.0f;
-        b[4] = v4 + 128.0f; b[5] = v5 + 128.0f; b[6] = v6 + 128.0f; b[7] = v7 + 128.0f;
+        b[0] = v0; b[1] = v1; b[2] = v2; b[3] = v3; b[4] = v4; b[5] = v5; b[6] = v6; b[7] = v7;
     }
     __syncthreads();
 
@@ -1050,37 +1050,41 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     // serves two of the four pixels when chroma is subsampled horizontally; its three colour terms are computed
     // once.  Each sample costs one addition and one conversion that also puts the byte in its place.
     const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
+    const uint32_t row_bytes = D.width * ncomp;  // a frame header holds the width in 16 bits
     for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
-        const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - py * groups_per_row) * 4u;
+        // (all factors below are far under 2^24: the 24-bit multiply runs at full rate, the 32-bit one at a quarter)
+        const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - __umul24(py, groups_per_row)) * 4u;
         const uint32_t gy = y_base + py, gx0 = x_base + px0;
         if (gy >= D.height || gx0 >= D.width) continue;
         const uint32_t m = px0 >> lmw, xin = px0 & (mcu_w - 1u);  // the 4 pixels share MCU and luma unit
-        const float* yb = blk + (m * upm + (py >> 3) * hs + (xin >> 3)) * kBlkStride + (py & 7u) * 9u + (xin & 7u);
+        const uint32_t mu = __umul24(m, upm);
+        const float* yb = blk + __umul24(mu + __umul24(py >> 3, hs) + (xin >> 3), (uint32_t)kBlkStride) + (py & 7u) * 9u + (xin & 7u);
         const float y0 = yb[0], y1 = yb[1], y2 = yb[2], y3 = yb[3];
         uint32_t w0 = 0u, w1 = 0u, w2 = 0u;
         if (ncomp == 1u) {
             w0 = pack_u8(y0, 0u, w0); w0 = pack_u8(y1, 1u, w0); w0 = pack_u8(y2, 2u, w0); w0 = pack_u8(y3, 3u, w0);
         } else {
-            const float* cbb = blk + (m * upm + hs * vs) * kBlkStride + (py >> lvs) * 9u + (xin >> lhs);
-            ChromaTerms c0, c1, c2, c3;
-            if (hs == 2u) {
-                c0 = chroma_terms(cbb[0], cbb[kBlkStride]);
-                c2 = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
-                c1 = c0;
-                c3 = c2;
-            } else {
-                c0 = chroma_terms(cbb[0], cbb[kBlkStride]);
-                c1 = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
-                c2 = chroma_terms(cbb[2], cbb[kBlkStride + 2]);
-                c3 = chroma_terms(cbb[3], cbb[kBlkStride + 3]);
-            }
+            const float* cbb = blk + __umul24(mu + hs * vs, (uint32_t)kBlkStride) + (py >> lvs) * 9u + (xin >> lhs);
             // bytes in memory: R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3
-            w0 = pack_u8(y0 + c0.r, 0u, w0); w0 = pack_u8(y0 + c0.g, 1u, w0); w0 = pack_u8(y0 + c0.b, 2u, w0);
-            w0 = pack_u8(y1 + c1.r, 3u, w0); w1 = pack_u8(y1 + c1.g, 0u, w1); w1 = pack_u8(y1 + c1.b, 1u, w1);
-            w1 = pack_u8(y2 + c2.r, 2u, w1); w1 = pack_u8(y2 + c2.g, 3u, w1); w2 = pack_u8(y2 + c2.b, 0u, w2);
-            w2 = pack_u8(y3 + c3.r, 1u, w2); w2 = pack_u8(y3 + c3.g, 2u, w2); w2 = pack_u8(y3 + c3.b, 3u, w2);
+            auto pack12 = [&](const ChromaTerms& c0, const ChromaTerms& c1, const ChromaTerms& c2, const ChromaTerms& c3) {
+                w0 = pack_u8(y0 + c0.r, 0u, w0); w0 = pack_u8(y0 + c0.g, 1u, w0); w0 = pack_u8(y0 + c0.b, 2u, w0);
+                w0 = pack_u8(y1 + c1.r, 3u, w0); w1 = pack_u8(y1 + c1.g, 0u, w1); w1 = pack_u8(y1 + c1.b, 1u, w1);
+                w1 = pack_u8(y2 + c2.r, 2u, w1); w1 = pack_u8(y2 + c2.g, 3u, w1); w2 = pack_u8(y2 + c2.b, 0u, w2);
+                w2 = pack_u8(y3 + c3.r, 1u, w2); w2 = pack_u8(y3 + c3.g, 2u, w2); w2 = pack_u8(y3 + c3.b, 3u, w2);
+            };
+            if (hs == 2u) {  // (the two cases are written out so that neither pays register moves for the other)
+                const ChromaTerms a = chroma_terms(cbb[0], cbb[kBlkStride]);
+                const ChromaTerms b = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
+                pack12(a, a, b, b);
+            } else {
+                const ChromaTerms a = chroma_terms(cbb[0], cbb[kBlkStride]);
+                const ChromaTerms b = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
+                const ChromaTerms c = chroma_terms(cbb[2], cbb[kBlkStride + 2]);
+                const ChromaTerms d = chroma_terms(cbb[3], cbb[kBlkStride + 3]);
+                pack12(a, b, c, d);
+            }
         }
-        uint8_t* dst = pix + ((size_t)gy * D.width + gx0) * ncomp;
+        uint8_t* dst = pix + (size_t)gy * row_bytes + __umul24(gx0, ncomp);
         const bool full = gx0 + 4u <= D.width;
         if (full && aligned) {
             uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);

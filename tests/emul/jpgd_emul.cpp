@@ -453,8 +453,8 @@ void pixels(const Emul& E, const int16_t* coef_all, uint8_t* pix) {
             }
             for (uint32_t j = 0; j < nblk * 8; ++j) {
                 float* b = &blk[(j >> 3) * 72 + (j & 7) * 9];
+                b[0] += kLevelShiftDc;
                 idct8(b[0], b[1], b[2], b[3], b[4], b[5], b[6], b[7]);
-                for (int e = 0; e < 8; ++e) b[e] += 128.0f;
             }
             for (uint32_t py = 0; py < mcu_h; ++py)
                 for (uint32_t px = 0; px < nm * mcu_w; ++px) {
