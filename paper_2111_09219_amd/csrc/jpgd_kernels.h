@@ -303,14 +303,21 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scan(Params P) {
     const uint32_t ii = blockIdx.x;
     const ImgDesc D = image_desc_uniform(P, ii);
     if (D.ntiles <= (uint32_t)kWG) return;  // images of up to 256 tiles: the scatter kernel sums the counts itself
-    uint32_t carry = 0u;
-    for (uint32_t base = 0; base < D.ntiles; base += kWG) {
-        uint32_t k = base + threadIdx.x;
-        uint32_t v = k < D.ntiles ? P.tile_cnt[D.tile0 + k] : 0u;
-        uint32_t chunk_total;
-        uint32_t ex = wg_excl_scan(v, scratch, &chunk_total);
-        if (k < D.ntiles) P.tile_cnt[D.tile0 + k] = carry + ex;
-        carry += chunk_total;
+    // every lane takes a run of consecutive tiles: sum, one scan over the 256 sums, then the prefixes inside the run
+    // (one pair of barriers in all; a loop of 256-tile scans was measured at 0.7 microseconds per step)
+    uint32_t* cnt = P.tile_cnt + D.tile0;
+    const uint32_t per = (D.ntiles + (uint32_t)kWG - 1u) / (uint32_t)kWG;
+    const uint32_t k0 = min(threadIdx.x * per, D.ntiles), k1 = min(k0 + per, D.ntiles);
+    uint32_t sum = 0u;
+#pragma unroll 8
+    for (uint32_t k = k0; k < k1; ++k) sum += cnt[k];
+    uint32_t carry;
+    uint32_t ex = wg_excl_scan(sum, scratch, &carry);
+#pragma unroll 8
+    for (uint32_t k = k0; k < k1; ++k) {
+        const uint32_t v = cnt[k];
+        cnt[k] = ex;
+        ex += v;
     }
     if (threadIdx.x == 0) {
         uint32_t nbytes = D.scan_bytes - carry;
@@ -788,14 +795,18 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
     const ImgDesc D = image_desc_uniform(P, ii);
     if (D.ngrp_max <= (uint32_t)kWG) return;  // images of up to 256 groups: the write kernel sums the totals itself
     const uint32_t ngrp = (P.st[ii].nsub + kWG - 1u) / kWG;
-    Seg carry = seg_zero();
-    for (uint32_t b0 = 0; b0 < ngrp; b0 += kWG) {
-        uint32_t k = b0 + threadIdx.x;
-        const Seg v = k < ngrp ? seg_unpack(P.grp_tot[D.grp0 + k]) : seg_zero();
-        Seg ct;
-        const Seg e = wg_excl_segscan(v, scratch, &ct);
-        if (k < ngrp) P.grp_pref[D.grp0 + k] = seg_pack(seg_join(carry, e));
-        carry = seg_join(carry, ct);
+    // as in k_unstuff_scan: a run of consecutive groups per lane, one scan over the 256 joined runs
+    const int4* tot = P.grp_tot + D.grp0;
+    int4* pref = P.grp_pref + D.grp0;
+    const uint32_t per = (ngrp + (uint32_t)kWG - 1u) / (uint32_t)kWG;
+    const uint32_t k0 = min(threadIdx.x * per, ngrp), k1 = min(k0 + per, ngrp);
+    Seg run = seg_zero();
+    for (uint32_t k = k0; k < k1; ++k) run = seg_join(run, seg_unpack(tot[k]));
+    Seg all;
+    Seg ex = wg_excl_segscan(run, scratch, &all);
+    for (uint32_t k = k0; k < k1; ++k) {
+        pref[k] = seg_pack(ex);
+        ex = seg_join(ex, seg_unpack(tot[k]));
     }
 }
 

@@ -327,6 +327,15 @@ def test_config3_4096_optimized_tables():
     _check_image(batch, 0, data, pixel_rects=[(0, 16, 0, 8), (120, 136, 100, 104), (240, 256, 250, 256)])
 
 
+def test_large_image_with_restart_intervals_and_small_subsequences():
+    """4096x4096 with an interval every 7 MCUs and 128-bit subsequences: more than 256 unstuff tiles and more than
+    256 scan groups, so both image-level scans run, the second one with the segmented sum of restart streams."""
+    data = config_jpeg(3, restart_interval=7).data
+    batch, rep = _decode([data], subseq_bits=128)
+    assert rep.n_subseq > 65536 * 4
+    _check_image(batch, 0, data, pixel_rects=[(0, 16, 0, 8), (240, 256, 250, 256)])
+
+
 @pytest.mark.slow
 def test_config5_flat_and_random_halves():
     """Full size: 15360x8640.  All coefficients are compared (the oracle's entropy decode takes seconds);
