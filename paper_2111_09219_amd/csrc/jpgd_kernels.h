@@ -1004,7 +1004,7 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
     }
     __syncthreads();
 
-    // output: groups of 4 horizontally adjacent pixels
+    // output
     // (sampling factors are 1 or 2: shifts instead of divisions; the one division by a free number, the
     // groups per row, goes through a reciprocal that is exact for the few hundred items of a workgroup)
     const uint32_t hs = D.hs, vs = D.vs, ncomp = D.ncomp;
@@ -1057,57 +1057,68 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
         }
         return;
     }
-    // RGB or gray: a lane produces the 4 (gray) or 12 bytes of its four pixels as whole words.  One chroma sample
-    // serves two of the four pixels when chroma is subsampled horizontally; its three colour terms are computed
-    // once.  Each sample costs one addition and one conversion that also puts the byte in its place.
+    // RGB or gray: a lane produces the 8 (gray) or 24 bytes of eight horizontally adjacent pixels -- one row of a
+    // luma data unit -- as whole words.  The colour terms of a chroma sample are computed once (a sample serves two
+    // of the pixels when chroma is subsampled horizontally); each output sample then costs one addition and one
+    // conversion that also puts the byte in its place.
+    // (all factors below are far under 2^24: the 24-bit multiply runs at full rate, the 32-bit one at a quarter)
     const bool aligned = (((size_t)D.width * ncomp) & 3u) == 0u && ((reinterpret_cast<size_t>(pix)) & 3u) == 0u;
     const uint32_t row_bytes = D.width * ncomp;  // a frame header holds the width in 16 bits
-    for (uint32_t j = t; j < groups_per_row * mcu_h; j += kWG) {
-        // (all factors below are far under 2^24: the 24-bit multiply runs at full rate, the 32-bit one at a quarter)
-        const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_gpr), px0 = (j - __umul24(py, groups_per_row)) * 4u;
+    const uint32_t rows8 = region_w >> 3;         // groups of 8 pixels per row of the workgroup's rectangle
+    const float inv_rows8 = 1.0f / (float)rows8;
+    // bytes in memory: R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3
+    auto pack12 = [](uint32_t& wa, uint32_t& wb, uint32_t& wc, float y0, float y1, float y2, float y3,
+                     const ChromaTerms& c0, const ChromaTerms& c1, const ChromaTerms& c2, const ChromaTerms& c3) {
+        wa = pack_u8(y0 + c0.r, 0u, wa); wa = pack_u8(y0 + c0.g, 1u, wa); wa = pack_u8(y0 + c0.b, 2u, wa);
+        wa = pack_u8(y1 + c1.r, 3u, wa); wb = pack_u8(y1 + c1.g, 0u, wb); wb = pack_u8(y1 + c1.b, 1u, wb);
+        wb = pack_u8(y2 + c2.r, 2u, wb); wb = pack_u8(y2 + c2.g, 3u, wb); wc = pack_u8(y2 + c2.b, 0u, wc);
+        wc = pack_u8(y3 + c3.r, 1u, wc); wc = pack_u8(y3 + c3.g, 2u, wc); wc = pack_u8(y3 + c3.b, 3u, wc);
+    };
+    for (uint32_t j = t; j < rows8 * mcu_h; j += kWG) {
+        const uint32_t py = (uint32_t)(((float)j + 0.5f) * inv_rows8), px0 = (j - __umul24(py, rows8)) * 8u;
         const uint32_t gy = y_base + py, gx0 = x_base + px0;
         if (gy >= D.height || gx0 >= D.width) continue;
-        const uint32_t m = px0 >> lmw, xin = px0 & (mcu_w - 1u);  // the 4 pixels share MCU and luma unit
+        const uint32_t m = px0 >> lmw, xin = px0 & (mcu_w - 1u);  // xin: 0, or 8 in the right half of a 16-wide MCU
         const uint32_t mu = __umul24(m, upm);
-        const float* yb = blk + __umul24(mu + __umul24(py >> 3, hs) + (xin >> 3), (uint32_t)kBlkStride) + (py & 7u) * 9u + (xin & 7u);
-        const float y0 = yb[0], y1 = yb[1], y2 = yb[2], y3 = yb[3];
-        uint32_t w0 = 0u, w1 = 0u, w2 = 0u;
+        const float* yb = blk + __umul24(mu + __umul24(py >> 3, hs) + (xin >> 3), (uint32_t)kBlkStride) + (py & 7u) * 9u;
+        const float y0 = yb[0], y1 = yb[1], y2 = yb[2], y3 = yb[3], y4 = yb[4], y5 = yb[5], y6 = yb[6], y7 = yb[7];
+        uint32_t w0 = 0u, w1 = 0u, w2 = 0u, w3 = 0u, w4 = 0u, w5 = 0u;
         if (ncomp == 1u) {
             w0 = pack_u8(y0, 0u, w0); w0 = pack_u8(y1, 1u, w0); w0 = pack_u8(y2, 2u, w0); w0 = pack_u8(y3, 3u, w0);
+            w1 = pack_u8(y4, 0u, w1); w1 = pack_u8(y5, 1u, w1); w1 = pack_u8(y6, 2u, w1); w1 = pack_u8(y7, 3u, w1);
         } else {
             const float* cbb = blk + __umul24(mu + hs * vs, (uint32_t)kBlkStride) + (py >> lvs) * 9u + (xin >> lhs);
-            // bytes in memory: R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3
-            auto pack12 = [&](const ChromaTerms& c0, const ChromaTerms& c1, const ChromaTerms& c2, const ChromaTerms& c3) {
-                w0 = pack_u8(y0 + c0.r, 0u, w0); w0 = pack_u8(y0 + c0.g, 1u, w0); w0 = pack_u8(y0 + c0.b, 2u, w0);
-                w0 = pack_u8(y1 + c1.r, 3u, w0); w1 = pack_u8(y1 + c1.g, 0u, w1); w1 = pack_u8(y1 + c1.b, 1u, w1);
-                w1 = pack_u8(y2 + c2.r, 2u, w1); w1 = pack_u8(y2 + c2.g, 3u, w1); w2 = pack_u8(y2 + c2.b, 0u, w2);
-                w2 = pack_u8(y3 + c3.r, 1u, w2); w2 = pack_u8(y3 + c3.g, 2u, w2); w2 = pack_u8(y3 + c3.b, 3u, w2);
-            };
+            const float* crb = cbb + kBlkStride;
             if (hs == 2u) {  // (the two cases are written out so that neither pays register moves for the other)
-                const ChromaTerms a = chroma_terms(cbb[0], cbb[kBlkStride]);
-                const ChromaTerms b = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
-                pack12(a, a, b, b);
+                const ChromaTerms a = chroma_terms(cbb[0], crb[0]), b = chroma_terms(cbb[1], crb[1]);
+                pack12(w0, w1, w2, y0, y1, y2, y3, a, a, b, b);
+                const ChromaTerms c = chroma_terms(cbb[2], crb[2]), d = chroma_terms(cbb[3], crb[3]);
+                pack12(w3, w4, w5, y4, y5, y6, y7, c, c, d, d);
             } else {
-                const ChromaTerms a = chroma_terms(cbb[0], cbb[kBlkStride]);
-                const ChromaTerms b = chroma_terms(cbb[1], cbb[kBlkStride + 1]);
-                const ChromaTerms c = chroma_terms(cbb[2], cbb[kBlkStride + 2]);
-                const ChromaTerms d = chroma_terms(cbb[3], cbb[kBlkStride + 3]);
-                pack12(a, b, c, d);
+                {
+                    const ChromaTerms a = chroma_terms(cbb[0], crb[0]), b = chroma_terms(cbb[1], crb[1]);
+                    const ChromaTerms c = chroma_terms(cbb[2], crb[2]), d = chroma_terms(cbb[3], crb[3]);
+                    pack12(w0, w1, w2, y0, y1, y2, y3, a, b, c, d);
+                }
+                {
+                    const ChromaTerms a = chroma_terms(cbb[4], crb[4]), b = chroma_terms(cbb[5], crb[5]);
+                    const ChromaTerms c = chroma_terms(cbb[6], crb[6]), d = chroma_terms(cbb[7], crb[7]);
+                    pack12(w3, w4, w5, y4, y5, y6, y7, a, b, c, d);
+                }
             }
         }
         uint8_t* dst = pix + (size_t)gy * row_bytes + __umul24(gx0, ncomp);
-        const bool full = gx0 + 4u <= D.width;
-        if (full && aligned) {
+        if (gx0 + 8u <= D.width && aligned) {
             uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
             d32[0] = w0;
+            d32[1] = w1;
             if (ncomp == 3u) {
-                d32[1] = w1;
-                d32[2] = w2;
+                d32[2] = w2; d32[3] = w3; d32[4] = w4; d32[5] = w5;
             }
         } else {
-            const uint32_t nbytes = min(4u, D.width - gx0) * ncomp;
+            const uint32_t nbytes = min(8u, D.width - gx0) * ncomp;
             for (uint32_t e = 0; e < nbytes; ++e) {
-                const uint32_t w = e < 4u ? w0 : (e < 8u ? w1 : w2);
+                const uint32_t w = e < 4u ? w0 : (e < 8u ? w1 : (e < 12u ? w2 : (e < 16u ? w3 : (e < 20u ? w4 : w5))));
                 dst[e] = (uint8_t)(w >> (8u * (e & 3u)));
             }
         }
