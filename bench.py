@@ -27,10 +27,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # counters read for a plain copy of known size; taken from the summaries in profiles/ (same commands).
 MEASURED_TRAFFIC = {
     ("hd1088_444_q90", "sync_intra"): 1.791e6,
-    ("hd1088_444_q90", "write"): 17.08e6,
-    ("hd1088_444_q90", "pixels"): 18.91e6,
+    ("hd1088_444_q90", "write"): 17.09e6,
+    ("hd1088_444_q90", "pixels"): 18.92e6,
     ("uhd16k_420_q92_flat_random", "sync_intra"): 84.79e6,
-    ("uhd16k_420_q92_flat_random", "write"): 1162.0e6,
+    ("uhd16k_420_q92_flat_random", "write"): 1123.0e6,
     ("uhd16k_420_q92_flat_random", "pixels"): 796.3e6,
 }
 
