@@ -585,8 +585,10 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     bool active = valid && (t + 1u < t1);
     uint32_t tt = t + 1u;
     uint32_t waves_used = kWG / 64u;
-    // the wavefront-per-chain code knows neither restart intervals nor more than four tables
-    const uint32_t coop_max = (restart || P.lut_slots > 4u) ? 0u : P.coop_max;
+    // The wavefront-per-chain code does not know more than four tables.  In a workgroup that sees restart intervals
+    // a chain may fall back to a single lane for a round (below): at most one chain per wavefront then, so that
+    // such rounds never take longer than the packed ones they replace.
+    const uint32_t coop_max = P.lut_slots > 4u ? 0u : (restart ? min(P.coop_max, (uint32_t)(kWG / 64)) : P.coop_max);
     uint32_t coop_n = 0u;
     for (uint32_t round = 0u;; ++round) {
         const uint64_t bal = __ballot(active);
@@ -679,12 +681,38 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
                 const uint32_t ctt = __builtin_amdgcn_readfirstlane(mv_tt[rd + k]);
                 int64_t cdc = 0;
                 const uint32_t limit = ((uint32_t)(u_base + (int32_t)ctt) + 1u) << P.logL;
-                coop_span_sync(cp, cu, cz, cnb, cdc, limit, u_first, u_nwords, unit_word, u_upm, P.lut_slots, fetch, lut_s);
+                // The wavefront's decoder does not know the rules of restart intervals.  A chain whose stretch holds
+                // no interval start does not need them (decode_span_sync_rst is the plain loop then); one whose
+                // stretch does is decoded by a single lane for this round.
+                uint32_t crossed = 0u;
+                uint32_t B = kNoBoundary;
+                if (restart) B = __builtin_amdgcn_readfirstlane(next_boundary(__builtin_amdgcn_readfirstlane(cp), limit + 64u, bword));
+                if (B == kNoBoundary) {
+                    coop_span_sync(cp, cu, cz, cnb, cdc, limit, u_first, u_nwords, unit_word, u_upm, P.lut_slots, fetch, lut_s);
+                } else {
+                    if (lane == 0u) {
+                        Lane cl;
+                        BitWin cw;
+                        cl.p = cp; cl.u = cu; cl.z = cz; cl.nb = 0u;
+                        win_init(cw, cl.p, (cl.p >> 5) - first_word, fetch);
+                        prime(cl, cw, sx, lut_s);
+                        decode_span_sync_rst(cl, cw, limit, cdc, crossed, sx, fetch, lut_s, bword);
+                        cp = cl.p; cu = cl.u; cz = cl.z; cnb = cl.nb;
+                    }
+                    cp = __builtin_amdgcn_readfirstlane(cp);
+                    cu = __builtin_amdgcn_readfirstlane(cu);
+                    cz = __builtin_amdgcn_readfirstlane(cz);
+                    cnb = __builtin_amdgcn_readfirstlane(cnb);
+                    crossed = __builtin_amdgcn_readfirstlane(crossed);
+                    const uint32_t dlo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)cdc);
+                    const uint32_t dhi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)cdc >> 32));
+                    cdc = (int64_t)(((uint64_t)dhi << 32) | (uint64_t)dlo);
+                }
                 const uint32_t x = pack_state(cp - limit, cz, cu);
                 const bool synced = x == sw[ctt];
                 if (lane == 0u) {
                     sw[ctt] = x;
-                    pnb[ctt] = cnb;
+                    pnb[ctt] = cnb | (crossed << 31);
                     pdc01[ctt] = pack_dc01(cdc);
                     pdc2[ctt] = pack_dc2(cdc);
                     mv_p[wr + k] = cp;

@@ -267,19 +267,29 @@ void sync_intra(Emul& E) {
             ++rounds;
             uint32_t now = 0;
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) now += active[t] ? 1u : 0u;
-            const bool coop = !restart && im.nslots <= 4u && now <= g_coop_max;  // stays true once it is
+            const bool coop = im.nslots <= 4u && now <= (restart ? std::min(g_coop_max, (uint32_t)(kWG / 64)) : g_coop_max);  // stays true once it is
             uint32_t unit_word[64];
             for (uint32_t lane = 0; lane < 64; ++lane) unit_word[lane] = coop_unit_word(E.sx, lane);
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
                 if (!active[t]) continue;
                 if (coop) {
                     const uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
-                    uint32_t nb;
-                    coop_span_sync(l[t].p, l[t].u, l[t].z, nb, dcacc[t], limit, first_word, nwords, unit_word, E.sx.upm,
-                                   im.nslots, fetch, im.lut.data());
+                    uint32_t nb, crossed = 0;
+                    // a chain whose stretch holds an interval start is decoded by one lane with the interval rules
+                    if (!restart || next_boundary(l[t].p, limit + 64u, bword) == kNoBoundary) {
+                        coop_span_sync(l[t].p, l[t].u, l[t].z, nb, dcacc[t], limit, first_word, nwords, unit_word, E.sx.upm,
+                                       im.nslots, fetch, im.lut.data());
+                    } else {
+                        l[t].nb = 0;
+                        dcacc[t] = 0;
+                        win_init(bw[t], l[t].p, (l[t].p >> 5) - first_word, fetch);
+                        prime(l[t], bw[t], E.sx, im.lut.data());
+                        decode_span_sync_rst(l[t], bw[t], limit, dcacc[t], crossed, E.sx, fetch, im.lut.data(), bword);
+                        nb = l[t].nb;
+                    }
                     uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u);
                     bool synced = x == sw[tt[t]];
-                    sw[tt[t]] = x; pnb[tt[t]] = nb;
+                    sw[tt[t]] = x; pnb[tt[t]] = nb | (crossed << 31);
                     pdc01[tt[t]] = pack_dc01(dcacc[t]);
                     pdc2[tt[t]] = pack_dc2(dcacc[t]);
                     ++tt[t];
