@@ -25,6 +25,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain copy of known size; taken from the summaries in profiles/ (same commands).
+# Share of the chip's vector issue slots the kernel uses and lanes switched on per vector instruction, from the SQ
+# counters in the same summaries (the entropy kernels are bound by dependent instruction issue, not by HBM).
+MEASURED_ISSUE = {
+    ("hd1088_444_q90", "sync_intra"): {"valu_issue_frac": 0.104, "lanes_per_valu_instr": 40.2},
+    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.382, "lanes_per_valu_instr": 38.2},
+}
+
 MEASURED_TRAFFIC = {
     ("hd1088_444_q90", "sync_intra"): 1.791e6,
     ("hd1088_444_q90", "write"): 17.09e6,
@@ -266,6 +273,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
                      "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,
+                     "issue": MEASURED_ISSUE.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,
                      "avg_launch_ms": round(dom_avg_ms, 5), "timed_launches": dom_launches,
                      "alg_bytes_per_launch": alg},
         "cpu_baseline": cpu,
