@@ -213,6 +213,30 @@ def test_planar_output(sub):
                 assert (tail == 0x5A).all()
 
 
+def test_coefficients_only():
+    """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
+    its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
+    passed stays untouched.  A corrupt stream is still reported."""
+    px = small_image(41, 200, 328, sigma=10.0)
+    enc = encode_jpeg(px, 88, "420", False)
+    data = enc.data
+    ref = OracleImage(data).coefficients()
+    batch = J.prepare_batch([data], J.Config.make(), want_pixels=False)
+    batch.decode()
+    assert np.array_equal(batch.coefficients(0).cpu().numpy(), ref)
+    batch = J.prepare_batch([data], J.Config.make(flags=J.F_NO_PIXELS))
+    batch.d_pixels.fill_(0x5A)
+    batch.d_coef.fill_(-7)
+    batch.decode()
+    assert np.array_equal(batch.coefficients(0).cpu().numpy(), ref)
+    assert int((batch.d_pixels != 0x5A).sum().item()) == 0
+    short = np.concatenate([data[:enc.scan_offset + enc.scan_len // 2], np.array([0xFF, 0xD9], np.uint8)])
+    batch = J.prepare_batch([short], J.Config.make(), want_pixels=False)
+    with pytest.raises(J.JpgdError) as e:
+        batch.decode()
+    assert e.value.name == "CORRUPT"
+
+
 def test_unstuff_kernel_alone():
     import torch
     rng = np.random.default_rng(9)
