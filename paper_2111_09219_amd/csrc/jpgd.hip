@@ -328,7 +328,7 @@ uint32_t staged_max_bits() {
 
 // with restart intervals the kernels also keep the interval-start bitmap of the staged bytes: one bit per byte
 size_t lds_bitmap_bytes(uint32_t L, bool restart) {
-    return restart ? ((size_t)(kWG * (L / 32) + 4 + 7) / 8 + 2) * 4 : 0;
+    return restart && L <= (uint32_t)kBitmapLdsMaxL ? ((size_t)(kWG * (L / 32) + 4 + 7) / 8 + 2) * 4 : 0;
 }
 size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;

@@ -14,6 +14,11 @@ namespace jpgd {
 // subsequence : L bits of the unstuffed stream, one lane
 // sequence    : the subsequences one workgroup synchronises among itself ("b" in the paper)
 constexpr int kWG = 256;          // lanes per workgroup of the sync and write kernels
+// Streams with restart intervals: the synchronisation and write kernels keep the interval-start bitmap of their
+// stretch of the stream in LDS up to this subsequence size.  Beyond it the copy (4 KB at 1024 bits) would cost a
+// third of the workgroups a CU can hold, and a lane asks for a bitmap word only once or twice per subsequence,
+// so the words are read from memory instead.
+constexpr int kBitmapLdsMaxL = 256;
 constexpr int kMaxOverlap = 191;  // warm-up lanes a sequence may borrow from its predecessor
 
 // ---- Huffman lookup tables ---------------------------------------------------------------------

@@ -203,13 +203,16 @@ __device__ __forceinline__ void stage_stream(const uint8_t* stream_img, uint32_t
 // word k of the bitmap is then bm_s[k - (first_word >> 3)]
 // Returns the OR of the words this lane copied: most workgroups of a scan with long intervals find no interval
 // start at all in their stretch and can run the plain loops.
-__device__ __forceinline__ uint32_t stage_bitmap(const uint32_t* bmap_img, uint32_t first_word, uint32_t nwords, uint32_t* bm_s) {
+// With keep == false nothing is stored: the words are only looked at (subsequences of more than kBitmapLdsMaxL bits,
+// whose kernels then read the few bitmap words they need from memory; see kBitmapLdsMaxL).
+__device__ __forceinline__ uint32_t stage_bitmap(const uint32_t* bmap_img, uint32_t first_word, uint32_t nwords, uint32_t* bm_s,
+                                                 bool keep) {
     const uint32_t k0 = first_word >> 3;
     const uint32_t n = ((first_word + nwords + 7u) >> 3) - k0 + 1u;
     uint32_t seen = 0u;
     for (uint32_t k = threadIdx.x; k < n; k += blockDim.x) {
         const uint32_t v = bmap_img[k0 + k];
-        bm_s[k] = v;
+        if (keep) bm_s[k] = v;
         seen |= v;
     }
     return seen;
@@ -550,8 +553,10 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
     const uint32_t bm_k0 = first_word >> 3;
     uint32_t seen = 0u;
-    if (D.restart) seen = stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
-    auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
+    const bool bm_lds = (1u << P.logL) <= (uint32_t)kBitmapLdsMaxL;
+    const uint32_t* bmap_img = P.bmap + D.bmap_off;
+    if (D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
+    auto bword = [&](uint32_t k) { return bm_lds ? bm_s[k - bm_k0] : bmap_img[k]; };
     const bool restart = __syncthreads_or(seen != 0u) != 0;  // also: staged tables and stream are complete
 
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
@@ -865,8 +870,10 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
     const uint32_t bm_k0 = first_word >> 3;
     uint32_t seen = 0u;
-    if (D.restart) seen = stage_bitmap(P.bmap + D.bmap_off, first_word, nwords, bm_s);
-    auto bword = [&](uint32_t k) { return bm_s[k - bm_k0]; };
+    const bool bm_lds = (1u << P.logL) <= (uint32_t)kBitmapLdsMaxL;
+    const uint32_t* bmap_img = P.bmap + D.bmap_off;
+    if (D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
+    auto bword = [&](uint32_t k) { return bm_lds ? bm_s[k - bm_k0] : bmap_img[k]; };
     const bool restart = __syncthreads_or(seen != 0u) != 0;  // interval starts in this group's stretch of the stream?
 
     const uint32_t t = threadIdx.x;
