@@ -213,6 +213,19 @@ def test_planar_output(sub):
                 assert (tail == 0x5A).all()
 
 
+@pytest.mark.parametrize("sub,shape", [("gray", (9, 65535)), ("420", (40001, 9)), ("444", (1, 1)), ("422", (3, 20000))])
+def test_extreme_shapes(sub, shape):
+    """The widest frame a header can describe, very tall and very narrow ones, a single pixel; RGB and planes."""
+    px = small_image(23, *shape, ncomp=1 if sub == "gray" else 3, sigma=7.0)
+    data = encode_jpeg(px, 80, sub, False).data
+    batch, rep = _decode([data])
+    o = _check_image(batch, 0, data)
+    batch, rep = _decode([data], flags=J.F_PLANAR)
+    want = o.planes(o.coefficients())
+    for got, ref in zip(batch.planes(0), want):
+        assert np.abs(got.cpu().numpy().astype(np.int16) - ref.astype(np.int16)).max() <= PIXEL_TOL
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was

@@ -307,6 +307,19 @@ def test_host_walkthrough_with_restart_intervals(emul, sub, opt, q, shape, L, H,
         assert np.array_equal(col.astype(np.uint16).view(np.int16)[keep], bs["dcsum"][keep, c].astype(np.int16))
 
 
+@pytest.mark.parametrize("sub,shape", [("gray", (9, 65535)), ("420", (40001, 9)), ("444", (1, 1)), ("422", (3, 20000))])
+def test_host_walkthrough_extreme_shapes(emul, sub, shape):
+    """The widest frame a header can describe, very tall and very narrow ones, a single pixel."""
+    px = small_image(23, *shape, ncomp=1 if sub == "gray" else 3, sigma=7.0)
+    data = encode_jpeg(px, 80, sub, False).data
+    rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, 128, 16)
+    assert rc == 0 and stats[3] == 0
+    ref = o.coefficients()
+    assert np.array_equal(coef, ref)
+    refpix = o.pixels(ref).reshape(pix.shape).astype(int)
+    assert np.abs(pix.astype(int) - refpix).max() <= 1
+
+
 def test_host_walkthrough_dense_ff_and_tiny_streams(emul):
     rng = np.random.default_rng(1)
     px = (rng.integers(0, 2, size=(64, 64)) * 255).astype(np.uint8)
