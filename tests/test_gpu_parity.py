@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 import paper_2111_09219_amd as J
-from oracle import OracleImage, unstuff_bytes
+from oracle import OracleError, OracleImage, unstuff_bytes
 from workloads import CONFIGS, config_jpeg, encode_jpeg, small_image
 
 pytestmark = pytest.mark.gpu
@@ -355,6 +355,52 @@ def test_corrupt_streams_are_reported_not_written_out_of_bounds():
         except J.JpgdError as err:
             assert err.name == "CORRUPT"
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("sub,opt,ri", [("444", True, 0), ("420", False, 0), ("422", True, 3)])
+def test_random_damage_is_reported_or_decoded_like_the_oracle(sub, opt, ri):
+    """Random bytes of the entropy-coded segment are overwritten (the host walk-through, with bounds checks on
+    every access, runs the same experiment in the CPU suite).  The call either reports CORRUPT or leaves exactly the
+    coefficients the sequential oracle produces from the same bytes, and never touches the guard areas."""
+    import torch
+    rng = np.random.default_rng(4242 + ri)
+    enc = encode_jpeg(small_image(61, 72, 120, ncomp=1 if sub == "gray" else 3, sigma=12.0), 85, sub, opt, restart_interval=ri)
+    agreed = 0
+    for trial in range(12):
+        bad = enc.data.copy()
+        for _ in range(int(rng.integers(1, 4))):
+            pos = enc.scan_offset + int(rng.integers(0, enc.scan_len))
+            if bad[pos] == 0xFF or bad[pos - 1] == 0xFF:
+                continue
+            bad[pos] = int(rng.integers(0, 255))
+        try:
+            o = OracleImage(bad)
+        except OracleError:
+            continue
+        batch = J.prepare_batch([bad], J.Config.make(subseq_bits=[128, 256, 1024][trial % 3]))
+        n_coef, n_pix = 64 * o.total_units, o.width * o.height * o.ncomp
+        guard_c = torch.full((4096,), 0x5A5A, dtype=torch.int16, device="cuda")
+        guard_p = torch.full((4096,), 0x5A, dtype=torch.uint8, device="cuda")
+        batch.d_coef = torch.cat([batch.d_coef[:n_coef], guard_c])
+        batch.d_pixels = torch.cat([batch.d_pixels[:n_pix], guard_p])
+        batch._cargs = None
+        try:
+            batch.decode()
+            ok = True
+        except J.JpgdError as err:
+            assert err.name == "CORRUPT"
+            ok = False
+        torch.cuda.synchronize()
+        assert int((batch.d_coef[n_coef:] != 0x5A5A).sum().item()) == 0
+        assert int((batch.d_pixels[n_pix:] != 0x5A).sum().item()) == 0
+        if ok:
+            try:
+                ref = o.coefficients()
+            except OracleError:
+                continue
+            assert np.array_equal(batch.coefficients(0).cpu().numpy(), ref)
+            agreed += 1
+    print("decoded like the oracle: %d of 12" % agreed)
 
 
 @pytest.mark.slow

@@ -340,6 +340,42 @@ def test_host_walkthrough_flags_corrupt_streams(emul):
         OracleImage(short).coefficients()
 
 
+@pytest.mark.parametrize("sub,opt,ri", [("gray", False, 0), ("444", True, 0), ("420", False, 0), ("422", True, 3), ("420", False, 1)])
+def test_host_walkthrough_survives_random_damage(emul, sub, opt, ri):
+    """Random bytes of the entropy-coded segment are overwritten.  The walk-through (whose fetches, stores and
+    cleared ranges are bounds-checked and abort the process when violated) must either report the stream as corrupt
+    or produce exactly what the sequential oracle produces from the same bytes, if that accepts them too."""
+    rng = np.random.default_rng(977 + ri)
+    enc = encode_jpeg(small_image(61, 72, 120, ncomp=1 if sub == "gray" else 3, sigma=12.0), 85, sub, opt, restart_interval=ri)
+    accepted = 0
+    for trial in range(40):
+        bad = enc.data.copy()
+        for _ in range(int(rng.integers(1, 4))):
+            pos = enc.scan_offset + int(rng.integers(0, enc.scan_len))
+            v = int(rng.integers(0, 255))        # never 0xFF: a marker in the middle would only shorten the scan
+            if bad[pos] == 0xFF or bad[pos - 1] == 0xFF:
+                continue
+            bad[pos] = v
+        L, H = [(128, 16), (256, 0), (1024, 32)][trial % 3]
+        emul.emul_set_coop_max([6, 64, 0][trial % 3])
+        try:
+            try:
+                rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, bad, L, H)
+            except OracleError:
+                continue                         # the oracle's parser already refuses the file
+        finally:
+            emul.emul_set_coop_max(6)
+        assert rc in (0, -6)
+        if rc == 0:
+            try:
+                ref = o.coefficients()
+            except OracleError:
+                continue                         # e.g. padding bits or marker numbers only the oracle checks
+            accepted += 1
+            assert np.array_equal(coef, ref)
+    print("accepted by both: %d of 40" % accepted)
+
+
 def _damaged_restart_files():
     """A scan with restart intervals from which (a) one marker, (b) most of one interval's bytes are missing.
     (A few missing bytes need not be noticed: the decoder falls back into step and the interval still ends
