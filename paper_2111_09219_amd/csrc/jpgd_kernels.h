@@ -864,6 +864,25 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t first_word = i0 * wps;
     const uint32_t nwords = nloc * wps + 4u;
     __shared__ UnitRow rows[8];
+    // the lane's record, its predecessor's state and the totals of the groups before this one are asked for
+    // first: their way from memory overlaps the staging below
+    const uint32_t t = threadIdx.x;
+    const uint32_t i = i0 + t;
+    const bool valid = t < nloc;
+    const SInfo* rec = P.sinfo + D.sub0;
+    SInfo mine = {0u, 0u, 0u, 0u};
+    uint32_t xprev = 0u;
+    if (valid) {
+        mine = rec[i];
+        if (i > 0u) xprev = rec[i - 1u].x;
+    }
+    const bool few_groups = D.ngrp_max <= (uint32_t)kWG;
+    int4 before = make_int4(0, 0, 0, 0);
+    if (few_groups) {
+        if (t < lg) before = P.grp_tot[D.grp0 + t];
+    } else {
+        before = P.grp_pref[wg];
+    }
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
@@ -876,24 +895,13 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     auto bword = [&](uint32_t k) { return bm_lds ? bm_s[k - bm_k0] : bmap_img[k]; };
     const bool restart = __syncthreads_or(seen != 0u) != 0;  // interval starts in this group's stretch of the stream?
 
-    const uint32_t t = threadIdx.x;
-    const uint32_t i = i0 + t;
-    const bool valid = t < nloc;
-    const SInfo* rec = P.sinfo + D.sub0;
-    SInfo mine = {0u, 0u, 0u, 0u};
-    uint32_t xprev = 0u;
-    if (valid) {
-        mine = rec[i];
-        if (i > 0u) xprev = rec[i - 1u].x;
-    }
     // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
     // plus the group's prefix
     Seg gp;
-    if (D.ngrp_max <= (uint32_t)kWG) {
-        const Seg v = (t < lg) ? seg_unpack(P.grp_tot[D.grp0 + t]) : seg_zero();
-        wg_excl_segscan(v, scratch, &gp);
+    if (few_groups) {
+        wg_excl_segscan(seg_unpack(before), scratch, &gp);  // (all zero from lane lg on: the identity of the join)
     } else {
-        gp = seg_unpack(P.grp_pref[wg]);
+        gp = seg_unpack(before);
     }
     Seg grp_tot;
     const Seg ex = seg_join(gp, wg_excl_segscan(seg_of_record(mine), scratch, &grp_tot));
