@@ -419,12 +419,14 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
             for (int k = 0; k < 64; ++k) qts[d.qt_off + c * 64 + k] = in.qt[in.tq[c]][k];
     }
     uint8_t* ws = (uint8_t*)d_workspace;
-    {
-        const uint32_t n16 = (uint32_t)((pl.h.upload_bytes + 15u) / 16u);
-        const uint32_t wgs = (n16 + kWG - 1u) / kWG;
-        hipLaunchKernelGGL(k_upload, dim3(wgs < 256u ? wgs : 256u), dim3(kWG), 0, stream, (const uint4*)g_stage.buf_dev,
-                           (uint4*)ws, n16);
-    }
+    // The parameter block goes from the pinned buffer into the workspace: for a batch by a kernel of its own (the
+    // first kernel of the path already looks its image up in the block), for a single image by extra workgroups of
+    // that first kernel, which then finds all it needs in its arguments.
+    const uint32_t up_n16 = (uint32_t)((pl.h.upload_bytes + 15u) / 16u);
+    uint32_t up_wgs = (up_n16 + kWG - 1u) / kWG;
+    if (up_wgs > 256u) up_wgs = 256u;
+    if (n > 1)
+        hipLaunchKernelGGL(k_upload, dim3(up_wgs), dim3(kWG), 0, stream, (const uint4*)g_stage.buf_dev, (uint4*)ws, up_n16);
 
     Params P;
     P.img = (const ImgDesc*)(ws + pl.h.off_img);
@@ -451,6 +453,10 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.coop_max = kCoopMax;
     P.verdict = nullptr;
     P.ticket = 0u;
+    P.up_src = (const uint4*)g_stage.buf_dev;
+    P.up_dst = (uint4*)ws;
+    P.up_n16 = up_n16;
+    P.up_wgs = n > 1 ? 0u : up_wgs;
     P.img0 = pl.img[0];
 
     // optional bracketing of single kernels with events (jpgd_config.timing_mask)
@@ -481,7 +487,8 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         if ((rc = t_end(K)) != JPGD_OK) return rc;                            \
     } while (0)
 
-    LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles, kWG, 0);
+    LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles + P.up_wgs, kWG, 0);
+    P.up_wgs = 0u;
     bool big_tiles = false, big_groups = false;  // the two image-level scans are only needed beyond 256 tiles / groups
     for (int i = 0; i < n; ++i) {
         big_tiles = big_tiles || pl.img[i].ntiles > (uint32_t)kWG;

@@ -18,7 +18,8 @@ struct Params {
     Status* status;
     const uint8_t* scans;
     uint8_t* stream;        // unstuffed streams, image i at img[i].stream_off
-    uint32_t* tile_cnt;     // per unstuff tile: bytes removed in it, then (in place) bytes removed before it
+    uint32_t* tile_cnt;     // per unstuff tile: bytes removed in it (low half) and restart markers met in it (high
+                            // half), then (in place, images of more than 256 tiles) bytes removed before it
     SInfo* sinfo;
     int4* grp_tot;          // per group of kWG subsequences: (units, dc0, dc1, dc2) totals
     int4* grp_pref;         // exclusive prefix of grp_tot inside the image
@@ -36,6 +37,13 @@ struct Params {
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
+    // A call with one image has the last up_wgs workgroups of k_unstuff_count copy the call's parameter block
+    // (up_n16 16-byte words) from pinned host memory into the workspace: that kernel does not need the block, all
+    // later ones do, and a kernel of its own for the copy would cost a dispatch.  up_wgs = 0: nothing to copy.
+    const uint4* up_src;
+    uint4* up_dst;
+    uint32_t up_n16;
+    uint32_t up_wgs;
     // pixel kernel: where its first lane reports the outcome of the write kernel before anything else (pinned host
     // memory: flags, inter_changed, .., ticket in word 15; null = somebody else reports) and this call's ticket
     uint32_t* verdict;
@@ -276,6 +284,11 @@ __device__ __forceinline__ UnstuffLane unstuff_load(const uint8_t* scan, uint32_
 __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     __shared__ uint32_t scratch[8];
     const uint32_t wg = blockIdx.x;
+    if (P.up_wgs && wg >= gridDim.x - P.up_wgs) {  // the copy of the parameter block (one image per call only)
+        const uint32_t first = gridDim.x - P.up_wgs;
+        for (uint32_t k = (wg - first) * kWG + threadIdx.x; k < P.up_n16; k += P.up_wgs * kWG) P.up_dst[k] = P.up_src[k];
+        return;
+    }
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.tile0; });
     const ImgDesc D = image_desc_uniform(P, ii);
     const uint32_t lt = wg - D.tile0;
@@ -286,17 +299,16 @@ __global__ __launch_bounds__(kWG) void k_unstuff_count(Params P) {
     uint32_t removed = u.nvalid - (uint32_t)__popc(u.keep_mask);
     uint32_t total;
     wg_excl_scan(removed, scratch, &total);
-    if (threadIdx.x == 0) P.tile_cnt[wg] = total;
+    uint32_t marks = 0u;
     if (restart) {
         // this tile's share of the interval-start bitmap is cleared here, the scatter kernel sets the bits;
         // the markers are counted so that the write pass can tell whether all intervals are there
         uint32_t* bm = P.bmap + D.bmap_off + lt * 128u;
         if (threadIdx.x < 128u) bm[threadIdx.x] = 0u;
         if (lt == D.ntiles - 1u && threadIdx.x < 128u) bm[128u + threadIdx.x] = 0u;
-        uint32_t marks;
         wg_excl_scan((uint32_t)__popc(u.mark_mask), scratch, &marks);
-        if (threadIdx.x == 0 && marks) atomicAdd(&P.st[ii].markers, marks);
     }
+    if (threadIdx.x == 0) P.tile_cnt[wg] = total | (marks << 16);  // at most 4096 and 2048
 }
 
 // one workgroup per image: per-tile counts -> bytes removed before each tile; unstuffed length and
@@ -311,19 +323,25 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scan(Params P) {
     uint32_t* cnt = P.tile_cnt + D.tile0;
     const uint32_t per = (D.ntiles + (uint32_t)kWG - 1u) / (uint32_t)kWG;
     const uint32_t k0 = min(threadIdx.x * per, D.ntiles), k1 = min(k0 + per, D.ntiles);
-    uint32_t sum = 0u;
-#pragma unroll 8
-    for (uint32_t k = k0; k < k1; ++k) sum += cnt[k];
-    uint32_t carry;
-    uint32_t ex = wg_excl_scan(sum, scratch, &carry);
+    uint32_t sum = 0u, msum = 0u;
 #pragma unroll 8
     for (uint32_t k = k0; k < k1; ++k) {
         const uint32_t v = cnt[k];
+        sum += v & 0xFFFFu;
+        msum += v >> 16;
+    }
+    uint32_t carry, markers;
+    wg_excl_scan(msum, scratch, &markers);
+    uint32_t ex = wg_excl_scan(sum, scratch, &carry);
+#pragma unroll 8
+    for (uint32_t k = k0; k < k1; ++k) {
+        const uint32_t v = cnt[k] & 0xFFFFu;
         cnt[k] = ex;
         ex += v;
     }
     if (threadIdx.x == 0) {
         uint32_t nbytes = D.scan_bytes - carry;
+        P.st[ii].markers = markers;
         P.st[ii].nbytes = nbytes;
         uint32_t L = 1u << P.logL;
         P.st[ii].nsub = (uint32_t)(((uint64_t)nbytes * 8u + L - 1u) >> P.logL);
@@ -352,12 +370,15 @@ __global__ __launch_bounds__(kWG) void k_unstuff_scatter(Params P) {
     // bytes removed before this tile: from the scan kernel, or, for images of up to 256 tiles, summed here
     uint32_t before, nbytes;
     if (D.ntiles <= (uint32_t)kWG) {
-        const uint32_t v = threadIdx.x < D.ntiles ? P.tile_cnt[D.tile0 + threadIdx.x] : 0u;
-        uint32_t all;
+        const uint32_t raw = threadIdx.x < D.ntiles ? P.tile_cnt[D.tile0 + threadIdx.x] : 0u;
+        const uint32_t v = raw & 0xFFFFu;
+        uint32_t all, markers = 0u;
         wg_excl_scan(v, scratch, &all);
         wg_excl_scan(threadIdx.x < lt ? v : 0u, scratch, &before);
+        if (D.restart != 0u && lt == 0u) wg_excl_scan(raw >> 16, scratch, &markers);
         nbytes = D.scan_bytes - all;
         if (lt == 0u && threadIdx.x == 0u) {
+            P.st[ii].markers = markers;
             P.st[ii].nbytes = nbytes;
             P.st[ii].nsub = (uint32_t)(((uint64_t)nbytes * 8u + (1u << P.logL) - 1u) >> P.logL);
         }
