@@ -340,7 +340,7 @@ size_t lds_write_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
 }
 
 // dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
-size_t g_lds_granted[6] = {0, 0, 0, 0, 0, 0};
+size_t g_lds_granted[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 int grant_lds(int which, const void* kernel, size_t bytes) {
     if (bytes <= 48 * 1024 || bytes <= g_lds_granted[which]) return JPGD_OK;
     HIP_OK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
@@ -384,9 +384,13 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
 
     std::lock_guard<std::mutex> lock(g_stage.mu);
     const bool staged = pl.L <= kStagedMaxL;
-    if ((rc = grant_lds(staged ? 0 : 3, staged ? (const void*)k_sync_intra<true> : (const void*)k_sync_intra<false>, lds_sync)) ||
-        (rc = grant_lds(staged ? 1 : 4, staged ? (const void*)k_write<true> : (const void*)k_write<false>, lds_write)) ||
-        (rc = grant_lds(2, (const void*)k_sync_inter, lds_inter)))
+    // the variants of the intra-sequence kernel: stream staged in LDS or not, call with or without restart intervals
+    const int variant = (staged ? 0 : 1) + (any_restart ? 2 : 0);
+    const void* const sync_kernels[4] = {(const void*)k_sync_intra<true, false>, (const void*)k_sync_intra<false, false>,
+                                         (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
+    if ((rc = grant_lds(variant, sync_kernels[variant], lds_sync)) ||
+        (rc = grant_lds(staged ? 4 : 5, staged ? (const void*)k_write<true> : (const void*)k_write<false>, lds_write)) ||
+        (rc = grant_lds(8, (const void*)k_sync_inter, lds_inter)))
         return rc;
     rc = stage_acquire(pl.h.upload_bytes + 16);
     if (rc) return rc;
@@ -496,8 +500,12 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     }
     if (big_tiles) LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
-    if (staged) LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra<true>, pl.seqs, kWG, lds_sync);
-    else LAUNCH(JPGD_K_SYNC_INTRA, k_sync_intra<false>, pl.seqs, kWG, lds_sync);
+    switch (variant) {
+        case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, kWG, lds_sync); break;
+        case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, kWG, lds_sync); break;
+        case 2: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, true>), pl.seqs, kWG, lds_sync); break;
+        default: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, true>), pl.seqs, kWG, lds_sync); break;
+    }
 
     uint32_t rounds = 0, redo = 0, flags = 0;
     const uint32_t max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;

@@ -539,7 +539,9 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
 // STAGED: the workgroup's stretch of the stream is copied to LDS first (small subsequences); otherwise lanes
 // read their words from global memory, one refill ahead, which leaves LDS to the tables and lets more
 // workgroups share a CU (large subsequences).
-template <bool STAGED>
+// RST: the call has images with restart intervals.  Calls without get a kernel with none of that code in it (the
+// intra-sequence kernel was measured 3 % slower on plain streams with it: registers and code layout).
+template <bool STAGED, bool RST>
 __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
@@ -576,9 +578,11 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     uint32_t seen = 0u;
     const bool bm_lds = (1u << P.logL) <= (uint32_t)kBitmapLdsMaxL;
     const uint32_t* bmap_img = P.bmap + D.bmap_off;
-    if (D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
+    if (RST && D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
     auto bword = [&](uint32_t k) { return bm_lds ? bm_s[k - bm_k0] : bmap_img[k]; };
-    const bool restart = __syncthreads_or(seen != 0u) != 0;  // also: staged tables and stream are complete
+    bool restart = false;
+    if (RST) restart = __syncthreads_or(seen != 0u) != 0;
+    else __syncthreads();  // staged tables and stream are complete
 
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     // cursor = word index inside the workgroup's window
@@ -868,6 +872,7 @@ __global__ __launch_bounds__(kWG) void k_group_scan(Params P) {
 
 template <bool STAGED>
 __global__ __launch_bounds__(kWG) void k_write(Params P) {
+    constexpr bool RST = true;  // (a variant without the restart code, as for k_sync_intra, was measured 2 % slower)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     __shared__ uint32_t scratch[20];
     const uint32_t wg = blockIdx.x;
@@ -912,9 +917,11 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     uint32_t seen = 0u;
     const bool bm_lds = (1u << P.logL) <= (uint32_t)kBitmapLdsMaxL;
     const uint32_t* bmap_img = P.bmap + D.bmap_off;
-    if (D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
+    if (RST && D.restart) seen = stage_bitmap(bmap_img, first_word, nwords, bm_s, bm_lds);
     auto bword = [&](uint32_t k) { return bm_lds ? bm_s[k - bm_k0] : bmap_img[k]; };
-    const bool restart = __syncthreads_or(seen != 0u) != 0;  // interval starts in this group's stretch of the stream?
+    bool restart = false;  // interval starts in this group's stretch of the stream?
+    if (RST) restart = __syncthreads_or(seen != 0u) != 0;
+    else __syncthreads();
 
     // position of this lane's first data unit and its DC predictors: exclusive scan inside the group
     // plus the group's prefix
@@ -979,7 +986,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
         else decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
     // all restart markers must have been there (the first lane of the image speaks for it)
-    if (D.restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
+    if (RST && D.restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
     // every lane checks the chain: unless the image is complete it must end in the recorded state
     if (unit < total) {
         if (l.p < limit || pack_state(l.p - limit, l.z, l.u) != mine.x) flags |= kStMismatch;
