@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # counters in the same summaries (the entropy kernels are bound by dependent instruction issue, not by HBM).
 MEASURED_ISSUE = {
     ("hd1088_444_q90", "sync_intra"): {"valu_issue_frac": 0.100, "lanes_per_valu_instr": 39.9},
-    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.382, "lanes_per_valu_instr": 38.2},
+    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.379, "lanes_per_valu_instr": 38.2},
 }
 
 MEASURED_TRAFFIC = {
