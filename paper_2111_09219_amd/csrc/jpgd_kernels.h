@@ -447,8 +447,15 @@ __device__ __forceinline__ uint32_t coop_resolve(LutPtr lut, uint32_t slot, uint
     return __builtin_amdgcn_readfirstlane((uint32_t)lut[at]);
 }
 
-// p, u, z: wave-uniform state of the chain, advanced until p >= limit.  org_word: stream word with cursor 0 of
-// `fetch`; cursors from nwords on are not read.  1 <= nslots <= 4 tables.
+// A table entry as the walk adds it to its packed state (coop_span_sync): bits taken (at least one) in bits 0..4
+// and zig-zag slots covered in bits 9..14; for a first-level escape nothing but bit 16, which stops the walk.
+constexpr int kCoopUnroll = 8;
+__device__ __forceinline__ uint32_t coop_step(uint32_t e) {
+    return (e & 0x8000u) ? 0x10000u : ((e & 0x7E00u) | max(e & 31u, 1u));
+}
+
+// p, u, z: wave-uniform state of the chain, advanced until p >= limit (limit >= 64).  org_word: stream word with
+// cursor 0 of `fetch`; cursors from nwords on are not read.  1 <= nslots <= 4 tables.
 template <class Fetch, class LutPtr>
 __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, uint32_t& z_io, uint32_t& nb_out,
                                                int64_t& dc_out, uint32_t limit, uint32_t org_word, uint32_t nwords,
@@ -468,9 +475,12 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
     uint32_t w0 = 0u, held = 0u;
     bool have = false;
     while (p < limit) {
-        uint32_t wb = (p >> 5) - w0;
+        // The window: 64 bit positions, lane j looking at the j-th.  It starts at the chain's position, or, with
+        // fewer than 64 bits left, ends at the limit: either way the walk is over when it leaves the window.
+        const uint32_t ws = limit - p >= 64u ? p : limit - 64u;
+        uint32_t wb = (ws >> 5) - w0;
         if (!have || wb + 3u > 63u) {
-            w0 = p >> 5;
+            w0 = ws >> 5;
             const uint32_t c = w0 - org_word + lane;
             held = c < nwords ? fetch(c) : 0u;
             wb = 0u;
@@ -478,7 +488,7 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
         }
         const uint32_t s0 = __builtin_amdgcn_readlane(held, wb), s1 = __builtin_amdgcn_readlane(held, wb + 1u);
         const uint32_t s2 = __builtin_amdgcn_readlane(held, wb + 2u), s3 = __builtin_amdgcn_readlane(held, wb + 3u);
-        const uint32_t bit = (p & 31u) + lane;  // < 95
+        const uint32_t bit = (ws & 31u) + lane;  // < 95
         const uint32_t off = bit >> 5;
         const uint32_t hi = off == 0u ? s0 : (off == 1u ? s1 : s2);
         const uint32_t lo = off == 0u ? s1 : (off == 1u ? s2 : s3);
@@ -491,43 +501,60 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
         for (uint32_t s = 0u; s < 4u; ++s) e[s] = lut[min(s, nslots - 1u) * (uint32_t)kLutEntries + idx];
         const uint32_t e01 = e[0] | (e[1] << 16), e23 = e[2] | (e[3] << 16);
         uint32_t acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);  // the AC entry in the low 16 bits
-        // follow the chain through the window: symbols that start before bit jmax of it
-        const uint32_t jmax = min(64u, limit - p);
-        uint32_t j = 0u;
+        uint32_t acs = coop_step(acv);
+        // Follow the chain through the window.  S = window position j (bits 0..6, at most 63 + 31) and zig-zag index
+        // z (bits 9..15, at most 63 + 63); adding a symbol's step advances both.  Bit 6 set: the window is behind
+        // us; bit 15: the data unit is complete; bit 16: the entry was an escape and nothing has been advanced.
+        uint32_t S = (p - ws) | (z << 9);
         for (;;) {
-            if (z == 0u) {  // DC symbol
-                const uint32_t pair = __builtin_amdgcn_readlane((dc_slot & 2u) ? e23 : e01, j);
-                const uint32_t pk = __builtin_amdgcn_readlane(peek, j);
+            if ((S >> 9) == 0u) {  // DC symbol (z = 0, so S is j)
+                const uint32_t pair = __builtin_amdgcn_readlane((dc_slot & 2u) ? e23 : e01, S);
+                const uint32_t pk = __builtin_amdgcn_readlane(peek, S);
                 uint32_t r = pair >> ((dc_slot & 1u) << 4);
                 if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, pk);
-                const uint32_t total = lut_total(r);
-                const int32_t v = symbol_value(pk, total, lut_size(r));
+                const int32_t v = symbol_value(pk, lut_total(r), lut_size(r));
                 dc += (int64_t)v * (int64_t)(1u << ((cur >> 10) & 31u));
-                z = lut_adv(r);  // 1, or 0 where no codeword starts
-                j += max(total, 1u);
-                if (j >= jmax) break;
-                if (z == 0u) continue;
+                S += coop_step(r);  // z becomes 1, or stays 0 where no codeword starts
+                if (S & 0x40u) break;
+                if ((S >> 9) == 0u) continue;
             }
-            // AC symbols up to the end of the unit or of the window; only j and z change in here
-            // (one test for both ends: z > 63 or j + 64 - jmax > 63)
-            do {
-                uint32_t r = __builtin_amdgcn_readlane(acv, j);
-                if (r & 0x8000u) r = coop_resolve(lut, ac_slot, r, (uint32_t)__builtin_amdgcn_readlane(peek, j));
-                j += max(lut_total(r), 1u);  // every table entry takes at least one bit; the loop must end even if one did not
-                z += lut_adv(r);
-            } while (max(z, j + (64u - jmax)) < 64u);
-            if (z >= 64u) {
+            // AC symbols up to the end of the unit or of the window.  A taken branch costs a lone wavefront far
+            // more than the three other instructions of a step, so the steps come eight in a row with one exit
+            // test each, and everything unusual leaves through that exit.
+            for (;;) {
+                bool out = false;
+#pragma unroll
+                for (int k = 0; k < kCoopUnroll; ++k) {
+                    S += __builtin_amdgcn_readlane(acs, S & 63u);
+                    if (__builtin_expect((S & 0x18040u) != 0u, 0)) {
+                        out = true;
+                        break;
+                    }
+                }
+                if (!out) continue;
+                if (S & 0x10000u) {  // the codeword is longer than the first-level index
+                    S &= 0xFFFFu;
+                    const uint32_t j = S & 63u;
+                    S += coop_step(coop_resolve(lut, ac_slot, (uint32_t)__builtin_amdgcn_readlane(acv, j),
+                                                (uint32_t)__builtin_amdgcn_readlane(peek, j)));
+                    if ((S & 0x8040u) == 0u) continue;
+                }
+                break;
+            }
+            if (S & 0x8000u) {  // unit complete
                 ++nb;
-                z = 0u;
+                S &= 0x7Fu;
                 u = (cur >> 6) & 15u;
                 dc_slot = (cur >> 3) & 7u;
                 cur = __builtin_amdgcn_readlane(unit_word, u);
                 ac_slot = cur & 7u;
                 acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);
+                acs = coop_step(acv);
             }
-            if (j >= jmax) break;
+            if (S & 0x40u) break;
         }
-        p += j;
+        p = ws + (S & 0x7Fu);
+        z = S >> 9;
     }
     p_io = p; u_io = u; z_io = z; nb_out = nb; dc_out = dc;
 }

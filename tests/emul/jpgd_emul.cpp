@@ -142,6 +142,8 @@ uint32_t coop_resolve(const uint16_t* lut, uint32_t slot, uint32_t e, uint32_t p
                ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u))];
 }
 
+uint32_t coop_step(uint32_t e) { return (e & 0x8000u) ? 0x10000u : ((e & 0x7E00u) | std::max(e & 31u, 1u)); }
+
 template <class Fetch>
 void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t& dc, uint32_t limit, uint32_t org_word,
                     uint32_t nwords, const uint32_t unit_word[64], uint32_t upm, uint32_t nslots, Fetch fetch,
@@ -154,9 +156,10 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
     uint32_t w0 = 0, held[64];
     bool have = false;
     while (p < limit) {
-        uint32_t wb = (p >> 5) - w0;
+        const uint32_t ws = limit - p >= 64u ? p : limit - 64u;
+        uint32_t wb = (ws >> 5) - w0;
         if (!have || wb + 3u > 63u) {
-            w0 = p >> 5;
+            w0 = ws >> 5;
             for (uint32_t lane = 0; lane < 64; ++lane) {
                 const uint32_t c = w0 - org_word + lane;
                 held[lane] = c < nwords ? fetch(c) : 0u;
@@ -166,7 +169,7 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
         }
         uint32_t peek[64], e01[64], e23[64];
         for (uint32_t lane = 0; lane < 64; ++lane) {
-            const uint32_t bit = (p & 31u) + lane, off = bit >> 5;
+            const uint32_t bit = (ws & 31u) + lane, off = bit >> 5;
             const uint32_t hi = held[wb + off], lo = held[wb + off + 1u];
             peek[lane] = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (bit & 31u)) >> 32);
             const uint32_t idx = peek[lane] >> (32 - kLutK);
@@ -176,36 +179,39 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
             e23[lane] = e[2] | (e[3] << 16);
         }
         auto entry = [&](uint32_t slot, uint32_t j) { return ((slot & 2u) ? e23[j] : e01[j]) >> ((slot & 1u) << 4); };
-        const uint32_t jmax = std::min(64u, limit - p);
-        uint32_t j = 0;
+        uint32_t S = (p - ws) | (z << 9);
         for (;;) {
-            if (z == 0u) {
-                uint32_t r = entry(dc_slot, j);
-                if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, peek[j]);
-                const uint32_t total = lut_total(r);
-                dc += (int64_t)symbol_value(peek[j], total, lut_size(r)) * (int64_t)(1u << ((cur >> 10) & 31u));
-                z = lut_adv(r);
-                j += std::max(total, 1u);
-                if (j >= jmax) break;
-                if (z == 0u) continue;
+            if ((S >> 9) == 0u) {
+                uint32_t r = entry(dc_slot, S);
+                if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, peek[S]);
+                dc += (int64_t)symbol_value(peek[S], lut_total(r), lut_size(r)) * (int64_t)(1u << ((cur >> 10) & 31u));
+                S += coop_step(r);
+                if (S & 0x40u) break;
+                if ((S >> 9) == 0u) continue;
             }
-            do {
-                uint32_t r = entry(ac_slot, j);
-                if (r & 0x8000u) r = coop_resolve(lut, ac_slot, r, peek[j]);
-                j += std::max(lut_total(r), 1u);
-                z += lut_adv(r);
-            } while (std::max(z, j + (64u - jmax)) < 64u);
-            if (z >= 64u) {
+            for (;;) {
+                S += coop_step(entry(ac_slot, S & 63u));
+                if ((S & 0x18040u) == 0u) continue;
+                if (S & 0x10000u) {
+                    S &= 0xFFFFu;
+                    const uint32_t j = S & 63u;
+                    S += coop_step(coop_resolve(lut, ac_slot, entry(ac_slot, j), peek[j]));
+                    if ((S & 0x8040u) == 0u) continue;
+                }
+                break;
+            }
+            if (S & 0x8000u) {
                 ++nb;
-                z = 0u;
+                S &= 0x7Fu;
                 u = (cur >> 6) & 15u;
                 dc_slot = (cur >> 3) & 7u;
                 cur = unit_word[u];
                 ac_slot = cur & 7u;
             }
-            if (j >= jmax) break;
+            if (S & 0x40u) break;
         }
-        p += j;
+        p = ws + (S & 0x7Fu);
+        z = S >> 9;
     }
 }
 
