@@ -127,6 +127,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         const uint32_t M = kPixBlocks / d.upm;
         d.pix_runs = (d.mcus_x + M - 1) / M;
         d.pix_wg0 = pl.pixwgs;
+        if ((uint64_t)pl.pixwgs + (uint64_t)d.pix_runs * d.mcus_y > 0x7FFFFFFFull) return JPGD_E_ARG;  // grid size
         pl.pixwgs += d.pix_runs * d.mcus_y;
         coef_units += d.total_units;
         // table slots: distinct DC tables first, then distinct AC tables, in order of first use
