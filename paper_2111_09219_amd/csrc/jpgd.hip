@@ -455,7 +455,19 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.seq_len = kWG - pl.h.overlap;
     P.lut_slots = pl.lut_slots;
     P.planar = (cfg && (cfg->flags & JPGD_F_PLANAR)) ? 1u : 0u;
-    P.coop_max = kCoopMax;
+    // Wavefronts per workgroup of the intra-sequence kernel: as many as the CU's 32 slots allow beside the other
+    // workgroups it will hold (LDS, or the size of the grid, decides how many those are), at most 16; more than
+    // 8 only pay when a round is long (measured: 16 instead of 8 gains 5 % at 1024 bits, nothing at 128).  Calls
+    // with restart intervals stay at four: their kernel needs twice the registers.
+    uint32_t sync_waves = (uint32_t)(kWG / 64);
+    if (!any_restart) {
+        const uint32_t by_lds = (uint32_t)(160u * 1024u / lds_sync), by_grid = (pl.seqs + 255u) / 256u;
+        const uint32_t per_cu = by_lds < by_grid ? (by_lds ? by_lds : 1u) : by_grid;
+        const uint32_t most = pl.L >= 512u ? (uint32_t)kSyncWavesMax : 8u;
+        while (sync_waves * 2u <= most && sync_waves * 2u * per_cu <= 32u) sync_waves *= 2u;
+    }
+    P.sync_waves = sync_waves;
+    P.coop_max = kCoopMax * sync_waves / (uint32_t)(kWG / 64);
     P.verdict = nullptr;
     P.ticket = 0u;
     P.up_src = (const uint4*)g_stage.buf_dev;
@@ -502,10 +514,10 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     if (big_tiles) LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
     switch (variant) {
-        case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, kWG, lds_sync); break;
-        case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, kWG, lds_sync); break;
-        case 2: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, true>), pl.seqs, kWG, lds_sync); break;
-        default: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, true>), pl.seqs, kWG, lds_sync); break;
+        case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
+        case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
+        case 2: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, true>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
+        default: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, true>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
     }
 
     uint32_t rounds = 0, redo = 0, flags = 0;

@@ -42,10 +42,14 @@ constexpr int kLutEntries = kLutL1 + kLutL2;
 constexpr int kMaxSlots = 6;  // up to 3 DC and 3 AC tables per image (one pair per component)
 constexpr uint32_t kAdvEob = 63u;
 
-// Intra-sequence synchronisation: with at most this many chains still running in a workgroup, each chain is
-// decoded by a whole wavefront (measured on 1920x1088 4:4:4 and 4096x4096 4:2:0 streams: 4 to 8 are within
-// noise of each other, 16 is slower than never doing it for large images).  At most 64.
-constexpr uint32_t kCoopMax = 6u;
+// Intra-sequence synchronisation: with at most one and a half chains per wavefront of the workgroup still running,
+// each chain is decoded by a whole wavefront.  Measured on 1920x1088 4:4:4 (128-bit subsequences) and on 4096x4096
+// and 15360x8640 4:2:0 (1024 bits): with four wavefronts 4 to 8 chains are within noise of each other and 16 is
+// slower than never doing it on the large images; with eight wavefronts 12 is best, with sixteen 24.
+constexpr uint32_t kCoopMax = 6u;  // for the kWG / 64 wavefronts that hold the lanes
+// The workgroup may have more wavefronts than those: the others do nothing but take chains in these rounds, so
+// that fewer chains share a wavefront (a CU has 32 wavefront slots and a sequence's tail leaves most of them idle).
+constexpr int kSyncWavesMax = 16;
 
 JPGD_HD bool lut_esc(uint32_t e) { return e >= 0x8000u; }
 JPGD_HD uint32_t lut_total(uint32_t e) { return e & 31u; }

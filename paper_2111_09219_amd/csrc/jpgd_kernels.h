@@ -37,6 +37,7 @@ struct Params {
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
+    uint32_t sync_waves;    // wavefronts per workgroup of that kernel: kWG / 64 that hold the lanes, the rest only take chains
     // A call with one image has the last up_wgs workgroups of k_unstuff_count copy the call's parameter block
     // (up_n16 16-byte words) from pinned host memory into the workspace: that kernel does not need the block, all
     // later ones do, and a kernel of its own for the copy would cost a dispatch.  up_wgs = 0: nothing to copy.
@@ -569,7 +570,7 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
 // RST: the call has images with restart intervals.  Calls without get a kernel with none of that code in it (the
 // intra-sequence kernel was measured 3 % slower on plain streams with it: registers and code layout).
 template <bool STAGED, bool RST>
-__global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
+__global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
@@ -645,12 +646,12 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     // The wavefront-per-chain code does not know more than four tables.  In a workgroup that sees restart intervals
     // a chain may fall back to a single lane for a round (below): at most one chain per wavefront then, so that
     // such rounds never take longer than the packed ones they replace.
-    const uint32_t coop_max = P.lut_slots > 4u ? 0u : (restart ? min(P.coop_max, (uint32_t)(kWG / 64)) : P.coop_max);
+    const uint32_t coop_max = P.lut_slots > 4u ? 0u : (restart ? min(P.coop_max, P.sync_waves) : P.coop_max);
     uint32_t coop_n = 0u;
     for (uint32_t round = 0u;; ++round) {
         const uint64_t bal = __ballot(active);
         uint32_t* cnt = scratch + ((round & 1u) << 2);
-        if ((t & 63u) == 0u) cnt[t >> 6] = (uint32_t)__popcll(bal);
+        if ((t & 63u) == 0u && t < (uint32_t)kWG) cnt[t >> 6] = (uint32_t)__popcll(bal);
         __syncthreads();  // also orders the records written in the previous round before their readers
         const uint32_t c0 = cnt[0], c1 = cnt[1], c2 = cnt[2], c3 = cnt[3];
         const uint32_t now = c0 + c1 + c2 + c3;
@@ -710,8 +711,9 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
     // The same rounds with one chain per wavefront.  The chains keep their slot k < coop_n in a list held twice
     // (read from one copy, written to the other, swapped every round; mv_tt = kCoopDone once a chain has
     // synchronised or reached the end of the sequence).  Every wavefront reads the whole list and takes the
-    // running chains whose rank among them is its own number modulo four, so the work stays spread as chains
-    // drop out; wavefront 0 carries the finished slots over.  One barrier per round.
+    // running chains whose rank among them is its own number modulo the number of wavefronts (the four that hold
+    // the lanes and the ones that are only here for this), so the work stays spread as chains drop out;
+    // wavefront 0 carries the finished slots over.  One barrier per round.
     if (coop_n) {
         constexpr uint32_t kCoopDone = 0xFFFFFFFFu;
         // the compiler cannot know that these are the same in every lane (they come from the image descriptor and
@@ -720,6 +722,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
         const uint32_t u_n = __builtin_amdgcn_readfirstlane(coop_n), u_t1 = __builtin_amdgcn_readfirstlane(t1);
         const uint32_t u_first = __builtin_amdgcn_readfirstlane(first_word), u_nwords = __builtin_amdgcn_readfirstlane(nwords);
         const uint32_t u_upm = __builtin_amdgcn_readfirstlane(sx.upm);
+        const uint32_t u_waves = P.sync_waves;  // a power of two
         const int32_t u_base = (int32_t)__builtin_amdgcn_readfirstlane((uint32_t)base);
         const uint32_t unit_word = coop_unit_word(sx, lane);
         for (uint32_t par = 0u;; par ^= 1u) {
@@ -730,7 +733,7 @@ __global__ __launch_bounds__(kWG) void k_sync_intra(Params P) {
             if (wave == 0u && lane < u_n && mine == kCoopDone) mv_tt[wr + lane] = kCoopDone;
             uint32_t rank = 0u;
             for (uint64_t m = running; m; m &= m - 1ull, ++rank) {
-                if ((rank & 3u) != wave) continue;
+                if ((rank & (u_waves - 1u)) != wave) continue;
                 const uint32_t k = (uint32_t)__ffsll((long long)m) - 1u;
                 uint32_t cp = mv_p[rd + k];
                 const uint32_t uz = mv_uz[rd + k];
