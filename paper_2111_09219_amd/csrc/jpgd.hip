@@ -460,11 +460,12 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     // 8 only pay when a round is long (measured: 16 instead of 8 gains 5 % at 1024 bits, nothing at 128).  Calls
     // with restart intervals stay at four: their kernel needs twice the registers.
     uint32_t sync_waves = (uint32_t)(kWG / 64);
-    if (!any_restart) {
+    {
+        const uint32_t slots = any_restart ? 20u : 32u;  // the kernel for restart intervals needs 92 registers: 5 per SIMD
         const uint32_t by_lds = (uint32_t)(160u * 1024u / lds_sync), by_grid = (pl.seqs + 255u) / 256u;
         const uint32_t per_cu = by_lds < by_grid ? (by_lds ? by_lds : 1u) : by_grid;
         const uint32_t most = pl.L >= 512u ? (uint32_t)kSyncWavesMax : 8u;
-        while (sync_waves * 2u <= most && sync_waves * 2u * per_cu <= 32u) sync_waves *= 2u;
+        while (sync_waves * 2u <= most && sync_waves * 2u * per_cu <= slots) sync_waves *= 2u;
     }
     P.sync_waves = sync_waves;
     P.coop_max = kCoopMax * sync_waves / (uint32_t)(kWG / 64);

@@ -127,7 +127,8 @@ struct Emul {
 // The wavefront-per-chain decoder of jpgd_kernels.h (coop_unit_word, coop_span_sync) with its 64 lanes run
 // one after another: the same table words, the same 64-word stretch held by the lanes, the same four answers
 // per lane and the same walk through them.
-uint32_t g_coop_max = kCoopMax;  // as the library sets it; the tests also run with 0 (never), 8 and 64
+uint32_t g_coop_max = kCoopMax;  // as the library sets it for four wavefronts; the tests also run with 0 (never), 8 and 64
+uint32_t g_sync_waves = kWG / 64;  // wavefronts per workgroup (the library launches 4, 8 or 16)
 
 uint32_t coop_unit_word(const Syntax& sx, uint32_t lane) {
     if (lane >= sx.upm) return 0u;
@@ -273,7 +274,7 @@ void sync_intra(Emul& E) {
             ++rounds;
             uint32_t now = 0;
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) now += active[t] ? 1u : 0u;
-            const bool coop = im.nslots <= 4u && now <= (restart ? std::min(g_coop_max, (uint32_t)(kWG / 64)) : g_coop_max);  // stays true once it is
+            const bool coop = im.nslots <= 4u && now <= (restart ? std::min(g_coop_max, g_sync_waves) : g_coop_max);  // stays true once it is
             uint32_t unit_word[64];
             for (uint32_t lane = 0; lane < 64; ++lane) unit_word[lane] = coop_unit_word(E.sx, lane);
             for (uint32_t t = 0; t < (uint32_t)kWG; ++t) {
@@ -533,6 +534,7 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
 
 // chains left at which the intra-sequence walk-through switches to the wavefront-per-chain decoder
 extern "C" void emul_set_coop_max(uint32_t n) { g_coop_max = n; }
+extern "C" void emul_set_sync_waves(uint32_t n) { g_sync_waves = n; }
 
 // the literal zig-zag table of jpgd_idct.h, for comparison with a generated one
 extern "C" void emul_zigzag(uint8_t out[64]) {

@@ -153,6 +153,7 @@ def emul():
     lib.emul_decode.argtypes = [vp, ctypes.c_size_t, u32, u32, u32, vp, vp, vp, u32, vp, vp]
     lib.emul_zigzag.argtypes = [vp]
     lib.emul_set_coop_max.argtypes = [u32]
+    lib.emul_set_sync_waves.argtypes = [u32]
     lib.emul_build_lut.argtypes = [vp, vp, ctypes.c_int, vp]
     return lib
 
@@ -280,13 +281,15 @@ def test_host_walkthrough_with_restart_intervals(emul, sub, opt, q, shape, L, H,
     any state fall into step at the next interval, DC sums and predictors start afresh there."""
     px = small_image(19, *shape, ncomp=1 if sub == "gray" else 3, sigma=11.0)
     data = encode_jpeg(px, q, sub, opt, restart_interval=ri).data
-    # with the switch at 64 chains nearly every overflow round runs one wavefront per chain, which hands chains
-    # whose stretch holds an interval start to a single lane
+    # with the switch at 64 chains and a wavefront for each of up to 16 chains many overflow rounds run one wavefront
+    # per chain, which hands chains whose stretch holds an interval start to a single lane
     emul.emul_set_coop_max(64 if ri in (2, 7, 1000) else 6)
+    emul.emul_set_sync_waves(16 if ri in (2, 7, 1000) else 4)
     try:
         rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
     finally:
         emul.emul_set_coop_max(6)
+        emul.emul_set_sync_waves(4)
     assert rc == 0 and stats[3] == 0
     assert o.restart_interval == ri
     assert np.array_equal(stream, o.unstuffed())
