@@ -28,16 +28,16 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # Share of the chip's vector issue slots the kernel uses and lanes switched on per vector instruction, from the SQ
 # counters in the same summaries (the entropy kernels are bound by dependent instruction issue, not by HBM).
 MEASURED_ISSUE = {
-    ("hd1088_444_q90", "sync_intra"): {"valu_issue_frac": 0.100, "lanes_per_valu_instr": 39.9},
-    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.379, "lanes_per_valu_instr": 38.2},
+    ("hd1088_444_q90", "sync_intra"): {"valu_issue_frac": 0.114, "lanes_per_valu_instr": 41.2},
+    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.429, "lanes_per_valu_instr": 40.6},
 }
 
 MEASURED_TRAFFIC = {
-    ("hd1088_444_q90", "sync_intra"): 1.740e6,
+    ("hd1088_444_q90", "sync_intra"): 1.748e6,
     ("hd1088_444_q90", "write"): 17.09e6,
     ("hd1088_444_q90", "pixels"): 18.91e6,
-    ("uhd16k_420_q92_flat_random", "sync_intra"): 84.74e6,
-    ("uhd16k_420_q92_flat_random", "write"): 1132.0e6,
+    ("uhd16k_420_q92_flat_random", "sync_intra"): 84.75e6,
+    ("uhd16k_420_q92_flat_random", "write"): 1129.0e6,
     ("uhd16k_420_q92_flat_random", "pixels"): 796.3e6,
 }
 

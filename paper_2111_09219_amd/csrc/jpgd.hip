@@ -59,14 +59,29 @@ bool same_tables(const jpgd_info& a, const jpgd_info& b) {
 }
 
 // Subsequence size when the caller leaves it open.  The paper picks 1024 bits for high-quality material and
-// 128 for short streams (Section 5, Tables II and III).  Here: as large as possible (fewer overflow rounds,
-// fewer records) while the call still has about 64k subsequences to spread over the chip's 1024 SIMDs.
+// 128 for short streams (Section 5, Tables II and III).  Two rules, the larger result counts:
+//  * size: as large as possible (fewer overflow rounds, fewer records) while the call still has about 64k
+//    subsequences to spread over the chip's 1024 SIMDs;
+//  * content: a decoder needs a certain number of data units, not of bits, to fall into step - about 30 in a
+//    4:4:4 or grey scan, about 140 in a 4:2:0 scan, where it also has to find its place among the six units of
+//    the MCU - and a sequence of 240 subsequences must be several times that long, or most of its chains run
+//    to its end without synchronising and the workgroup is no faster than one sequential decoder.  Measured
+//    optimum: 2 (4:4:4, grey), 10 (4:2:0) times the scan's average bits per data unit; 4:2:2 is taken between.
 uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
     uint64_t bits = 0;
-    for (int i = 0; i < n; ++i) bits += infos[i].scan_bytes * 8u;
-    uint32_t L = 128u;
-    while (L < 1024u && bits / (2u * L) >= 65536u) L *= 2u;
-    return L;
+    double want = 0.0;
+    for (int i = 0; i < n; ++i) {
+        const double b = (double)infos[i].scan_bytes * 8.0;
+        const double per_unit = b / (double)(infos[i].total_units ? infos[i].total_units : 1u);
+        const double factor = infos[i].units_per_mcu >= 6u ? 10.0 : infos[i].units_per_mcu >= 4u ? 6.0 : 2.0;
+        bits += infos[i].scan_bytes * 8u;
+        want += b * factor * per_unit;
+    }
+    want /= (double)(bits ? bits : 1u);  // average over the call's bits
+    uint32_t by_size = 128u, by_content = 128u;
+    while (by_size < 1024u && bits / (2u * by_size) >= 65536u) by_size *= 2u;
+    while (by_content < 1024u && want > 1.41 * (double)by_content) by_content *= 2u;
+    return by_size > by_content ? by_size : by_content;
 }
 
 // Validates arguments that do not need the GPU and lays the workspace out.
