@@ -74,7 +74,8 @@ typedef struct {
 
 typedef struct {
     uint32_t subseq_bits;  /* subsequence size in bits ("s*32" in Algorithm 1): 128, 256, 512, 1024
-                              or 2048; 0 = choose per call from the stream sizes                   */
+                              or 2048; 0 = choose per call from the size of the streams and their
+                              bits per data unit                                                 */
     uint32_t overlap;      /* subsequences by which neighbouring sequences overlap (warm-up lanes
                               in front of each sequence); 0 = the paper's disjoint sequences;
                               must be < 192; 0xFFFFFFFF = library default (16 or 32)               */
