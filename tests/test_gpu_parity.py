@@ -226,6 +226,33 @@ def test_extreme_shapes(sub, shape):
         assert np.abs(got.cpu().numpy().astype(np.int16) - ref.astype(np.int16)).max() <= PIXEL_TOL
 
 
+def test_automatic_subsequence_size():
+    """The size the library picks when the caller leaves it open follows the scan's bits per data unit (twice that
+    for 4:4:4 and grey scans, ten times for 4:2:0, to the nearest power of two in 128..1024) as long as the call
+    is small; whatever it picks, the result is the oracle's."""
+    cases = [("444", 30, 128), ("444", 99, None), ("420", 50, None), ("420", 97, None), ("gray", 90, None)]
+    for k, (sub, q, expect) in enumerate(cases):
+        px = small_image(60 + k, 240, 336, ncomp=1 if sub == "gray" else 3, sigma=14.0)
+        data = encode_jpeg(px, q, sub, False).data
+        batch, rep = _decode([data])
+        o = _check_image(batch, 0, data)
+        per_unit = 8.0 * o.info.scan_len / o.total_units
+        want = per_unit * (10.0 if sub == "420" else 2.0)
+        L = 128
+        while L < 1024 and want > 1.41 * L:
+            L *= 2
+        assert rep.subseq_bits == L, (sub, q, per_unit, rep.subseq_bits, L)
+        if expect is not None:
+            assert rep.subseq_bits == expect
+    # a dense 4:2:0 scan gets a larger size than an equally long 4:4:4 scan of the same density would
+    sizes = {}
+    for sub in ("444", "420"):
+        px = small_image(77, 240, 336, sigma=30.0)
+        data = encode_jpeg(px, 95, sub, False).data
+        sizes[sub] = _decode([data])[1].subseq_bits
+    assert sizes["420"] > sizes["444"]
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
