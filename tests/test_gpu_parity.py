@@ -253,6 +253,44 @@ def test_automatic_subsequence_size():
     assert sizes["420"] > sizes["444"]
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_randomised_calls(seed):
+    """Calls drawn at random: layout, size (not a multiple of the MCU more often than not), quality 5..100, standard or
+    per-image tables, restart intervals, subsequence size, overlap, one image or several different ones, RGB or planes."""
+    rng = np.random.default_rng(977 + seed)
+    for k in range(60):
+        nb = int(rng.choice([1, 1, 1, 2, 5]))
+        any_ri = rng.random() < 0.4
+        datas = []
+        for j in range(nb):
+            sub = ["gray", "444", "422", "420", "420", "444"][int(rng.integers(6))]
+            big = rng.random() < 0.15
+            h, w = int(rng.integers(8, 900 if big else 200)), int(rng.integers(8, 1300 if big else 260))
+            q = int(rng.choice([5, 20, 50, 75, 85, 92, 97, 100]))
+            ri = int(rng.choice([0, 1, 3, 17, 1000])) if any_ri else 0
+            px = small_image(9000 + 100 * seed + 10 * k + j, h, w, ncomp=1 if sub == "gray" else 3,
+                             sigma=float(rng.choice([0.5, 6.0, 25.0, 80.0])))
+            datas.append(encode_jpeg(px, q, sub, bool(rng.integers(2)), restart_interval=ri).data)
+        cfg = dict(subseq_bits=int(rng.choice([0, 0, 128, 256, 512, 1024, 2048])))
+        ov = int(rng.choice([-1, -1, 0, 5, 64, 191]))
+        if ov >= 0:
+            cfg["overlap"] = ov
+        planar = rng.random() < 0.3
+        if planar:
+            cfg["flags"] = J.F_PLANAR
+        batch, rep = _decode(datas, **cfg)
+        for i, data in enumerate(datas):
+            o = OracleImage(data)
+            ref = o.coefficients()
+            assert np.array_equal(batch.coefficients(i).cpu().numpy(), ref), (seed, k, i)
+            if planar:
+                for got, want in zip(batch.planes(i), o.planes(ref)):
+                    assert np.abs(got.cpu().numpy().astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL, (seed, k, i)
+            else:
+                want = o.pixels(ref)
+                assert np.abs(batch.pixels(i).cpu().numpy().astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL, (seed, k, i)
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
