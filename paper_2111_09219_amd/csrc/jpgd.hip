@@ -66,16 +66,20 @@ bool same_tables(const jpgd_info& a, const jpgd_info& b) {
 //    4:4:4 or grey scan, about 140 in a 4:2:0 scan, where it also has to find its place among the six units of
 //    the MCU - and a sequence of 240 subsequences must be several times that long, or most of its chains run
 //    to its end without synchronising and the workgroup is no faster than one sequential decoder.  Measured
-//    optimum: 2 (4:4:4, grey), 10 (4:2:0) times the scan's average bits per data unit; 4:2:2 is taken between.
+//    optimum: 2 (4:4:4, grey), 4 (4:2:2), 10 (4:2:0) times the scan's average bits per data unit, and never
+//    below 256 bits for a subsampled scan.
 uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
     uint64_t bits = 0;
     double want = 0.0;
     for (int i = 0; i < n; ++i) {
         const double b = (double)infos[i].scan_bytes * 8.0;
         const double per_unit = b / (double)(infos[i].total_units ? infos[i].total_units : 1u);
-        const double factor = infos[i].units_per_mcu >= 6u ? 10.0 : infos[i].units_per_mcu >= 4u ? 6.0 : 2.0;
+        const bool subsampled = infos[i].units_per_mcu >= 4u;
+        const double factor = infos[i].units_per_mcu >= 6u ? 10.0 : subsampled ? 4.0 : 2.0;
+        double w = factor * per_unit;
+        if (subsampled && w < 256.0) w = 256.0;
         bits += infos[i].scan_bytes * 8u;
-        want += b * factor * per_unit;
+        want += b * w;
     }
     want /= (double)(bits ? bits : 1u);  // average over the call's bits
     uint32_t by_size = 128u, by_content = 128u;

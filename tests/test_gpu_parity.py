@@ -228,16 +228,19 @@ def test_extreme_shapes(sub, shape):
 
 def test_automatic_subsequence_size():
     """The size the library picks when the caller leaves it open follows the scan's bits per data unit (twice that
-    for 4:4:4 and grey scans, ten times for 4:2:0, to the nearest power of two in 128..1024) as long as the call
-    is small; whatever it picks, the result is the oracle's."""
-    cases = [("444", 30, 128), ("444", 99, None), ("420", 50, None), ("420", 97, None), ("gray", 90, None)]
+    for 4:4:4 and grey scans, four times for 4:2:2, ten times for 4:2:0, to the nearest power of two in 128..1024,
+    at least 256 for subsampled scans) as long as the call is small; whatever it picks, the result is the oracle's."""
+    cases = [("444", 30, 128), ("444", 99, None), ("420", 50, None), ("420", 97, None), ("gray", 90, None),
+             ("422", 20, 256), ("422", 96, None)]
     for k, (sub, q, expect) in enumerate(cases):
         px = small_image(60 + k, 240, 336, ncomp=1 if sub == "gray" else 3, sigma=14.0)
         data = encode_jpeg(px, q, sub, False).data
         batch, rep = _decode([data])
         o = _check_image(batch, 0, data)
         per_unit = 8.0 * o.info.scan_len / o.total_units
-        want = per_unit * (10.0 if sub == "420" else 2.0)
+        want = per_unit * {"420": 10.0, "422": 4.0}.get(sub, 2.0)
+        if sub in ("420", "422"):
+            want = max(want, 256.0)  # never below 256 bits for a subsampled scan
         L = 128
         while L < 1024 and want > 1.41 * L:
             L *= 2
