@@ -1,0 +1,57 @@
+"""The contract of bench.py: what it refuses, and the shape of the one JSON line it prints."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BENCH = os.path.join(ROOT, "bench.py")
+
+
+def _run(*args, timeout=600):
+    return subprocess.run([sys.executable, BENCH, *args], cwd=ROOT, capture_output=True, text=True, timeout=timeout)
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = _run("--gpus", "2")
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_algorithmic_bytes_follow_the_stated_formulas():
+    sys.path.insert(0, ROOT)
+    import bench
+    Bs, B, S, K, out = 1000, 990, 62, 40, 2560
+    assert bench.algorithmic_bytes("unstuff_count", Bs, B, S, K, out) == Bs
+    assert bench.algorithmic_bytes("unstuff_scatter", Bs, B, S, K, out) == Bs + B
+    assert bench.algorithmic_bytes("sync_intra", Bs, B, S, K, out) == B + 16 * S
+    assert bench.algorithmic_bytes("write", Bs, B, S, K, out) == B + 16 * S + 128 * K
+    assert bench.algorithmic_bytes("pixels", Bs, B, S, K, out) == 128 * K + out
+    assert bench.HBM_PEAK_GBS == 8000.0
+
+
+@pytest.mark.gpu
+def test_the_json_line_has_the_agreed_fields():
+    r = _run("--config", "1", "--steps", "8", "--warmup", "2", "--cpu-seconds", "0.3")
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 8 and d["warmup"] == 2 and d["vs_baseline"] is None
+    assert d["unit"] == "MB/s" and d["higher_is_better"] is True and d["data"] == "synthetic"
+    assert "workload" in d["config"] and "model" not in d["config"]
+    roof = d["roofline"]
+    for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert key in roof, key
+    assert roof["bound"] == "hbm" and roof["peak"] == 8000.0 and roof["unit"] == "GB/s"
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-4
+    cpu = d["cpu_baseline"]
+    for key in ("value", "unit", "cores", "kind", "sample"):
+        assert key in cpu, key
+    assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0
+    assert d["value"] > 0 and d["ms_per_step"] > 0
