@@ -222,7 +222,7 @@ struct Staging {
     uint8_t* buf = nullptr;        // pinned
     uint8_t* buf_dev = nullptr;    // the same bytes as the device addresses them
     size_t cap = 0;
-    uint32_t* verdict = nullptr;   // pinned, 16 words: [0] flags, [1] inter_changed, [15] ticket of the report
+    uint32_t* verdict = nullptr;   // pinned, 16 words: [0] flags, [1] inter_changed, [2] pending, [15] ticket of the report
     uint32_t* verdict_dev = nullptr;
     uint32_t ticket = 0;
     std::vector<hipEvent_t> timers;  // pairs of events for timing_mask
@@ -257,6 +257,7 @@ __global__ void k_verdict(const Status* st, volatile uint32_t* host, uint32_t ti
     if (threadIdx.x == 0) {
         host[0] = st->flags;
         host[1] = st->inter_changed;
+        host[2] = st->pending;
         __threadfence_system();
         host[15] = ticket;
     }
@@ -568,10 +569,17 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         HIP_OK(hipGetLastError());
         if ((rc = wait_verdict(stream, ticket)) != JPGD_OK) return rc;
         flags = g_stage.verdict[0];
+        // `pending`: a sequence whose records were made for another entry state than the one the sequence before it
+        // now ends in (k_group_totals).  Its states may all be right, so that the write pass finds nothing, while the
+        // counts and DC sums of its first records are not: it takes another round like a broken chain does.
+        const bool pending = g_stage.verdict[2] != 0u;
         const bool chain_broken = (flags & (kStMismatch | kStUnit)) != 0;
         // A broken chain with more than one sequence may only mean that synchronisation needs another
         // inter-sequence round (paper: the host repeats the phase until all sequences are synchronised).
-        if (!chain_broken || !pl.bnds || rounds >= max_rounds) break;
+        if ((!chain_broken && !pending) || !pl.bnds || rounds >= max_rounds) {
+            if (pending && pl.bnds) flags |= kStMismatch;  // out of rounds: the result is not to be trusted
+            break;
+        }
         ++redo;
         HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
     }

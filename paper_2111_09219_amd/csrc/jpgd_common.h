@@ -141,7 +141,8 @@ constexpr uint32_t kStUnit = 8u;       // unit index and recorded data-unit phas
 struct Status {
     uint32_t flags;
     uint32_t inter_changed;  // boundaries whose first comparison failed in the last inter-sequence round
-    uint32_t pad[2];
+    uint32_t pending;        // set if some sequence's records do not continue the state the sequence before it ends in
+    uint32_t pad;
 };
 
 constexpr int kUnstuffTile = 4096;  // bytes per workgroup of the unstuff kernels (256 lanes x 16 bytes)

@@ -46,7 +46,7 @@ struct Params {
     uint32_t up_n16;
     uint32_t up_wgs;
     // pixel kernel: where its first lane reports the outcome of the write kernel before anything else (pinned host
-    // memory: flags, inter_changed, .., ticket in word 15; null = somebody else reports) and this call's ticket
+    // memory: flags, inter_changed, pending, .., ticket in word 15; null = somebody else reports) and this call's ticket
     uint32_t* verdict;
     uint32_t ticket;
     // A call with one image carries its descriptor in the kernel arguments: every workgroup of every kernel
@@ -874,6 +874,22 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
     Seg tot;
     wg_excl_segscan(seg_of_record(r), scratch, &tot);
     if (threadIdx.x == 0) P.grp_tot[wg] = seg_pack(tot);
+    // The records of a sequence are those of a decoder that entered it in the state `warm_x` holds for it (the
+    // state its workgroup's warm-up lanes arrived in, or the one an inter-sequence lane started from).  If the
+    // sequence before it now ends in another state - an inter-sequence lane rewrote its last record in this very
+    // round, after the lane of this boundary had looked - the states further on can still be right, and the write
+    // pass will find nothing wrong, but the counts and DC sums of the sequence's first records belong to the other
+    // entry state.  The boundaries inside this group are looked at here (at most four: a sequence has at least 65
+    // subsequences), and the host runs another round if one is found.
+    {
+        const uint32_t i0 = (wg - D.grp0) * kWG;
+        const uint32_t first = (i0 + P.seq_len - 1u) / P.seq_len;  // first sequence that starts in this group
+        const uint32_t g = (first + threadIdx.x) * P.seq_len;
+        if (threadIdx.x < 4u && g > 0u && g < nsub && g < i0 + (uint32_t)kWG) {
+            const uint32_t seq = first + threadIdx.x;
+            if (P.warm_x[D.seq0 + seq] != P.sinfo[D.sub0 + g - 1u].x) atomicOr(&P.status->pending, 1u);
+        }
+    }
 }
 
 // one workgroup per image: exclusive prefix of the group totals
@@ -1053,6 +1069,7 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
         volatile uint32_t* host = P.verdict;
         host[0] = P.status->flags;
         host[1] = P.status->inter_changed;
+        host[2] = P.status->pending;
         __threadfence_system();
         host[15] = P.ticket;
     }

@@ -121,7 +121,7 @@ struct Emul {
     std::vector<uint32_t> warm;  // per sequence: the state its records continue (0xFFFFFFFF = none)
     UnitRow rows[8];
     Syntax sx;
-    uint32_t inter_changed = 0, rounds_max = 0, flags = 0;
+    uint32_t inter_changed = 0, rounds_max = 0, flags = 0, pending = 0;
 };
 
 // The wavefront-per-chain decoder of jpgd_kernels.h (coop_unit_word, coop_span_sync) with its 64 lanes run
@@ -337,11 +337,15 @@ void sync_inter(Emul& E) {
     auto bword = [&](uint32_t k) { return im.bmap[k]; };
     const bool restart = im.in.restart_interval != 0;
     E.inter_changed = 0;
+    // On the GPU all boundaries are looked at together: every lane reads the last record of the sequence before
+    // its boundary when the kernel starts, whatever another lane does to that record later in the same round.
+    std::vector<uint32_t> seen;
+    for (uint32_t b = 0; (uint64_t)(b + 1) * E.seq_len < nsub; ++b) seen.push_back(E.sinfo[(b + 1) * E.seq_len - 1].x);
     for (uint32_t b = 0;; ++b) {
         uint64_t gfirst = (uint64_t)(b + 1) * E.seq_len;
         if (gfirst >= nsub) break;
         uint32_t g = (uint32_t)gfirst, gend = std::min(nsub, g + E.seq_len);
-        uint32_t x0 = E.sinfo[g - 1].x;
+        uint32_t x0 = seen[b];
         if (E.warm[b + 1] == x0) continue;  // the two sequences already form one chain
         Lane l;
         BitWin w;
@@ -380,6 +384,10 @@ void scan_and_write(Emul& E, int16_t* coef) {
     int32_t pred[3] = {0, 0, 0};
     std::vector<uint32_t> strm;
     E.flags = 0;
+    // k_group_totals: does every sequence's set of records continue the state the sequence before it ends in?
+    E.pending = 0;
+    for (uint32_t b = 0; (uint64_t)(b + 1) * E.seq_len < nsub; ++b)
+        if (E.warm[b + 1] != E.sinfo[(b + 1) * E.seq_len - 1].x) E.pending = 1;
     for (uint32_t i0 = 0; i0 < nsub; i0 += kWG) {
         const uint32_t nloc = std::min<uint32_t>(kWG, nsub - i0);
         const uint32_t first_word = i0 * wps, nwords = nloc * wps + 4;
@@ -519,7 +527,10 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
         if (nseq > 1) { sync_inter(E); ++rounds; }
         scan_and_write(E, coef);
         bool broken = (E.flags & (kStMismatch | kStUnit)) != 0;
-        if (!broken || nseq <= 1 || rounds >= max_rounds) break;
+        if ((!broken && !E.pending) || nseq <= 1 || rounds >= max_rounds) {
+            if (E.pending && nseq > 1) E.flags |= kStMismatch;
+            break;
+        }
     }
     if (stats) {
         stats[0] = rounds; stats[1] = E.inter_changed; stats[2] = E.rounds_max; stats[3] = E.flags;

@@ -294,6 +294,32 @@ def test_randomised_calls(seed):
                 assert np.abs(batch.pixels(i).cpu().numpy().astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL, (seed, k, i)
 
 
+def test_sequences_that_need_several_inter_sequence_rounds():
+    """A 4:2:0 scan at quality 100 in 128-bit subsequences: decoders need more than a sequence to fall into step, the
+    boundaries between sequences are settled over several rounds, and a round in which one lane rewrites the record
+    another lane's decision rested on must be followed by another (states all right, DC sums of one record not)."""
+    px = small_image(16352, 303, 231, sigma=80.0)
+    data = encode_jpeg(px, 100, "420", False).data
+    o = OracleImage(data)
+    bs = o.boundary_states(128)
+    n = len(bs["p"])
+    live = np.cumsum(bs["units"]) < o.total_units
+    for cfg in (dict(subseq_bits=128), dict(subseq_bits=128, overlap=64), dict(subseq_bits=128, overlap=0)):
+        batch, rep = _decode([data], **cfg)
+        assert rep.inter_rounds >= 3
+        _check_image(batch, 0, data)
+        rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
+        assert np.array_equal(rec["units"][:n][live], bs["units"][live])
+        assert np.array_equal(rec["dcsum"][:n][live].astype(np.int16), bs["dcsum"][live].astype(np.int16))
+    # among other images in one call, and with too few rounds allowed: reported, not returned as it is
+    other = encode_jpeg(small_image(3, 120, 200, sigma=9.0), 85, "444", False).data
+    batch, rep = _decode([other, data, other], subseq_bits=128)
+    for i, f in enumerate([other, data, other]):
+        _check_image(batch, i, f)
+    with pytest.raises(J.JpgdError):
+        _decode([data], subseq_bits=128, max_rounds=2)
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was

@@ -274,6 +274,32 @@ def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H, coop
     assert np.array_equal(dc0[keep], bs["dcsum"][keep, 0].astype(np.int16))
 
 
+def test_host_walkthrough_sequences_that_need_several_inter_sequence_rounds(emul):
+    """A 4:2:0 scan at quality 100 (data units of some 650 bits) cut into 128-bit subsequences: a decoder needs more
+    than a whole sequence to fall into step, so the boundaries between sequences are settled one round after the
+    other.  A boundary lane looks at the last record of the sequence before it when the round starts; if another
+    lane rewrites that record in the same round, the sequence behind the boundary can end up with all states right
+    (the write pass finds nothing) and the DC sums of its first record made for another entry state.  The totals
+    kernel looks for such boundaries and another round follows."""
+    px = small_image(16352, 303, 231, sigma=80.0)
+    data = encode_jpeg(px, 100, "420", False).data
+    o = OracleImage(data)
+    ref = o.coefficients()
+    bs = o.boundary_states(128)
+    live = np.cumsum(bs["units"]) < o.total_units
+    for H in (16, 64, 0):
+        rc, coef, pix, sinfo, stream, stats, _ = _emul_run(emul, data, 128, H)
+        assert rc == 0 and stats[3] == 0
+        assert stats[0] >= 3                      # rounds: the case is what it is meant to be
+        assert np.array_equal(coef, ref)
+        dc01 = sinfo[:, 2]
+        got0 = (dc01 & 0xFFFF).astype(np.uint16).astype(np.int16)
+        assert np.array_equal(got0[live], bs["dcsum"][live, 0].astype(np.int16))
+    # with too few rounds allowed the call must say so instead of returning what it has
+    rc, coef, *_ = _emul_run(emul, data, 128, 16, max_rounds=2)
+    assert rc != 0
+
+
 @pytest.mark.parametrize("sub,opt,q,shape", CASES)
 @pytest.mark.parametrize("L,H,ri", [(128, 0, 1), (128, 16, 3), (256, 0, 2), (1024, 32, 1), (1024, 0, 7), (512, 16, 1000)])
 def test_host_walkthrough_with_restart_intervals(emul, sub, opt, q, shape, L, H, ri):
