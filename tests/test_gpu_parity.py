@@ -320,6 +320,37 @@ def test_sequences_that_need_several_inter_sequence_rounds():
         _decode([data], subseq_bits=128, max_rounds=2)
 
 
+def test_randomised_calls_in_the_regime_of_many_inter_sequence_rounds():
+    """High-quality scans cut into small subsequences, every overlap, with and without restart intervals: the number of
+    inter-sequence rounds ranges from one to dozens.  Coefficients and the converged records (positions, unit counts,
+    DC sums) are the oracle's."""
+    rng = np.random.default_rng(4711)
+    most = 0
+    for k in range(40):
+        sub = ["420", "422", "444", "420", "gray"][int(rng.integers(5))]
+        h, w = int(rng.integers(150, 700)), int(rng.integers(150, 700))
+        q = int(rng.choice([95, 97, 100, 100]))
+        ri = int(rng.choice([0, 0, 0, 1000, 50, 7]))
+        L = int(rng.choice([128, 128, 256, 512]))
+        ov = int(rng.choice([-1, -1, 0, 16, 64, 191]))
+        px = small_image(70000 + k, h, w, ncomp=1 if sub == "gray" else 3, sigma=float(rng.choice([6.0, 25.0, 80.0, 120.0])))
+        data = encode_jpeg(px, q, sub, bool(rng.integers(2)), restart_interval=ri).data
+        cfg = dict(subseq_bits=L)
+        if ov >= 0:
+            cfg["overlap"] = ov
+        batch, rep = _decode([data], **cfg)
+        most = max(most, rep.inter_rounds)
+        o = _check_image(batch, 0, data)
+        rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
+        bs = o.boundary_states(L)
+        n = len(bs["p"])
+        live = np.cumsum(bs["units"]) < o.total_units
+        assert np.array_equal(rec["p"][:n][live].astype(np.int64), bs["p"][live]), k
+        assert np.array_equal(rec["units"][:n][live], bs["units"][live]), k
+        assert np.array_equal(rec["dcsum"][:n][live].astype(np.int16), bs["dcsum"][live].astype(np.int16)), k
+    assert most >= 4
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
