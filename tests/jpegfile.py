@@ -91,3 +91,56 @@ def value_bits(v: int) -> tuple[int, str]:
     size = abs(v).bit_length()
     raw = v if v > 0 else v + (1 << size) - 1
     return size, format(raw, "0%db" % size)
+
+
+# ---- header surgery on files another encoder wrote (the entropy-coded data stays as it is) ----------------
+
+def _segments(b: bytes):
+    """(offset, marker, length field) of every segment up to and including SOS."""
+    i = 2
+    while i < len(b):
+        assert b[i] == 0xFF
+        mk, ln = b[i + 1], (b[i + 2] << 8) | b[i + 3]
+        yield i, mk, ln
+        if mk == 0xDA:
+            return
+        i += 2 + ln
+
+
+def with_tables_of_its_own_for_the_third_component(data: np.ndarray) -> np.ndarray:
+    """A three-component file whose second and third components share tables 1/1 becomes one whose third component
+    uses tables 2/2, copies of 1/1: the same coefficients, but three DC and three AC tables to keep apart."""
+    b = bytearray(np.asarray(data, np.uint8).tobytes())
+    tabs, sos_at = {}, None
+    for at, mk, ln in _segments(bytes(b)):
+        if mk == 0xC4:
+            j = at + 4
+            while j < at + 2 + ln:
+                n = sum(b[j + 1:j + 17])
+                tabs[b[j]] = (bytes(b[j + 1:j + 17]), bytes(b[j + 17:j + 17 + n]))
+                j += 17 + n
+        if mk == 0xDA:
+            sos_at = at
+    extra = b""
+    for cls in (0, 1):
+        bits, vals = tabs[(cls << 4) | 1]
+        extra += seg(0xC4, bytes([(cls << 4) | 2]) + bits + vals)
+    assert b[sos_at + 4] == 3 and b[sos_at + 5 + 2 * 2 + 1] == 0x11
+    b[sos_at + 5 + 2 * 2 + 1] = 0x22
+    return np.frombuffer(bytes(b[:sos_at]) + extra + bytes(b[sos_at:]), np.uint8).copy()
+
+
+def relabelled_as_1x2(data: np.ndarray) -> np.ndarray:
+    """A 4:2:2 file (luma sampled 2x1: MCUs of 16x8 pixels) re-labelled as one with luma sampled 1x2 (MCUs of 8x16)
+    and the frame size that gives the same grid of MCUs: the scan is the same sequence of data units, so the
+    coefficients are the same, while the pixels are laid out for the new geometry."""
+    b = bytearray(np.asarray(data, np.uint8).tobytes())
+    for at, mk, ln in _segments(bytes(b)):
+        if mk == 0xC0:
+            h, w = (b[at + 5] << 8) | b[at + 6], (b[at + 7] << 8) | b[at + 8]
+            mx, my = -(-w // 16), -(-h // 8)
+            b[at + 5:at + 7] = (my * 16).to_bytes(2, "big")
+            b[at + 7:at + 9] = (mx * 8).to_bytes(2, "big")
+            assert b[at + 11] == 0x21
+            b[at + 11] = 0x12
+    return np.frombuffer(bytes(b), np.uint8).copy()

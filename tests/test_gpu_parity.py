@@ -14,6 +14,8 @@ import paper_2111_09219_amd as J
 from oracle import OracleError, OracleImage, unstuff_bytes
 from workloads import CONFIGS, config_jpeg, encode_jpeg, small_image
 
+import jpegfile as jf
+
 pytestmark = pytest.mark.gpu
 
 PIXEL_TOL = 1
@@ -349,6 +351,27 @@ def test_randomised_calls_in_the_regime_of_many_inter_sequence_rounds():
         assert np.array_equal(rec["units"][:n][live], bs["units"][live]), k
         assert np.array_equal(rec["dcsum"][:n][live].astype(np.int16), bs["dcsum"][live].astype(np.int16)), k
     assert most >= 4
+
+
+def test_six_tables_and_1x2_sampling():
+    """A file whose components each have a DC and an AC table of their own (six tables: the rounds with one
+    wavefront per chain, which know four, stay off) and a file with luma sampled 1x2; alone, and both in one call
+    with an ordinary file between them (the table sets differ from image to image)."""
+    px = small_image(5, 397, 531, sigma=9.0)
+    plain = encode_jpeg(px, 90, "444", False).data
+    six = jf.with_tables_of_its_own_for_the_third_component(plain)
+    tall = jf.relabelled_as_1x2(encode_jpeg(px, 90, "422", True).data)
+    for cfg in (dict(), dict(subseq_bits=128), dict(subseq_bits=1024, overlap=0)):
+        for data in (six, tall):
+            batch, rep = _decode([data], **cfg)
+            _check_image(batch, 0, data)
+        batch, rep = _decode([six, plain, tall, six], **cfg)
+        for i, data in enumerate([six, plain, tall, six]):
+            _check_image(batch, i, data)
+    batch, rep = _decode([tall], flags=J.F_PLANAR)
+    o = OracleImage(tall)
+    for got, ref in zip(batch.planes(0), o.planes(o.coefficients())):
+        assert np.abs(got.cpu().numpy().astype(np.int16) - ref.astype(np.int16)).max() <= PIXEL_TOL
 
 
 def test_coefficients_only():

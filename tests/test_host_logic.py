@@ -274,6 +274,26 @@ def test_host_walkthrough_reproduces_oracle(emul, sub, opt, q, shape, L, H, coop
     assert np.array_equal(dc0[keep], bs["dcsum"][keep, 0].astype(np.int16))
 
 
+def test_host_walkthrough_six_tables_and_1x2_sampling(emul):
+    """Layouts the encoder of the workloads does not write, made by header surgery: a file whose three components
+    each have tables of their own (six tables: more than the wavefront-per-chain rounds handle, so they stay
+    off), and a file whose luma is sampled 1x2 (two luma units one above the other in the MCU)."""
+    px = small_image(5, 197, 331, sigma=9.0)
+    plain = encode_jpeg(px, 90, "444", False).data
+    six = jf.with_tables_of_its_own_for_the_third_component(plain)
+    tall = jf.relabelled_as_1x2(encode_jpeg(px, 90, "422", True).data)
+    assert list(J.jpgd_parse(six).ta)[:3] == [0, 1, 2] and J.jpgd_parse(tall).vsamp[0] == 2
+    assert np.array_equal(OracleImage(six).coefficients(), OracleImage(plain).coefficients())
+    for data in (six, tall):
+        for L, H in ((128, 16), (1024, 0), (256, 64)):
+            rc, coef, pix, sinfo, stream, stats, o = _emul_run(emul, data, L, H)
+            assert rc == 0 and stats[3] == 0
+            ref = o.coefficients()
+            assert np.array_equal(coef, ref)
+            want = o.pixels(ref).reshape(pix.shape)
+            assert np.abs(pix.astype(np.int16) - want.astype(np.int16)).max() <= 1
+
+
 def test_host_walkthrough_sequences_that_need_several_inter_sequence_rounds(emul):
     """A 4:2:0 scan at quality 100 (data units of some 650 bits) cut into 128-bit subsequences: a decoder needs more
     than a whole sequence to fall into step, so the boundaries between sequences are settled one round after the
