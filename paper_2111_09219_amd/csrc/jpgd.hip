@@ -544,21 +544,30 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
 
     uint32_t rounds = 0, redo = 0, flags = 0;
     const uint32_t max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
-    for (;;) {
+    // The first time everything is launched in one go, write pass and pixels included: nearly every call is settled
+    // by one inter-sequence round, and the host need not hear from the GPU in between.  If it is not settled, the
+    // boundaries are settled first (rounds of the inter-sequence kernel and the totals kernel, which says whether a
+    // boundary is still open; paper: the host repeats the phase until all sequences are synchronised) and the write
+    // pass and the pixels run once more at the end.
+    auto launch_scan = [&]() -> int {
         if (pl.bnds) {
             LAUNCH(JPGD_K_SYNC_INTER, k_sync_inter, pl.bnds, 64, lds_inter);
             ++rounds;
         }
         LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, pl.grps, kWG, 0);
         if (big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
-        if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
-        else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
+        return JPGD_OK;
+    };
+    // pending (out): a sequence whose records were made for another entry state than the one the sequence before it
+    // now ends in (k_group_totals).  Its states may all be right, so that the write pass finds nothing, while the
+    // counts and DC sums of its first records are not.
+    auto launch_report = [&](bool with_pixels, bool& pending) -> int {
         const uint32_t ticket = ++g_stage.ticket;
         // The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the
-        // verdict is bad its output is either redone below or reported as unspecified.  Its first lane passes
-        // the verdict on before anything else; the host waits for the verdict alone, and the pixels are
-        // complete in stream order, like the output of any kernel.  Without pixels a one-lane kernel reports.
-        if (want_pixels) {
+        // verdict is bad its output is either redone or reported as unspecified.  Its first lane passes the
+        // verdict on before anything else; the host waits for the verdict alone, and the pixels are complete
+        // in stream order, like the output of any kernel.  Without pixels a one-lane kernel reports.
+        if (with_pixels) {
             P.verdict = g_stage.verdict_dev;
             P.ticket = ticket;
             LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
@@ -569,19 +578,30 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
         HIP_OK(hipGetLastError());
         if ((rc = wait_verdict(stream, ticket)) != JPGD_OK) return rc;
         flags = g_stage.verdict[0];
-        // `pending`: a sequence whose records were made for another entry state than the one the sequence before it
-        // now ends in (k_group_totals).  Its states may all be right, so that the write pass finds nothing, while the
-        // counts and DC sums of its first records are not: it takes another round like a broken chain does.
-        const bool pending = g_stage.verdict[2] != 0u;
-        const bool chain_broken = (flags & (kStMismatch | kStUnit)) != 0;
-        // A broken chain with more than one sequence may only mean that synchronisation needs another
-        // inter-sequence round (paper: the host repeats the phase until all sequences are synchronised).
-        if ((!chain_broken && !pending) || !pl.bnds || rounds >= max_rounds) {
-            if (pending && pl.bnds) flags |= kStMismatch;  // out of rounds: the result is not to be trusted
-            break;
+        pending = g_stage.verdict[2] != 0u;
+        return JPGD_OK;
+    };
+    auto launch_write = [&]() -> int {
+        if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
+        else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
+        return JPGD_OK;
+    };
+    bool pending = false;
+    if ((rc = launch_scan()) || (rc = launch_write()) || (rc = launch_report(want_pixels, pending))) return rc;
+    // A broken chain (a write lane that did not end in the recorded state) with more than one sequence, or an open
+    // boundary, means that the boundaries need more rounds; a broken chain with all boundaries settled is a
+    // corrupt stream, and no round will mend it.
+    if (pending && pl.bnds && rounds < max_rounds) {
+        while (pending && rounds < max_rounds) {
+            ++redo;
+            HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
+            if ((rc = launch_scan()) || (rc = launch_report(false, pending))) return rc;
         }
-        ++redo;
-        HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
+        const bool open = pending;
+        if ((rc = launch_write()) || (rc = launch_report(want_pixels, pending))) return rc;
+        if (open) flags |= kStMismatch;  // out of rounds: the result is not to be trusted
+    } else if (pending && pl.bnds) {
+        flags |= kStMismatch;
     }
 #undef LAUNCH
     if (report) {

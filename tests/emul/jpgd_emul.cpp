@@ -372,6 +372,13 @@ void sync_inter(Emul& E) {
     }
 }
 
+// k_group_totals: does every sequence's set of records continue the state the sequence before it ends in?
+void check_boundaries(Emul& E) {
+    E.pending = 0;
+    for (uint32_t b = 0; (uint64_t)(b + 1) * E.seq_len < E.im.nsub; ++b)
+        if (E.warm[b + 1] != E.sinfo[(b + 1) * E.seq_len - 1].x) E.pending = 1;
+}
+
 void scan_and_write(Emul& E, int16_t* coef) {
     const Image& im = E.im;
     const uint32_t nsub = im.nsub, logL = E.logL, L = 1u << logL, wps = L >> 5;
@@ -384,10 +391,6 @@ void scan_and_write(Emul& E, int16_t* coef) {
     int32_t pred[3] = {0, 0, 0};
     std::vector<uint32_t> strm;
     E.flags = 0;
-    // k_group_totals: does every sequence's set of records continue the state the sequence before it ends in?
-    E.pending = 0;
-    for (uint32_t b = 0; (uint64_t)(b + 1) * E.seq_len < nsub; ++b)
-        if (E.warm[b + 1] != E.sinfo[(b + 1) * E.seq_len - 1].x) E.pending = 1;
     for (uint32_t i0 = 0; i0 < nsub; i0 += kWG) {
         const uint32_t nloc = std::min<uint32_t>(kWG, nsub - i0);
         const uint32_t first_word = i0 * wps, nwords = nloc * wps + 4;
@@ -522,15 +525,22 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
     const uint32_t nseq = (E.im.nsub + E.seq_len - 1) / E.seq_len;
     E.warm.assign(nseq + 1, 0xFFFFFFFFu);
     sync_intra(E);
+    // as the host code of the library: everything once; if a boundary is still open, rounds that settle the
+    // boundaries, then the write pass once more
     uint32_t rounds = 0;
-    for (;;) {
+    auto scan = [&]() {
         if (nseq > 1) { sync_inter(E); ++rounds; }
+        check_boundaries(E);
+    };
+    scan();
+    scan_and_write(E, coef);
+    if (E.pending && nseq > 1 && rounds < max_rounds) {
+        while (E.pending && rounds < max_rounds) scan();
+        const bool open = E.pending != 0;
         scan_and_write(E, coef);
-        bool broken = (E.flags & (kStMismatch | kStUnit)) != 0;
-        if ((!broken && !E.pending) || nseq <= 1 || rounds >= max_rounds) {
-            if (E.pending && nseq > 1) E.flags |= kStMismatch;
-            break;
-        }
+        if (open) E.flags |= kStMismatch;
+    } else if (E.pending && nseq > 1) {
+        E.flags |= kStMismatch;
     }
     if (stats) {
         stats[0] = rounds; stats[1] = E.inter_changed; stats[2] = E.rounds_max; stats[3] = E.flags;
