@@ -114,7 +114,9 @@ typedef struct {
     uint32_t n_subseq;      /* subsequences over all images (upper bound from the stuffed sizes)  */
     uint32_t n_sequences;   /* thread blocks of the intra-sequence kernel                         */
     uint32_t inter_rounds;  /* inter-sequence rounds run                                          */
-    uint32_t redo;          /* times scan+write were repeated because verification failed         */
+    uint32_t redo;          /* further rounds (inter-sequence + totals kernels) it took until every
+                               sequence continued the state the one before it ends in; the write pass
+                               and the pixels then ran a second time                               */
     uint32_t device_flags;  /* raw status word from the device                                    */
     uint32_t launches[JPGD_N_KERNELS];  /* launches of each kernel in this call                          */
     float kernel_ms[JPGD_N_KERNELS];    /* summed duration of the launches selected by timing_mask       */
