@@ -374,6 +374,35 @@ def test_six_tables_and_1x2_sampling():
         assert np.abs(got.cpu().numpy().astype(np.int16) - ref.astype(np.int16)).max() <= PIXEL_TOL
 
 
+def test_decode_on_a_stream_of_the_callers():
+    """The stream argument: the call's kernels run on the caller's stream, after work already queued on it (here
+    the copy that brings the scan in) and before work queued after it (a copy of the pixels), with the default
+    stream left alone; timing brackets are recorded on that stream too."""
+    import torch
+    px = small_image(91, 300, 420, sigma=10.0)
+    data = encode_jpeg(px, 88, "420", False).data
+    o = OracleImage(data)
+    ref = o.coefficients()
+    want = o.pixels(ref)
+    batch = J.prepare_batch([data], J.Config.make(timing_mask=(1 << J.KERNELS.index("sync_intra")) | (1 << J.KERNELS.index("pixels"))))
+    staged = batch.d_scans.clone()
+    batch.d_scans.zero_()
+    batch.d_coef.fill_(-3)
+    batch.d_pixels.fill_(7)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        batch.d_scans.copy_(staged, non_blocking=True)      # queued before the call on the same stream
+        rep = batch.decode(stream=side)
+        out = batch.d_pixels.clone()                         # queued after it
+    side.synchronize()
+    assert np.array_equal(batch.coefficients(0).cpu().numpy(), ref)
+    n = o.width * o.height * 3
+    got = out[:n].cpu().numpy().reshape(o.height, o.width, 3)
+    assert np.abs(got.astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL
+    assert rep.kernel_ms[J.KERNELS.index("sync_intra")] > 0 and rep.kernel_ms[J.KERNELS.index("pixels")] > 0
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
