@@ -403,6 +403,41 @@ def test_decode_on_a_stream_of_the_callers():
     assert rep.kernel_ms[J.KERNELS.index("sync_intra")] > 0 and rep.kernel_ms[J.KERNELS.index("pixels")] > 0
 
 
+def test_calls_from_two_threads():
+    """Two host threads, each with its own buffers and stream, call the library at the same time: calls are
+    serialised inside (one staging buffer, one verdict), and every result is the oracle's."""
+    import threading
+    import torch
+    files = [encode_jpeg(small_image(95 + k, 260 + 40 * k, 380, sigma=9.0), 85 + 5 * k, sub, bool(k)).data
+             for k, sub in enumerate(("420", "444"))]
+    refs = [OracleImage(f).coefficients() for f in files]
+    batches = [J.prepare_batch([f], J.Config.make(subseq_bits=L)) for f, L in zip(files, (128, 0))]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    errors = []
+
+    def work(k):
+        try:
+            for _ in range(40):
+                batches[k].d_coef.zero_()
+                batches[k].decode(stream=streams[k])
+                streams[k].synchronize()
+                if not np.array_equal(batches[k].coefficients(0).cpu().numpy(), refs[k]):
+                    errors.append("thread %d: coefficients differ" % k)
+                    return
+        except Exception as e:  # noqa: BLE001 - reported below
+            errors.append("thread %d: %r" % (k, e))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads)
+    assert errors == []
+    for k in range(2):
+        _check_image(batches[k], 0, files[k])
+
+
 def test_coefficients_only():
     """Calls that ask for no pixels (no pixel buffer, or JPGD_F_NO_PIXELS): the verdict then comes from a kernel of
     its own instead of the pixel kernel's first lane; the coefficients are the same and a pixel buffer that was
