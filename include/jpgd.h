@@ -205,7 +205,9 @@ int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, u
  * next multiple of 16) is compacted into
  * d_out (256-byte aligned, room for n + 256 bytes: the kernel clears 192 bytes after the last one);
  * *out_len [host] receives the unstuffed length.  d_workspace: 256-byte aligned, at least
- * 1024 + 4 * ceil(n / 4096) bytes.  Returns after the stream has drained.
+ * 1024 + 4 * ceil(n / 4096) bytes.  Returns after the stream has drained.  The input is taken as a scan
+ * without restart intervals: only stuffed zeros are dropped (the decode calls, which know a file's DRI, also
+ * drop the RSTm markers).
  */
 int jpgd_unstuff(const uint8_t* d_in /*[device]*/, size_t n, uint8_t* d_out /*[device]*/, size_t* out_len /*[host]*/,
                  void* d_workspace, size_t workspace_bytes, void* stream);
