@@ -33,11 +33,11 @@ MEASURED_ISSUE = {
 }
 
 MEASURED_TRAFFIC = {
-    ("hd1088_444_q90", "sync_intra"): 1.748e6,
-    ("hd1088_444_q90", "write"): 17.09e6,
-    ("hd1088_444_q90", "pixels"): 18.91e6,
+    ("hd1088_444_q90", "sync_intra"): 1.747e6,
+    ("hd1088_444_q90", "write"): 14.65e6,
+    ("hd1088_444_q90", "pixels"): 18.89e6,
     ("uhd16k_420_q92_flat_random", "sync_intra"): 84.75e6,
-    ("uhd16k_420_q92_flat_random", "write"): 1129.0e6,
+    ("uhd16k_420_q92_flat_random", "write"): 1122.0e6,
     ("uhd16k_420_q92_flat_random", "pixels"): 796.3e6,
 }
 
