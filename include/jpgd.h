@@ -124,8 +124,8 @@ typedef struct {
 
 /*
  * Host only, touches no GPU.  Reads the marker segments of a baseline JPEG
- * file (paper, Section 4.1: "after parsing the batch and extracting all
- * necessary Huffman tables") and locates the entropy-coded segment without
+ * file (paper, Section 4.1: the batch is parsed and the Huffman tables are
+ * extracted on the host before any kernel runs) and locates the entropy-coded segment without
  * scanning it: it ends at the last EOI marker of the file.
  *
  * Accepted: SOF0, 8-bit, one scan, 1 component or 3 components with chroma
@@ -134,8 +134,9 @@ typedef struct {
  * JPGD_E_UNSUPPORTED: progressive / extended / lossless / arithmetic frames,
  * 12-bit, other component counts or sampling, several scans.
  * JPGD_E_TABLE: table id > 3, more than 256 symbols, more codes of some
- * length than that length can hold, a DC table with a symbol above 15 (a DC
- * symbol is a number of value bits), a table a component refers to missing.
+ * length than that length can hold, a DC table with a symbol above 11 (a DC
+ * symbol is a number of value bits; 8-bit samples need at most 11), a table a
+ * component refers to missing.
  * JPGD_E_TRUNCATED / JPGD_E_MARKER: as named.
  */
 int jpgd_parse(const uint8_t* file /*[host]*/, size_t len, jpgd_info* out /*[host]*/);

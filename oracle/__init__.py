@@ -5,6 +5,6 @@ this package.  It wraps jpeg_oracle.c (a plain sequential baseline-JPEG decoder,
 double-precision pixel path) through ctypes and imports nothing from the GPU
 package or from the input generators.
 """
-from .oracle import (OracleError, OracleImage, build, idct8x8, unstuff_bytes, zigzag)
+from .oracle import (OracleError, OracleImage, build, idct8x8, idct_scaled, unstuff_bytes, zigzag)
 
-__all__ = ["OracleError", "OracleImage", "build", "idct8x8", "unstuff_bytes", "zigzag"]
+__all__ = ["OracleError", "OracleImage", "build", "idct8x8", "idct_scaled", "unstuff_bytes", "zigzag"]

@@ -774,3 +774,139 @@ int orc_decode_planes(const orc_image* im, const int16_t* coef, uint8_t* planes)
         }
     return ORC_OK;
 }
+
+/* ------------------------------------------------------ reduced-size output */
+/*
+ * Output at 1/d of the size, d = 2, 4 or 8, computed in the transform domain (the paper stops at full-size
+ * planes, Section 4.3, and names the inverse transform as the stage that now limits the decoder, Section 6;
+ * a decoder that feeds a training pipeline usually wants a smaller image than the file holds and can skip
+ * most of that stage).  The definition used here is the usual one for block transforms: of every data unit
+ * only the n x n lowest frequencies are kept, n = 8 / d, and the n-point inverse transform of the same
+ * family is applied to them,
+ *   f(y,x) = 1/4 * sum_{u<n} sum_{v<n} C(u) C(v) F(v,u) cos((2x+1) u pi / (2n)) cos((2y+1) v pi / (2n)),
+ * with the factor 1/4 of the 8-point transform kept, so that a unit that holds only a DC term keeps its
+ * value (DC * Q / 8) at every size.  Every data unit thus yields n x n samples; everything after that is as
+ * at full size: level shift, chroma replicated by the sampling factors, JFIF colour matrix, one rounding at
+ * the very end, crop.  The output has ceil(width / d) x ceil(height / d) pixels; a component plane has
+ * ceil(plane_w / d) x ceil(plane_h / d) samples.  d = 1 is the full-size path above.
+ */
+void orc_idct_scaled(const double F[64], int n, double* f) {
+    const double pi = 3.14159265358979323846;
+    for (int y = 0; y < n; ++y)
+        for (int x = 0; x < n; ++x) {
+            double s = 0.0;
+            for (int v = 0; v < n; ++v)
+                for (int u = 0; u < n; ++u) {
+                    double cu = u == 0 ? 1.0 / sqrt(2.0) : 1.0, cv = v == 0 ? 1.0 / sqrt(2.0) : 1.0;
+                    s += cu * cv * F[v * 8 + u] * cos((2 * x + 1) * u * pi / (2.0 * n)) * cos((2 * y + 1) * v * pi / (2.0 * n));
+                }
+            f[y * n + x] = 0.25 * s;
+        }
+}
+
+static int scale_ok(int d) { return d == 1 || d == 2 || d == 4 || d == 8; }
+
+/* n x n samples (double, level shift applied, not rounded) of data unit k at 1/d size, n = 8 / d */
+static void unit_samples_scaled(const orc_image* im, const int16_t* coef, int64_t k, int n, double* out) {
+    int u = (int)(k % im->info.units_per_mcu);
+    const uint16_t* q = im->info.qt[im->info.tq[im->unit_comp[u]]];
+    double F[64];
+    for (int i = 0; i < 64; ++i) F[g_zz[i]] = (double)coef[k * 64 + i] * (double)q[i];
+    orc_idct_scaled(F, n, out);
+    for (int i = 0; i < n * n; ++i) out[i] += 128.0;
+}
+
+int orc_scaled_size(const orc_image* im, int d, int32_t* w, int32_t* h) {
+    if (!im || !scale_ok(d)) return ORC_E_ARG;
+    *w = (im->info.width + d - 1) / d;
+    *h = (im->info.height + d - 1) / d;
+    return ORC_OK;
+}
+
+int orc_scaled_plane_size(const orc_image* im, int d, int c, int32_t* w, int32_t* h) {
+    if (!im || !scale_ok(d)) return ORC_E_ARG;
+    int32_t pw, ph;
+    int rc = orc_plane_size(im, c, &pw, &ph);
+    if (rc) return rc;
+    *w = (pw + d - 1) / d;
+    *h = (ph + d - 1) / d;
+    return ORC_OK;
+}
+
+/* interleaved gray or RGB image of ceil(height/d) x ceil(width/d) pixels */
+int orc_decode_pixels_scaled(const orc_image* im, const int16_t* coef, int d, uint8_t* pixels) {
+    if (!im || !coef || !pixels || !scale_ok(d)) return ORC_E_ARG;
+    init_tables();
+    const orc_info* in = &im->info;
+    const int n = 8 / d;
+    int32_t ow, oh;
+    orc_scaled_size(im, d, &ow, &oh);
+    int mw = n * in->hmax, mh = n * in->vmax; /* output pixels per MCU */
+    double* plane = (double*)malloc(sizeof(double) * 3 * (size_t)mw * mh);
+    double blk[64];
+    for (int my = 0; my < in->mcus_y; ++my)
+        for (int mx = 0; mx < in->mcus_x; ++mx) {
+            int64_t k0 = ((int64_t)my * in->mcus_x + mx) * in->units_per_mcu;
+            for (int u = 0; u < in->units_per_mcu; ++u) {
+                int c = im->unit_comp[u];
+                unit_samples_scaled(im, coef, k0 + u, n, blk);
+                int rx = in->hmax / in->hs[c], ry = in->vmax / in->vs[c];
+                for (int y = 0; y < n; ++y)
+                    for (int x = 0; x < n; ++x)
+                        for (int dy = 0; dy < ry; ++dy)
+                            for (int dx = 0; dx < rx; ++dx) {
+                                int px = (im->unit_bx[u] * n + x) * rx + dx;
+                                int py = (im->unit_by[u] * n + y) * ry + dy;
+                                plane[((size_t)c * mh + py) * mw + px] = blk[y * n + x];
+                            }
+            }
+            for (int y = 0; y < mh; ++y)
+                for (int x = 0; x < mw; ++x) {
+                    int gx = mx * mw + x, gy = my * mh + y;
+                    if (gx >= ow || gy >= oh) continue;
+                    uint8_t* o = pixels + ((size_t)gy * ow + gx) * in->ncomp;
+                    double Y = plane[((size_t)0 * mh + y) * mw + x];
+                    if (in->ncomp == 1) { o[0] = to_u8(Y); continue; }
+                    double Cb = plane[((size_t)1 * mh + y) * mw + x] - 128.0;
+                    double Cr = plane[((size_t)2 * mh + y) * mw + x] - 128.0;
+                    o[0] = to_u8(Y + 1.402 * Cr);
+                    o[1] = to_u8(Y - 0.344136 * Cb - 0.714136 * Cr);
+                    o[2] = to_u8(Y + 1.772 * Cb);
+                }
+        }
+    free(plane);
+    return ORC_OK;
+}
+
+/* the component planes at 1/d size, one after the other */
+int orc_decode_planes_scaled(const orc_image* im, const int16_t* coef, int d, uint8_t* planes) {
+    if (!im || !coef || !planes || !scale_ok(d)) return ORC_E_ARG;
+    init_tables();
+    const orc_info* in = &im->info;
+    const int n = 8 / d;
+    size_t base[3] = {0, 0, 0};
+    int32_t pw[3], ph[3];
+    size_t off = 0;
+    for (int c = 0; c < in->ncomp; ++c) {
+        orc_scaled_plane_size(im, d, c, &pw[c], &ph[c]);
+        base[c] = off;
+        off += (size_t)pw[c] * ph[c];
+    }
+    double blk[64];
+    for (int my = 0; my < in->mcus_y; ++my)
+        for (int mx = 0; mx < in->mcus_x; ++mx) {
+            int64_t k0 = ((int64_t)my * in->mcus_x + mx) * in->units_per_mcu;
+            for (int u = 0; u < in->units_per_mcu; ++u) {
+                int c = im->unit_comp[u];
+                unit_samples_scaled(im, coef, k0 + u, n, blk);
+                for (int y = 0; y < n; ++y)
+                    for (int x = 0; x < n; ++x) {
+                        int gx = (mx * in->hs[c] + im->unit_bx[u]) * n + x;
+                        int gy = (my * in->vs[c] + im->unit_by[u]) * n + y;
+                        if (gx >= pw[c] || gy >= ph[c]) continue;
+                        planes[base[c] + (size_t)gy * pw[c] + gx] = to_u8(blk[y * n + x]);
+                    }
+            }
+        }
+    return ORC_OK;
+}

@@ -83,6 +83,12 @@ def _load():
         lib.orc_decode_pixels.argtypes = [vp, vp, vp]
         lib.orc_decode_planes.argtypes = [vp, vp, vp]
         lib.orc_plane_size.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.orc_idct_scaled.argtypes = [vp, i32, vp]
+        lib.orc_idct_scaled.restype = None
+        lib.orc_scaled_size.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.orc_scaled_plane_size.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.orc_decode_pixels_scaled.argtypes = [vp, vp, i32, vp]
+        lib.orc_decode_planes_scaled.argtypes = [vp, vp, i32, vp]
         _lib = lib
     return _lib
 
@@ -114,6 +120,14 @@ def idct8x8(F: np.ndarray) -> np.ndarray:
     out = np.empty(64, dtype=np.float64)
     _load().orc_idct8x8(src.ctypes.data, out.ctypes.data)
     return out.reshape(8, 8)
+
+
+def idct_scaled(F: np.ndarray, n: int) -> np.ndarray:
+    """n x n samples from the n x n lowest frequencies of the 8x8 block F (n = 8, 4, 2, 1); see jpeg_oracle.c."""
+    src = np.ascontiguousarray(F, dtype=np.float64).reshape(64)
+    out = np.empty(n * n, dtype=np.float64)
+    _load().orc_idct_scaled(src.ctypes.data, n, out.ctypes.data)
+    return out.reshape(n, n)
 
 
 class OracleImage:
@@ -204,6 +218,36 @@ class OracleImage:
         shapes = self.plane_shapes()
         buf = np.zeros(sum(h * w for h, w in shapes), dtype=np.uint8)
         _check(self._lib.orc_decode_planes(self._h, coef.ctypes.data, buf.ctypes.data))
+        out, off = [], 0
+        for h, w in shapes:
+            out.append(buf[off:off + h * w].reshape(h, w))
+            off += h * w
+        return out
+
+    def pixels_scaled(self, denom: int, coef: np.ndarray | None = None) -> np.ndarray:
+        """The image at 1/denom of its size (denom 1, 2, 4, 8): uint8 [ceil(H/denom), ceil(W/denom)(, 3)]."""
+        if coef is None:
+            coef = self.coefficients()
+        coef = np.ascontiguousarray(coef, dtype=np.int16)
+        w, h = ctypes.c_int32(), ctypes.c_int32()
+        _check(self._lib.orc_scaled_size(self._h, denom, ctypes.byref(w), ctypes.byref(h)))
+        shape = (h.value, w.value) if self.ncomp == 1 else (h.value, w.value, 3)
+        out = np.zeros(shape, dtype=np.uint8)
+        _check(self._lib.orc_decode_pixels_scaled(self._h, coef.ctypes.data, denom, out.ctypes.data))
+        return out
+
+    def planes_scaled(self, denom: int, coef: np.ndarray | None = None):
+        """The component planes at 1/denom of their size, uint8."""
+        if coef is None:
+            coef = self.coefficients()
+        coef = np.ascontiguousarray(coef, dtype=np.int16)
+        shapes = []
+        for c in range(self.ncomp):
+            w, h = ctypes.c_int32(), ctypes.c_int32()
+            _check(self._lib.orc_scaled_plane_size(self._h, denom, c, ctypes.byref(w), ctypes.byref(h)))
+            shapes.append((h.value, w.value))
+        buf = np.zeros(sum(h * w for h, w in shapes), dtype=np.uint8)
+        _check(self._lib.orc_decode_planes_scaled(self._h, coef.ctypes.data, denom, buf.ctypes.data))
         out, off = [], 0
         for h, w in shapes:
             out.append(buf[off:off + h * w].reshape(h, w))

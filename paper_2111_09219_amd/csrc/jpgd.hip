@@ -5,7 +5,9 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <chrono>
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "../../include/jpgd.h"
@@ -102,7 +104,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     pl.L = L;
     pl.img.assign(n, ImgDesc());
     pl.lut_of_img.assign(n, 0);
-    size_t stream_bytes = 0, coef_units = 0;
+    size_t stream_bytes = 0;
     for (int i = 0; i < n; ++i) {
         const jpgd_info& in = infos[i];
         ImgDesc& d = pl.img[i];
@@ -149,7 +151,6 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         d.pix_wg0 = pl.pixwgs;
         if ((uint64_t)pl.pixwgs + (uint64_t)d.pix_runs * d.mcus_y > 0x7FFFFFFFull) return JPGD_E_ARG;  // grid size
         pl.pixwgs += d.pix_runs * d.mcus_y;
-        coef_units += d.total_units;
         // table slots: distinct DC tables first, then distinct AC tables, in order of first use
         uint32_t dc_ids[3], ac_ids[3], ndc = 0, nac = 0, comp_dc[3], comp_ac[3];
         for (uint32_t c = 0; c < in.ncomp; ++c) {
@@ -211,14 +212,25 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     return JPGD_OK;
 }
 
-// ---- pinned host memory for the per-call parameters and the verdict ------------------------------------
-// Both are reached from the GPU directly: a small kernel copies the parameters into the workspace and another
-// one reports the verdict, so that nothing but kernels sits in the stream (a copy engine between two kernels,
-// or an event, costs several microseconds of an otherwise idle GPU each).  A call only returns after its verdict
-// has arrived, which is after its parameters were read: one staging buffer is enough, and it may be replaced
-// by a larger one at the start of a call.
-struct Staging {
-    std::mutex mu;
+// ---- one decode call between its enqueue and its wait ---------------------------------------------------
+// Per call: a pinned buffer for the parameter block and a pinned, coherent 64-byte block for the verdict.  Both are
+// reached from the GPU directly: a small kernel (or a few extra workgroups of the first kernel) copies the parameters
+// into the workspace and the first lane of the pixel kernel reports the verdict, so that nothing but kernels sits in
+// the stream (a copy engine between two kernels, or an event, costs several microseconds of an otherwise idle GPU
+// each).  Calls in flight each hold a slot of their own, so that a host thread can enqueue the next batch while the
+// GPU still works on this one (the paper's end-to-end setting, Section 5: transfers and decoding of consecutive
+// batches overlap), and two threads never wait for each other.
+constexpr int kMaxDevices = 16;
+constexpr size_t kStaticWsBytes = (size_t)JPGD_STATIC_WORKSPACE_BYTES;
+constexpr size_t kStaticStageBytes = 64 * 1024;  // parameter block of one image: 20 KB with four tables, 27 KB with six
+
+struct Timed { int kernel; size_t ev; };
+
+}  // namespace
+
+struct jpgd_call {
+    // owned for the life of the process
+    int device = -1;
     uint8_t* buf = nullptr;        // pinned
     uint8_t* buf_dev = nullptr;    // the same bytes as the device addresses them
     size_t cap = 0;
@@ -226,26 +238,83 @@ struct Staging {
     uint32_t* verdict_dev = nullptr;
     uint32_t ticket = 0;
     std::vector<hipEvent_t> timers;  // pairs of events for timing_mask
+    bool busy = false;
+    bool fixed = false;            // the slot of the entry point that allocates nothing: never grown, never shared
+    // the call in flight
+    Plan pl;
+    Params P;
+    hipStream_t stream = nullptr;
+    uint8_t* ws = nullptr;
+    bool want_pixels = false, staged = false, big_groups = false;
+    int variant = 0;
+    size_t lds_sync = 0, lds_write = 0, lds_inter = 0;
+    uint32_t tmask = 0, max_rounds = 0, rounds = 0, redo = 0;
+    std::vector<Timed> timed;
+    uint32_t launches[JPGD_N_KERNELS] = {0};
 };
-Staging g_stage;
 
-int stage_acquire(size_t bytes) {
-    Staging& s = g_stage;
-    if (s.cap < bytes) {
-        if (s.buf) (void)hipHostFree(s.buf);
-        s.buf = s.buf_dev = nullptr;
-        s.cap = 0;
-        size_t want = bytes + (bytes >> 2) + 4096;
-        if (hipHostMalloc((void**)&s.buf, want, hipHostMallocMapped) != hipSuccess) return JPGD_E_HIP;
-        if (hipHostGetDevicePointer((void**)&s.buf_dev, s.buf, 0) != hipSuccess) return JPGD_E_HIP;
-        s.cap = want;
+namespace {
+
+using Call = jpgd_call;
+
+std::mutex g_mu;                 // guards the slot list, the table cache and the per-device bookkeeping; never held
+                                 // while the GPU is waited for
+std::vector<Call*> g_calls;
+constexpr size_t kMaxCalls = 64;
+
+int hip_failed(const char* what, hipError_t e) {
+    fprintf(stderr, "jpgd: %s failed: %s\n", what, hipGetErrorString(e));
+    return JPGD_E_HIP;
+}
+#define HIP_OK(expr)                                                \
+    do {                                                            \
+        hipError_t e_ = (expr);                                     \
+        if (e_ != hipSuccess) return hip_failed(#expr, e_);         \
+    } while (0)
+
+int call_reserve(Call& c, size_t bytes) {
+    if (c.cap < bytes) {
+        if (c.fixed) return JPGD_E_WORKSPACE;
+        if (c.buf) (void)hipHostFree(c.buf);
+        c.buf = c.buf_dev = nullptr;
+        c.cap = 0;
+        const size_t want = bytes + (bytes >> 2) + 4096;
+        HIP_OK(hipHostMalloc((void**)&c.buf, want, hipHostMallocMapped));
+        HIP_OK(hipHostGetDevicePointer((void**)&c.buf_dev, c.buf, 0));
+        c.cap = want;
     }
-    if (!s.verdict) {
-        if (hipHostMalloc((void**)&s.verdict, 64, hipHostMallocMapped | hipHostMallocCoherent) != hipSuccess) return JPGD_E_HIP;
-        if (hipHostGetDevicePointer((void**)&s.verdict_dev, s.verdict, 0) != hipSuccess) return JPGD_E_HIP;
-        memset(s.verdict, 0, 64);
+    if (!c.verdict) {
+        if (c.fixed) return JPGD_E_WORKSPACE;
+        HIP_OK(hipHostMalloc((void**)&c.verdict, 64, hipHostMallocMapped | hipHostMallocCoherent));
+        HIP_OK(hipHostGetDevicePointer((void**)&c.verdict_dev, c.verdict, 0));
+        memset(c.verdict, 0, 64);
     }
     return JPGD_OK;
+}
+
+// a free slot of the current device (a new one if all are in flight)
+int call_acquire(Call** out) {
+    int dev = 0;
+    HIP_OK(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mu);
+    for (Call* c : g_calls)
+        if (!c->busy && !c->fixed && c->device == dev) {
+            c->busy = true;
+            *out = c;
+            return JPGD_OK;
+        }
+    if (g_calls.size() >= kMaxCalls) return JPGD_E_BUSY;
+    Call* c = new Call();
+    c->device = dev;
+    c->busy = true;
+    g_calls.push_back(c);
+    *out = c;
+    return JPGD_OK;
+}
+
+void call_release(Call* c) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    c->busy = false;
 }
 
 __global__ __launch_bounds__(kWG) void k_upload(const uint4* __restrict__ src, uint4* __restrict__ dst, uint32_t n16) {
@@ -263,9 +332,20 @@ __global__ void k_verdict(const Status* st, volatile uint32_t* host, uint32_t ti
     }
 }
 
+// The status words go back to zero before a further round.  A kernel, not a memset: callers may capture the
+// stream, and the rest of the path is kernels only.
+__global__ void k_clear_status(Status* st) {
+    if (threadIdx.x == 0) {
+        st->flags = 0u;
+        st->inter_changed = 0u;
+        st->pending = 0u;
+        st->pad = 0u;
+    }
+}
+
 // Lookup tables built recently, keyed by the DHT lists they came from: most files share a handful of
 // tables (the typical ones of the standard above all), and building one costs a few microseconds of a
-// call that may take a hundred.  Callers hold g_stage.mu.
+// call that may take a hundred.  Guarded by g_lut_mu.
 struct LutCacheEntry {
     bool is_dc;
     uint8_t bits[16];
@@ -274,6 +354,7 @@ struct LutCacheEntry {
     uint64_t stamp;
     uint16_t lut[kLutEntries];
 };
+std::mutex g_lut_mu;
 std::vector<LutCacheEntry> g_lut_cache;
 uint64_t g_lut_clock = 0;
 constexpr size_t kLutCacheMax = 32;
@@ -282,6 +363,7 @@ bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_
     uint32_t nvals = 0;
     for (int k = 0; k < 16; ++k) nvals += bits[k];
     if (nvals > 256u) return false;
+    std::lock_guard<std::mutex> lock(g_lut_mu);
     for (LutCacheEntry& e : g_lut_cache)
         if (e.is_dc == is_dc && e.nvals == nvals && !memcmp(e.bits, bits, 16) && !memcmp(e.vals, vals, nvals)) {
             e.stamp = ++g_lut_clock;
@@ -307,26 +389,28 @@ bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_
     return true;
 }
 
-int hip_failed(const char* what, hipError_t e) {
-    fprintf(stderr, "jpgd: %s failed: %s\n", what, hipGetErrorString(e));
-    return JPGD_E_HIP;
-}
-#define HIP_OK(expr)                                                \
-    do {                                                            \
-        hipError_t e_ = (expr);                                     \
-        if (e_ != hipSuccess) return hip_failed(#expr, e_);         \
-    } while (0)
-
-// Spins until k_verdict has reported under `ticket`.  The stream is asked now and then, so that a failed
+// Waits until the verdict has been reported under `ticket`.  A short decode is answered within microseconds, so the
+// wait starts as a spin on the pinned word; after 50 microseconds the thread yields between looks and after 2 ms it
+// sleeps, so that a long decode does not cost a busy core.  The stream is asked now and then, so that a failed
 // launch or a lost report ends the wait with an error instead of hanging.
-int wait_verdict(hipStream_t stream, uint32_t ticket) {
-    volatile uint32_t* v = g_stage.verdict;
-    for (uint32_t spins = 1;; ++spins) {
-        if (v[15] == ticket) break;
-        if ((spins & 0x3FFFu) == 0u) {
-            hipError_t q = hipStreamQuery(stream);
+int wait_verdict(Call& c) {
+    volatile uint32_t* v = c.verdict;
+    const auto t0 = std::chrono::steady_clock::now();
+    int64_t waited_us = 0;
+    for (uint32_t looks = 1;; ++looks) {
+        if (v[15] == c.ticket) break;
+        if (waited_us < 50) {
+            if ((looks & 63u) == 0u)
+                waited_us = std::chrono::duration_cast<std::chrono::microseconds>(std::chrono::steady_clock::now() - t0).count();
+            continue;
+        }
+        waited_us = std::chrono::duration_cast<std::chrono::microseconds>(std::chrono::steady_clock::now() - t0).count();
+        if (waited_us < 2000) std::this_thread::yield();
+        else std::this_thread::sleep_for(std::chrono::microseconds(50));
+        if ((looks & 0xFFu) == 0u) {
+            hipError_t q = hipStreamQuery(c.stream);
             if (q == hipSuccess) {
-                if (v[15] == ticket) break;
+                if (v[15] == c.ticket) break;
                 fprintf(stderr, "jpgd: the stream is idle but the verdict has not arrived\n");
                 return JPGD_E_HIP;
             }
@@ -361,62 +445,120 @@ size_t lds_write_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
 }
 
-// dynamic LDS beyond the default limit has to be requested per kernel; remember what was granted
-size_t g_lds_granted[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-int grant_lds(int which, const void* kernel, size_t bytes) {
-    if (bytes <= 48 * 1024 || bytes <= g_lds_granted[which]) return JPGD_OK;
+// dynamic LDS beyond the default limit has to be requested per kernel and device; remember what was granted
+size_t g_lds_granted[kMaxDevices][9];
+int grant_lds(int dev, int which, const void* kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return JPGD_OK;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (dev < 0 || dev >= kMaxDevices) return JPGD_E_ARG;
+    if (bytes <= g_lds_granted[dev][which]) return JPGD_OK;
     HIP_OK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-    g_lds_granted[which] = bytes;
+    g_lds_granted[dev][which] = bytes;
     return JPGD_OK;
 }
 
-}  // namespace
+// ---- launches ---------------------------------------------------------------------------------------
 
-extern "C" size_t jpgd_workspace_bytes(const jpgd_info* infos, int n_images, const jpgd_config* cfg) {
-    Plan pl;
-    if (make_plan(infos, n_images, cfg, pl) != JPGD_OK) return 0;
-    return pl.h.total_bytes;
+int t_begin(Call& c, int k) {
+    c.launches[k]++;
+    if (!(c.tmask & (1u << k))) return JPGD_OK;
+    const size_t need = 2 * (c.timed.size() + 1);
+    while (c.timers.size() < need) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return JPGD_E_HIP;
+        c.timers.push_back(e);
+    }
+    c.timed.push_back({k, 2 * c.timed.size()});
+    return hipEventRecord(c.timers[c.timed.back().ev], c.stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
+}
+int t_end(Call& c, int k) {
+    if (!(c.tmask & (1u << k))) return JPGD_OK;
+    return hipEventRecord(c.timers[c.timed.back().ev + 1], c.stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
+}
+#define LAUNCH(K, kernel, grid, block, lds)                                       \
+    do {                                                                          \
+        int rc_ = t_begin(c, K);                                                  \
+        if (rc_ != JPGD_OK) return rc_;                                           \
+        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, c.stream, c.P);  \
+        if ((rc_ = t_end(c, K)) != JPGD_OK) return rc_;                           \
+    } while (0)
+
+// inter-sequence round, group totals, prefix of the totals
+int launch_scan(Call& c) {
+    if (c.pl.bnds) {
+        LAUNCH(JPGD_K_SYNC_INTER, k_sync_inter, c.pl.bnds, 64, c.lds_inter);
+        ++c.rounds;
+    }
+    LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, c.pl.grps, kWG, 0);
+    if (c.big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, c.pl.h.nimg, kWG, 0);
+    return JPGD_OK;
 }
 
-extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
-                                 int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
-                                 const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
-                                 const jpgd_config* cfg, void* stream_v, jpgd_report* report) {
-    if (!infos || n < 1 || !d_scans || !scan_offsets || !d_coef || !coef_offsets || !d_workspace) return JPGD_E_ARG;
-    if (d_pixels && !pixel_offsets) return JPGD_E_ARG;
-    if (((uintptr_t)d_scans & 15u) || ((uintptr_t)d_coef & 15u)) return JPGD_E_ARG;
-    if ((uintptr_t)d_workspace & 255u) return JPGD_E_WORKSPACE;
-    Plan pl;
+int launch_write(Call& c) {
+    if (c.staged) LAUNCH(JPGD_K_WRITE, k_write<true>, c.pl.grps, kWG, c.lds_write);
+    else LAUNCH(JPGD_K_WRITE, k_write<false>, c.pl.grps, kWG, c.lds_write);
+    return JPGD_OK;
+}
+
+// The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the verdict is bad
+// its output is either redone or reported as unspecified.  Its first lane passes the verdict on before anything
+// else; the host waits for the verdict alone, and the pixels are complete in stream order, like the output of any
+// kernel.  Without pixels a one-lane kernel reports.
+int launch_report(Call& c, bool with_pixels) {
+    const uint32_t ticket = ++c.ticket;
+    if (with_pixels) {
+        c.P.verdict = c.verdict_dev;
+        c.P.ticket = ticket;
+        if (c.P.scale_log2 == 0u) LAUNCH(JPGD_K_PIXELS, k_pixels, c.pl.pixwgs, kWG, 0);
+        else if (c.P.scale_log2 == 1u) LAUNCH(JPGD_K_PIXELS, k_pixels_scaled<4>, c.pl.pixwgs, kWG, 0);
+        else if (c.P.scale_log2 == 2u) LAUNCH(JPGD_K_PIXELS, k_pixels_scaled<2>, c.pl.pixwgs, kWG, 0);
+        else LAUNCH(JPGD_K_PIXELS, k_pixels_scaled<1>, c.pl.pixwgs, kWG, 0);
+    } else {
+        hipLaunchKernelGGL(k_verdict, dim3(1), dim3(64), 0, c.stream, (const Status*)(c.ws + c.pl.h.off_status),
+                           (volatile uint32_t*)c.verdict_dev, ticket);
+    }
+    HIP_OK(hipGetLastError());
+    return JPGD_OK;
+}
+
+// Everything of a call up to and including its first report: validation, plan, parameter block, all kernels.
+// Nothing here waits for the GPU.  ws_cap: bytes behind d_workspace.
+int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                 int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels, const uint64_t* pixel_offsets,
+                 void* d_workspace, size_t ws_cap, const jpgd_config* cfg, hipStream_t stream) {
+    Plan& pl = c.pl;
     int rc = make_plan(infos, n, cfg, pl);
     if (rc) return rc;
-    if (workspace_bytes < pl.h.total_bytes) return JPGD_E_WORKSPACE;
-    const bool want_pixels = d_pixels && !(cfg && (cfg->flags & JPGD_F_NO_PIXELS));
+    if (ws_cap < pl.h.total_bytes) return JPGD_E_WORKSPACE;
+    const uint32_t flags_in = cfg ? cfg->flags : 0u;
+    const uint32_t scale_log2 = (flags_in & JPGD_F_SCALE_8) == JPGD_F_SCALE_8 ? 3u : (flags_in & JPGD_F_SCALE_4) ? 2u : (flags_in & JPGD_F_SCALE_2) ? 1u : 0u;
+    c.want_pixels = d_pixels && !(flags_in & JPGD_F_NO_PIXELS);
     for (int i = 0; i < n; ++i) {
         if (scan_offsets[i] & 15u) return JPGD_E_ARG;
         if (coef_offsets[i] & 63u) return JPGD_E_ARG;
         pl.img[i].scan_off = scan_offsets[i];
         pl.img[i].coef_off = coef_offsets[i];
-        pl.img[i].pix_off = want_pixels ? pixel_offsets[i] : 0;
+        pl.img[i].pix_off = c.want_pixels ? pixel_offsets[i] : 0;
     }
-    hipStream_t stream = (hipStream_t)stream_v;
+    c.stream = stream;
+    c.ws = (uint8_t*)d_workspace;
     const bool any_restart = pl.bmap_words != 0u;
-    const size_t lds_sync = lds_sync_bytes(pl.L, pl.lut_slots, any_restart), lds_write = lds_write_bytes(pl.L, pl.lut_slots, any_restart);
-    const size_t lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
-    if (lds_sync > 150 * 1024) return JPGD_E_ARG;
-
-    std::lock_guard<std::mutex> lock(g_stage.mu);
-    const bool staged = pl.L <= kStagedMaxL;
+    c.lds_sync = lds_sync_bytes(pl.L, pl.lut_slots, any_restart);
+    c.lds_write = lds_write_bytes(pl.L, pl.lut_slots, any_restart);
+    c.lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
+    if (c.lds_sync > 150 * 1024) return JPGD_E_ARG;
+    c.staged = pl.L <= kStagedMaxL;
     // the variants of the intra-sequence kernel: stream staged in LDS or not, call with or without restart intervals
-    const int variant = (staged ? 0 : 1) + (any_restart ? 2 : 0);
+    c.variant = (c.staged ? 0 : 1) + (any_restart ? 2 : 0);
     const void* const sync_kernels[4] = {(const void*)k_sync_intra<true, false>, (const void*)k_sync_intra<false, false>,
                                          (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
-    if ((rc = grant_lds(variant, sync_kernels[variant], lds_sync)) ||
-        (rc = grant_lds(staged ? 4 : 5, staged ? (const void*)k_write<true> : (const void*)k_write<false>, lds_write)) ||
-        (rc = grant_lds(8, (const void*)k_sync_inter, lds_inter)))
+    if ((rc = grant_lds(c.device, c.variant, sync_kernels[c.variant], c.lds_sync)) ||
+        (rc = grant_lds(c.device, c.staged ? 4 : 5, c.staged ? (const void*)k_write<true> : (const void*)k_write<false>, c.lds_write)) ||
+        (rc = grant_lds(c.device, 8, (const void*)k_sync_inter, c.lds_inter)))
         return rc;
-    rc = stage_acquire(pl.h.upload_bytes + 16);
+    rc = call_reserve(c, pl.h.upload_bytes + 16);
     if (rc) return rc;
-    uint8_t* up = g_stage.buf;
+    uint8_t* up = c.buf;
     memset(up, 0, pl.h.upload_bytes);
     memcpy(up, &pl.h, sizeof pl.h);
     memcpy(up + pl.h.off_img, pl.img.data(), sizeof(ImgDesc) * (size_t)n);
@@ -429,32 +571,30 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
             uint16_t* set = luts + d.lut_off;
             uint32_t built = 0u;  // slots of this set already filled
             for (uint32_t u = 0; u < d.upm; ++u) {
-                uint32_t c = (d.sched_comp >> (4 * u)) & 15u;
+                uint32_t cc = (d.sched_comp >> (4 * u)) & 15u;
                 uint32_t sd = (d.sched_dc >> (4 * u)) & 15u, sa = (d.sched_ac >> (4 * u)) & 15u;
                 if (!(built & (1u << sd)) &&
-                    !cached_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, set + sd * kLutEntries))
+                    !cached_lut(in.dht_bits[0][in.td[cc]], in.dht_vals[0][in.td[cc]], true, set + sd * kLutEntries))
                     return JPGD_E_TABLE;
                 built |= 1u << sd;
                 if (!(built & (1u << sa)) &&
-                    !cached_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, set + sa * kLutEntries))
+                    !cached_lut(in.dht_bits[1][in.ta[cc]], in.dht_vals[1][in.ta[cc]], false, set + sa * kLutEntries))
                     return JPGD_E_TABLE;
                 built |= 1u << sa;
             }
         }
-        for (uint32_t c = 0; c < in.ncomp; ++c)
-            for (int k = 0; k < 64; ++k) qts[d.qt_off + c * 64 + k] = in.qt[in.tq[c]][k];
+        for (uint32_t cc = 0; cc < in.ncomp; ++cc)
+            for (int k = 0; k < 64; ++k) qts[d.qt_off + cc * 64 + k] = in.qt[in.tq[cc]][k];
     }
-    uint8_t* ws = (uint8_t*)d_workspace;
+    uint8_t* ws = c.ws;
     // The parameter block goes from the pinned buffer into the workspace: for a batch by a kernel of its own (the
     // first kernel of the path already looks its image up in the block), for a single image by extra workgroups of
     // that first kernel, which then finds all it needs in its arguments.
     const uint32_t up_n16 = (uint32_t)((pl.h.upload_bytes + 15u) / 16u);
     uint32_t up_wgs = (up_n16 + kWG - 1u) / kWG;
     if (up_wgs > 256u) up_wgs = 256u;
-    if (n > 1)
-        hipLaunchKernelGGL(k_upload, dim3(up_wgs), dim3(kWG), 0, stream, (const uint4*)g_stage.buf_dev, (uint4*)ws, up_n16);
 
-    Params P;
+    Params& P = c.P;
     P.img = (const ImgDesc*)(ws + pl.h.off_img);
     P.st = (ImgState*)(ws + pl.h.off_state);
     P.status = (Status*)(ws + pl.h.off_status);
@@ -475,7 +615,8 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.overlap = pl.h.overlap;
     P.seq_len = kWG - pl.h.overlap;
     P.lut_slots = pl.lut_slots;
-    P.planar = (cfg && (cfg->flags & JPGD_F_PLANAR)) ? 1u : 0u;
+    P.planar = (flags_in & JPGD_F_PLANAR) ? 1u : 0u;
+    P.scale_log2 = scale_log2;
     // Wavefronts per workgroup of the intra-sequence kernel: as many as the CU's 32 slots allow beside the other
     // workgroups it will hold (LDS, or the size of the grid, decides how many those are), at most 16; more than
     // 8 only pay when a round is long (measured: 16 instead of 8 gains 5 % at 1024 bits, nothing at 128).  Calls
@@ -483,7 +624,7 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     uint32_t sync_waves = (uint32_t)(kWG / 64);
     {
         const uint32_t slots = any_restart ? 20u : 32u;  // the kernel for restart intervals needs 92 registers: 5 per SIMD
-        const uint32_t by_lds = (uint32_t)(160u * 1024u / lds_sync), by_grid = (pl.seqs + 255u) / 256u;
+        const uint32_t by_lds = (uint32_t)(160u * 1024u / c.lds_sync), by_grid = (pl.seqs + 255u) / 256u;
         const uint32_t per_cu = by_lds < by_grid ? (by_lds ? by_lds : 1u) : by_grid;
         const uint32_t most = pl.L >= 512u ? (uint32_t)kSyncWavesMax : 8u;
         while (sync_waves * 2u <= most && sync_waves * 2u * per_cu <= slots) sync_waves *= 2u;
@@ -492,135 +633,172 @@ extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d
     P.coop_max = kCoopMax * sync_waves / (uint32_t)(kWG / 64);
     P.verdict = nullptr;
     P.ticket = 0u;
-    P.up_src = (const uint4*)g_stage.buf_dev;
+    P.up_src = (const uint4*)c.buf_dev;
     P.up_dst = (uint4*)ws;
     P.up_n16 = up_n16;
     P.up_wgs = n > 1 ? 0u : up_wgs;
     P.img0 = pl.img[0];
 
-    // optional bracketing of single kernels with events (jpgd_config.timing_mask)
-    const uint32_t tmask = cfg ? cfg->timing_mask : 0u;
-    struct Timed { int kernel; size_t ev; };
-    std::vector<Timed> timed;
-    uint32_t launches[JPGD_N_KERNELS] = {0};
-    auto t_begin = [&](int k) -> int {
-        launches[k]++;
-        if (!(tmask & (1u << k))) return JPGD_OK;
-        size_t need = 2 * (timed.size() + 1);
-        while (g_stage.timers.size() < need) {
-            hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) return JPGD_E_HIP;
-            g_stage.timers.push_back(e);
-        }
-        timed.push_back({k, 2 * timed.size()});
-        return hipEventRecord(g_stage.timers[timed.back().ev], stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
-    };
-    auto t_end = [&](int k) -> int {
-        if (!(tmask & (1u << k))) return JPGD_OK;
-        return hipEventRecord(g_stage.timers[timed.back().ev + 1], stream) == hipSuccess ? JPGD_OK : JPGD_E_HIP;
-    };
-#define LAUNCH(K, kernel, grid, block, lds)                                   \
-    do {                                                                      \
-        if ((rc = t_begin(K)) != JPGD_OK) return rc;                          \
-        hipLaunchKernelGGL(kernel, dim3(grid), dim3(block), lds, stream, P);  \
-        if ((rc = t_end(K)) != JPGD_OK) return rc;                            \
-    } while (0)
+    c.tmask = cfg ? cfg->timing_mask : 0u;
+    c.timed.clear();
+    memset(c.launches, 0, sizeof c.launches);
+    c.rounds = c.redo = 0u;
+    c.max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
 
+    if (n > 1)
+        hipLaunchKernelGGL(k_upload, dim3(up_wgs), dim3(kWG), 0, stream, (const uint4*)c.buf_dev, (uint4*)ws, up_n16);
     LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles + P.up_wgs, kWG, 0);
     P.up_wgs = 0u;
-    bool big_tiles = false, big_groups = false;  // the two image-level scans are only needed beyond 256 tiles / groups
+    bool big_tiles = false;  // the two image-level scans are only needed beyond 256 tiles / groups
+    c.big_groups = false;
     for (int i = 0; i < n; ++i) {
         big_tiles = big_tiles || pl.img[i].ntiles > (uint32_t)kWG;
-        big_groups = big_groups || pl.img[i].ngrp_max > (uint32_t)kWG;
+        c.big_groups = c.big_groups || pl.img[i].ngrp_max > (uint32_t)kWG;
     }
     if (big_tiles) LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
-    switch (variant) {
-        case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
-        case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
-        case 2: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, true>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
-        default: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, true>), pl.seqs, 64u * P.sync_waves, lds_sync); break;
+    switch (c.variant) {
+        case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
+        case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
+        case 2: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, true>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
+        default: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, true>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
     }
+    // Everything is launched in one go, write pass and pixels included: nearly every call is settled by one
+    // inter-sequence round, and the host need not hear from the GPU in between.
+    if ((rc = launch_scan(c)) || (rc = launch_write(c)) || (rc = launch_report(c, c.want_pixels))) return rc;
+    return JPGD_OK;
+}
 
-    uint32_t rounds = 0, redo = 0, flags = 0;
-    const uint32_t max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
-    // The first time everything is launched in one go, write pass and pixels included: nearly every call is settled
-    // by one inter-sequence round, and the host need not hear from the GPU in between.  If it is not settled, the
-    // boundaries are settled first (rounds of the inter-sequence kernel and the totals kernel, which says whether a
-    // boundary is still open; paper: the host repeats the phase until all sequences are synchronised) and the write
-    // pass and the pixels run once more at the end.
-    auto launch_scan = [&]() -> int {
-        if (pl.bnds) {
-            LAUNCH(JPGD_K_SYNC_INTER, k_sync_inter, pl.bnds, 64, lds_inter);
-            ++rounds;
-        }
-        LAUNCH(JPGD_K_SCAN_TOTALS, k_group_totals, pl.grps, kWG, 0);
-        if (big_groups) LAUNCH(JPGD_K_SCAN_PREFIX, k_group_scan, n, kWG, 0);
-        return JPGD_OK;
-    };
-    // pending (out): a sequence whose records were made for another entry state than the one the sequence before it
+// Waits for the verdict of a call and, if the boundaries between sequences are not settled yet, settles them first
+// (rounds of the inter-sequence kernel and the totals kernel, which says whether a boundary is still open; paper: the
+// host repeats the phase until all sequences are synchronised) and runs the write pass and the pixels once more.
+int finish_call(Call& c, jpgd_report* report) {
+    int rc = wait_verdict(c);
+    if (rc) return rc;
+    uint32_t flags = c.verdict[0];
+    // pending: a sequence whose records were made for another entry state than the one the sequence before it
     // now ends in (k_group_totals).  Its states may all be right, so that the write pass finds nothing, while the
     // counts and DC sums of its first records are not.
-    auto launch_report = [&](bool with_pixels, bool& pending) -> int {
-        const uint32_t ticket = ++g_stage.ticket;
-        // The pixel kernel is enqueued before the verdict is known: it only reads coefficients, and if the
-        // verdict is bad its output is either redone or reported as unspecified.  Its first lane passes the
-        // verdict on before anything else; the host waits for the verdict alone, and the pixels are complete
-        // in stream order, like the output of any kernel.  Without pixels a one-lane kernel reports.
-        if (with_pixels) {
-            P.verdict = g_stage.verdict_dev;
-            P.ticket = ticket;
-            LAUNCH(JPGD_K_PIXELS, k_pixels, pl.pixwgs, kWG, 0);
-        } else {
-            hipLaunchKernelGGL(k_verdict, dim3(1), dim3(64), 0, stream, (const Status*)(ws + pl.h.off_status),
-                               (volatile uint32_t*)g_stage.verdict_dev, ticket);
-        }
-        HIP_OK(hipGetLastError());
-        if ((rc = wait_verdict(stream, ticket)) != JPGD_OK) return rc;
-        flags = g_stage.verdict[0];
-        pending = g_stage.verdict[2] != 0u;
-        return JPGD_OK;
-    };
-    auto launch_write = [&]() -> int {
-        if (staged) LAUNCH(JPGD_K_WRITE, k_write<true>, pl.grps, kWG, lds_write);
-        else LAUNCH(JPGD_K_WRITE, k_write<false>, pl.grps, kWG, lds_write);
-        return JPGD_OK;
-    };
-    bool pending = false;
-    if ((rc = launch_scan()) || (rc = launch_write()) || (rc = launch_report(want_pixels, pending))) return rc;
+    bool pending = c.verdict[2] != 0u;
     // A broken chain (a write lane that did not end in the recorded state) with more than one sequence, or an open
     // boundary, means that the boundaries need more rounds; a broken chain with all boundaries settled is a
     // corrupt stream, and no round will mend it.
-    if (pending && pl.bnds && rounds < max_rounds) {
-        while (pending && rounds < max_rounds) {
-            ++redo;
-            HIP_OK(hipMemsetAsync(ws + pl.h.off_status, 0, sizeof(Status), stream));
-            if ((rc = launch_scan()) || (rc = launch_report(false, pending))) return rc;
+    if (pending && c.pl.bnds && c.rounds < c.max_rounds) {
+        while (pending && c.rounds < c.max_rounds) {
+            ++c.redo;
+            hipLaunchKernelGGL(k_clear_status, dim3(1), dim3(64), 0, c.stream, (Status*)(c.ws + c.pl.h.off_status));
+            if ((rc = launch_scan(c)) || (rc = launch_report(c, false)) || (rc = wait_verdict(c))) return rc;
+            pending = c.verdict[2] != 0u;
         }
         const bool open = pending;
-        if ((rc = launch_write()) || (rc = launch_report(want_pixels, pending))) return rc;
+        if ((rc = launch_write(c)) || (rc = launch_report(c, c.want_pixels)) || (rc = wait_verdict(c))) return rc;
+        flags = c.verdict[0];
         if (open) flags |= kStMismatch;  // out of rounds: the result is not to be trusted
-    } else if (pending && pl.bnds) {
+    } else if (pending && c.pl.bnds) {
         flags |= kStMismatch;
     }
-#undef LAUNCH
     if (report) {
         memset(report, 0, sizeof *report);
-        report->subseq_bits = pl.L;
-        report->n_subseq = pl.nsub_total;
-        report->n_sequences = pl.seqs;
-        report->inter_rounds = rounds;
-        report->redo = redo;
+        report->subseq_bits = c.pl.L;
+        report->n_subseq = c.pl.nsub_total;
+        report->n_sequences = c.pl.seqs;
+        report->inter_rounds = c.rounds;
+        report->redo = c.redo;
         report->device_flags = flags;
-        for (int k = 0; k < JPGD_N_KERNELS; ++k) report->launches[k] = launches[k];
-        for (const Timed& t : timed) {
+        for (int k = 0; k < JPGD_N_KERNELS; ++k) report->launches[k] = c.launches[k];
+        for (const Timed& t : c.timed) {
             float ms = 0.f;
-            (void)hipEventSynchronize(g_stage.timers[t.ev + 1]);  // the pixel kernel may still be running
-            if (hipEventElapsedTime(&ms, g_stage.timers[t.ev], g_stage.timers[t.ev + 1]) == hipSuccess)
+            (void)hipEventSynchronize(c.timers[t.ev + 1]);  // the pixel kernel may still be running
+            if (hipEventElapsedTime(&ms, c.timers[t.ev], c.timers[t.ev + 1]) == hipSuccess)
                 report->kernel_ms[t.kernel] += ms;
         }
     }
     return flags ? JPGD_E_CORRUPT : JPGD_OK;
+}
+#undef LAUNCH
+
+bool bad_pointers(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets, int16_t* d_coef,
+                  const uint64_t* coef_offsets, uint8_t* d_pixels, const uint64_t* pixel_offsets) {
+    if (!infos || n < 1 || !d_scans || !scan_offsets || !d_coef || !coef_offsets) return true;
+    if (d_pixels && !pixel_offsets) return true;
+    return ((uintptr_t)d_scans & 15u) || ((uintptr_t)d_coef & 15u);
+}
+
+// A call that failed after its first launch: kernels already queued may still read the slot's pinned buffer, so
+// the stream is drained before the slot goes back.
+void abandon_call(Call* c) {
+    if (c->stream || c->launches[JPGD_K_UNSTUFF_COUNT]) (void)hipStreamSynchronize(c->stream);
+    call_release(c);
+}
+
+// ---- device memory for the entry point that allocates nothing ------------------------------------------
+// A workspace of fixed size inside the library's own image, one copy per GPU.  The name is only a handle on the
+// host: the address kernels can use is asked from the runtime, once per device, and kept.
+static __device__ __align__(256) uint8_t scratch[kStaticWsBytes];
+
+struct DeviceSetup {
+    bool ready = false;
+    uint8_t* scratch_ptr = nullptr;  // device address of `scratch` on this device
+    Call* call = nullptr;            // the fixed slot of jpgd_decode_static on this device
+    std::mutex in_use;               // calls through the fixed slot take turns
+};
+DeviceSetup g_dev[kMaxDevices];
+
+}  // namespace
+
+extern "C" size_t jpgd_workspace_bytes(const jpgd_info* infos, int n_images, const jpgd_config* cfg) {
+    Plan pl;
+    if (make_plan(infos, n_images, cfg, pl) != JPGD_OK) return 0;
+    return pl.h.total_bytes;
+}
+
+extern "C" int jpgd_decode_batch_async(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                                       int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
+                                       const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
+                                       const jpgd_config* cfg, void* stream, jpgd_call** call) {
+    if (!call) return JPGD_E_ARG;
+    *call = nullptr;
+    if (bad_pointers(n, infos, d_scans, scan_offsets, d_coef, coef_offsets, d_pixels, pixel_offsets) || !d_workspace)
+        return JPGD_E_ARG;
+    if ((uintptr_t)d_workspace & 255u) return JPGD_E_WORKSPACE;
+    Call* c = nullptr;
+    int rc = call_acquire(&c);
+    if (rc) return rc;
+    c->stream = nullptr;
+    memset(c->launches, 0, sizeof c->launches);
+    rc = enqueue_call(*c, n, infos, d_scans, scan_offsets, d_coef, coef_offsets, d_pixels, pixel_offsets, d_workspace,
+                      workspace_bytes, cfg, (hipStream_t)stream);
+    if (rc) {
+        abandon_call(c);
+        return rc;
+    }
+    *call = c;
+    return JPGD_OK;
+}
+
+extern "C" int jpgd_wait(jpgd_call* call, jpgd_report* report) {
+    if (!call) return JPGD_E_ARG;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        bool known = false;
+        for (Call* c : g_calls) known = known || c == call;
+        if (!known || !call->busy || call->fixed) return JPGD_E_ARG;
+    }
+    const int rc = finish_call(*call, report);
+    if (rc == JPGD_E_HIP) abandon_call(call);
+    else call_release(call);
+    return rc;
+}
+
+extern "C" int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                                 int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
+                                 const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
+                                 const jpgd_config* cfg, void* stream, jpgd_report* report) {
+    jpgd_call* call = nullptr;
+    const int rc = jpgd_decode_batch_async(n, infos, d_scans, scan_offsets, d_coef, coef_offsets, d_pixels, pixel_offsets,
+                                           d_workspace, workspace_bytes, cfg, stream, &call);
+    if (rc) return rc;
+    return jpgd_wait(call, report);
 }
 
 extern "C" int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
@@ -629,6 +807,83 @@ extern "C" int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t
     const uint64_t zero = 0;
     return jpgd_decode_batch(1, info, d_scan, &zero, d_coef, &zero, d_pixels, &zero, d_workspace, workspace_bytes, cfg,
                              stream, report);
+}
+
+extern "C" int jpgd_init(void) {
+    int dev = 0;
+    HIP_OK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return JPGD_E_ARG;
+    DeviceSetup& D = g_dev[dev];
+    std::lock_guard<std::mutex> turn(D.in_use);
+    if (D.ready) return JPGD_OK;
+    uint8_t* ptr = nullptr;
+    HIP_OK(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255u)) return JPGD_E_HIP;
+    Call* c = new Call();
+    c->device = dev;
+    int rc = call_reserve(*c, kStaticStageBytes);
+    if (rc) {
+        delete c;
+        return rc;
+    }
+    c->fixed = true;
+    // Dynamic LDS of the kernels as the fixed-size entry point may need it (one image, any subsequence size): asked for
+    // here, so that the entry point itself changes no attribute of a function.
+    const void* const sync_kernels[4] = {(const void*)k_sync_intra<true, false>, (const void*)k_sync_intra<false, false>,
+                                         (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
+    for (int v = 0; v < 4; ++v)
+        if ((rc = grant_lds(dev, v, sync_kernels[v], lds_sync_bytes(2048u, kMaxSlots, v >= 2)))) break;
+    if (!rc) rc = grant_lds(dev, 4, (const void*)k_write<true>, lds_write_bytes(2048u, kMaxSlots, true));
+    if (!rc) rc = grant_lds(dev, 5, (const void*)k_write<false>, lds_write_bytes(2048u, kMaxSlots, true));
+    if (!rc) rc = grant_lds(dev, 8, (const void*)k_sync_inter, (size_t)kMaxSlots * kLutEntries * 2);
+    if (rc) return rc;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        g_calls.push_back(c);
+    }
+    D.scratch_ptr = ptr;
+    D.call = c;
+    D.ready = true;
+    return JPGD_OK;
+}
+
+extern "C" size_t jpgd_static_workspace_bytes(void) { return kStaticWsBytes; }
+
+extern "C" int jpgd_decode_static(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
+                                  const jpgd_config* cfg, void* stream, jpgd_report* report) {
+    const uint64_t zero = 0;
+    if (bad_pointers(1, info, d_scan, &zero, d_coef, &zero, d_pixels, &zero)) return JPGD_E_ARG;
+    if (cfg && cfg->timing_mask) return JPGD_E_ARG;  // events would have to be created
+    int dev = 0;
+    HIP_OK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return JPGD_E_ARG;
+    DeviceSetup& D = g_dev[dev];
+    std::lock_guard<std::mutex> turn(D.in_use);  // one call at a time: they all use the device's one array
+    if (!D.ready) {
+        fprintf(stderr, "jpgd: jpgd_decode_static needs jpgd_init() on this device first\n");
+        return JPGD_E_ARG;
+    }
+    {
+        // sizes beyond the fixed workspace or the fixed parameter buffer are refused before anything is launched
+        Plan pl;
+        const int rc = make_plan(info, 1, cfg, pl);
+        if (rc) return rc;
+        if (pl.h.total_bytes > kStaticWsBytes || pl.h.upload_bytes + 16 > D.call->cap) {
+            fprintf(stderr, "jpgd: jpgd_decode_static: this image needs %zu bytes of workspace, the built-in one has %zu\n",
+                    (size_t)pl.h.total_bytes, kStaticWsBytes);
+            return JPGD_E_WORKSPACE;
+        }
+    }
+    Call& c = *D.call;
+    c.busy = true;
+    c.stream = nullptr;
+    memset(c.launches, 0, sizeof c.launches);
+    int rc = enqueue_call(c, 1, info, d_scan, &zero, d_coef, &zero, d_pixels, &zero, D.scratch_ptr, kStaticWsBytes, cfg,
+                          (hipStream_t)stream);
+    if (!rc) rc = finish_call(c, report);
+    if (rc != JPGD_OK && rc != JPGD_E_CORRUPT && (c.stream || c.launches[JPGD_K_UNSTUFF_COUNT])) (void)hipStreamSynchronize(c.stream);
+    c.busy = false;
+    return rc;
 }
 
 extern "C" int jpgd_read_sync_info(const void* d_workspace, int image, uint32_t capacity, uint32_t* n_subseq,
@@ -675,10 +930,20 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     const size_t need = up256(off_tiles + (size_t)tiles * 4);
     if (workspace_bytes < need) return JPGD_E_WORKSPACE;
     hipStream_t stream = (hipStream_t)stream_v;
-    std::lock_guard<std::mutex> lock(g_stage.mu);
-    int rc = stage_acquire(off_tiles);
+    Call* c = nullptr;
+    int rc = call_acquire(&c);
     if (rc) return rc;
-    uint8_t* up = g_stage.buf;
+    struct Release {
+        Call* c;
+        hipStream_t s;
+        ~Release() {
+            (void)hipStreamSynchronize(s);
+            call_release(c);
+        }
+    } release{c, stream};
+    rc = call_reserve(*c, off_tiles);
+    if (rc) return rc;
+    uint8_t* up = c->buf;
     memset(up, 0, off_tiles);
     ImgDesc d;
     memset(&d, 0, sizeof d);
@@ -701,8 +966,8 @@ extern "C" int jpgd_unstuff(const uint8_t* d_in, size_t n, uint8_t* d_out, size_
     if (tiles > (uint32_t)kWG) hipLaunchKernelGGL(k_unstuff_scan, dim3(1), dim3(kWG), 0, stream, P);
     hipLaunchKernelGGL(k_unstuff_scatter, dim3(tiles), dim3(kWG), 0, stream, P);
     HIP_OK(hipGetLastError());
-    HIP_OK(hipMemcpyAsync(g_stage.verdict, ws + off_state, sizeof(ImgState), hipMemcpyDeviceToHost, stream));
+    HIP_OK(hipMemcpyAsync(c->verdict, ws + off_state, sizeof(ImgState), hipMemcpyDeviceToHost, stream));
     HIP_OK(hipStreamSynchronize(stream));
-    *out_len = g_stage.verdict[0];
+    *out_len = c->verdict[0];
     return JPGD_OK;
 }

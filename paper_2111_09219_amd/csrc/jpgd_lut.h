@@ -25,12 +25,12 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
     if (k > 256) return false;
     if (is_dc)
         for (uint32_t i = 0; i < k; ++i)
-            if (vals[i] > 15) return false;  // a DC symbol is a number of value bits; 8-bit samples need at most 11
+            if (vals[i] > 11) return false;  // a DC symbol is a number of value bits: 0..11 for 8-bit samples
 
     auto entry_for = [&](uint32_t sym, int len) -> uint16_t {
         uint32_t size, adv;
         if (is_dc) {
-            size = sym;  // at most 15, checked below
+            size = sym;  // at most 11, checked above
             adv = 1;
         } else {
             uint32_t run = sym >> 4;

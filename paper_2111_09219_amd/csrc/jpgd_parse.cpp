@@ -75,9 +75,12 @@ extern "C" int jpgd_parse(const uint8_t* file, size_t len, jpgd_info* out) {
                 unsigned total = 0;
                 for (int i = 0; i < 16; ++i) total += bits[i];
                 if (q + 17 + total > n) return JPGD_E_TRUNCATED;
-                if (cls == 0)  // a DC symbol is a count of value bits: 0..11 for 8-bit samples, 15 at the very most
+                // A DC symbol is a count of value bits, 0..11 for the 8-bit samples of a baseline frame (T.81, F.1.2.1).
+                // Larger counts cannot occur in a valid stream, and the kernels rely on the bound: a difference of
+                // up to 11 bits keeps the per-subsequence DC sums inside their 15-bit fields.
+                if (cls == 0)
                     for (unsigned i = 0; i < total; ++i)
-                        if (seg[q + 17 + i] > 15) return JPGD_E_TABLE;
+                        if (seg[q + 17 + i] > 11) return JPGD_E_TABLE;
                 memcpy(out->dht_bits[cls][id], bits, 16);
                 memset(out->dht_vals[cls][id], 0, 256);
                 memcpy(out->dht_vals[cls][id], seg + q + 17, total);

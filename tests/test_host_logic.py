@@ -106,9 +106,13 @@ def test_parse_rejections():
     # a DHT whose lengths cannot form a prefix code: three codes of length 1
     _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q}, [(0, 0, [3] + [0] * 15, [0, 1, 2]), (1, 0, *ac)],
                         b"\x00"), "TABLE")
-    # a DC table with a symbol that cannot be a number of value bits
-    _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q},
-                        [(0, 0, [0, 2] + [0] * 14, [3, 16]), (1, 0, *ac)], b"\x00"), "TABLE")
+    # a DC table with a symbol that cannot be a number of value bits of an 8-bit sample's difference (0..11): the
+    # sync pass carries the DC sums of a subsequence in 15-bit fields, which 12 or more value bits would overflow
+    for sym in (12, 15, 16):
+        _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q},
+                            [(0, 0, [0, 2] + [0] * 14, [3, sym]), (1, 0, *ac)], b"\x00"), "TABLE")
+    assert J.jpgd_parse(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 0)], {0: q},
+                                    [(0, 0, [0, 2] + [0] * 14, [3, 11]), (1, 0, *ac)], b"\x00")).total_units == 1
     # scan refers to an AC table that was never defined
     _expect(jf.assemble(8, 8, [(1, 1, 1, 0)], [(1, 0, 1)], {0: q}, [(0, 0, *std_dc), (1, 0, *ac)], b"\x00"), "TABLE")
     # 4 components, and chroma sampled 2x2

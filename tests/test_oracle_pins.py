@@ -597,3 +597,126 @@ def test_planes_and_rgb_agree():
     rgb = np.stack([y + 1.402 * cr, y - 0.344136 * cb - 0.714136 * cr, y + 1.772 * cb], -1)
     rgb = np.clip(np.floor(rgb + 0.5), 0, 255)
     assert np.abs(rgb - o.pixels().astype(np.float64)).max() <= 2
+
+
+# ----------------------------------------------------------------------------- reduced-size output
+
+def _corner(rng, n, amp=300.0):
+    F = np.zeros((8, 8))
+    F[:n, :n] = rng.uniform(-amp, amp, size=(n, n))
+    return F
+
+
+@pytest.mark.parametrize("n", [8, 4, 2, 1])
+def test_scaled_idct_is_the_n_point_transform_of_the_low_frequencies(n):
+    """orc_idct_scaled against scipy's orthonormal n-point inverse DCT (type III) of the n x n corner: the
+    orthonormal transform has the factor sqrt(2/n) per dimension where the oracle keeps the 8-point transform's
+    1/2, so the two differ by n/8.  Coefficients outside the corner must not matter, and n = 8 is orc_idct8x8."""
+    from oracle import idct_scaled
+    rng = np.random.default_rng(100 + n)
+    for _ in range(20):
+        F = rng.uniform(-500, 500, size=(8, 8))
+        got = idct_scaled(F, n)
+        want = scipy.fft.idctn(F[:n, :n], type=2, norm="ortho") * (n / 8.0)
+        assert np.allclose(got, want, atol=1e-9)
+        G = F.copy()
+        G[n:, :] = 0.0
+        G[:, n:] = 0.0
+        assert np.array_equal(idct_scaled(G, n), got)
+    assert np.allclose(idct_scaled(F, 8), idct8x8(F), atol=1e-9)
+    # not transposed: a purely horizontal frequency varies along x only
+    if n > 1:
+        H = np.zeros((8, 8)); H[0, 1] = 100.0
+        f = idct_scaled(H, n)
+        assert np.allclose(f, f[0:1, :].repeat(n, axis=0)) and f[0, 0] > 0 > f[0, n - 1]
+
+
+@pytest.mark.parametrize("n", [4, 2, 1])
+def test_scaled_idct_against_box_averages_of_the_full_size_transform(n):
+    """Closed form that ties the reduced sizes to the pinned 8-point transform: the mean of
+    cos((2x+1) u pi/16) over the d = 8/n samples x = d*k .. d*k+d-1 is A(u) cos((2k+1) u pi/(2n)) with
+    A(u) = sin(d u pi/16) / (d sin(u pi/16)), A(0) = 1.  So for a block limited to the n x n corner the
+    d x d box average of the full-size samples equals the n-point output of the block with F(v,u) scaled by
+    A(u) A(v); for n = 1 this is: the single output sample is the mean of the full-size block."""
+    from oracle import idct_scaled
+    d = 8 // n
+    rng = np.random.default_rng(200 + n)
+    k = np.arange(8)
+    A = np.ones(8)
+    A[1:] = np.sin(d * k[1:] * np.pi / 16) / (d * np.sin(k[1:] * np.pi / 16))
+    for _ in range(10):
+        F = _corner(rng, n)
+        full = idct8x8(F)
+        box = full.reshape(n, d, n, d).mean(axis=(1, 3))
+        got = idct_scaled(F * np.outer(A, A), n)
+        assert np.allclose(got, box, atol=1e-9)
+    # a block that is not band-limited: at 1/8 size the output is still the block's mean (all other basis
+    # functions average to zero over the block)
+    F = rng.uniform(-300, 300, size=(8, 8))
+    assert np.allclose(idct_scaled(F, 1)[0, 0], idct8x8(F).mean(), atol=1e-9)
+
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_scaled_output_geometry_and_flat_images(sub):
+    """A flat image stays flat at every size (a DC-only unit keeps its value: DC*Q/8 + 128), the output has
+    ceil(W/d) x ceil(H/d) pixels, and at 1/8 size every pixel is the rounded mean of its block computed from the
+    full-size samples before rounding -- checked on an image whose full-size output is smooth, against the
+    8x8 box average of the full-size oracle output within the rounding of that output (half a level each way)."""
+    ncomp = 1 if sub == "gray" else 3
+    flat = np.full((37, 51, 3), (200, 90, 40), np.uint8) if ncomp == 3 else np.full((37, 51), 117, np.uint8)
+    o = OracleImage(encode_jpeg(flat, 90, sub).data)
+    full = o.pixels()
+    for d in (1, 2, 4, 8):
+        got = o.pixels_scaled(d)
+        assert got.shape[:2] == (-(-37 // d), -(-51 // d))
+        assert (got.reshape(-1, ncomp) == full.reshape(-1, ncomp)[0]).all()
+        planes = o.planes_scaled(d)
+        for c, (pl, ref) in enumerate(zip(planes, o.planes())):
+            assert pl.shape == (-(-ref.shape[0] // d), -(-ref.shape[1] // d))
+            assert (pl == ref[0, 0]).all()
+    assert np.array_equal(o.pixels_scaled(1), full)
+    # 1/8 size = block means: a gray gradient image, full-size planes averaged over 8x8 (exact MCU multiple)
+    px = small_image(5, 64, 96, ncomp=ncomp, sigma=3.0)
+    o = OracleImage(encode_jpeg(px, 95, sub).data)
+    eighth = o.planes_scaled(8)
+    for pl8, ref in zip(eighth, o.planes()):
+        h8, w8 = pl8.shape
+        box = ref[:h8 * 8, :w8 * 8].astype(np.float64).reshape(h8, 8, w8, 8).mean(axis=(1, 3))
+        assert np.abs(pl8.astype(np.float64) - box).max() <= 1.0   # rounding of 64 samples vs rounding of their mean
+    # colour at reduced size: the RGB output equals the colour conversion of the reduced planes (replicated),
+    # within the one rounding the planes add
+    for d in (2, 4, 8):
+        rgb = o.pixels_scaled(d)
+        pls = o.planes_scaled(d)
+        if ncomp == 1:
+            assert np.array_equal(rgb, pls[0])
+            continue
+        vs = 2 if sub == "420" else 1
+        hs = 2 if sub in ("422", "420") else 1
+        Y = pls[0].astype(np.float64)
+        Cb = np.repeat(np.repeat(pls[1], vs, axis=0), hs, axis=1)[:Y.shape[0], :Y.shape[1]].astype(np.float64) - 128
+        Cr = np.repeat(np.repeat(pls[2], vs, axis=0), hs, axis=1)[:Y.shape[0], :Y.shape[1]].astype(np.float64) - 128
+        want = np.stack([Y + 1.402 * Cr, Y - 0.344136 * Cb - 0.714136 * Cr, Y + 1.772 * Cb], axis=-1)
+        assert np.abs(rgb.astype(np.float64) - np.clip(want, 0, 255)).max() <= 2.0
+
+
+def test_scaled_output_against_an_outside_decoder():
+    """libjpeg's reduced-size decoding (Pillow's draft mode).  At 1/8 size both take the DC term alone: the
+    outputs are equal.  At 1/2 and 1/4 the library Pillow links derives its transform from the 8-point one and lets
+    frequencies outside the n x n corner in, so the two definitions only coincide where those frequencies are
+    empty: on a smooth image (gradients, no edges, no noise) they agree within one level, and the sizes always
+    agree.  (On images with sharp edges they differ by up to some twenty levels next to the edges; the n-point
+    definition is the oracle's, recorded as a reading of its own.)"""
+    px = small_image(9, 120, 168, ncomp=1, sigma=0.0, shapes=0)
+    noisy = small_image(9, 120, 168, ncomp=1, sigma=5.0)
+    for img, tol in ((px, {2: 1, 4: 1, 8: 0}), (noisy, {8: 0})):
+        buf = io.BytesIO()
+        Image.fromarray(img).save(buf, "JPEG", quality=92)
+        o = OracleImage(np.frombuffer(buf.getvalue(), np.uint8))
+        for d, t in tol.items():
+            im = Image.open(io.BytesIO(buf.getvalue()))
+            im.draft("L", (168 // d, 120 // d))
+            ref = np.asarray(im)
+            got = o.pixels_scaled(d)
+            assert got.shape == ref.shape
+            assert np.abs(got.astype(np.int16) - ref.astype(np.int16)).max() <= t
