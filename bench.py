@@ -5,14 +5,17 @@ A step is one jpgd_decode_batch call over one synthetic workload: unstuff, synch
 inter), scan, write (with DC), pixels -- inputs already resident in HBM, outputs left in HBM.
 Prints ONE JSON line (see README / DESIGN.md, "Measurement").
 
-  python bench.py                       # benchmark configs[1]: one 1920x1088 4:4:4 q90 image
-  python bench.py --config 5            # other workloads (1..5), for the notes in the design doc
+  python bench.py                       # headline: benchmark configs[4], one 15360x8640 4:2:0 q92 image;
+                                        # the other four configs are timed in the same run ("per_config")
+  python bench.py --config 2            # another workload (1..5) as the headline, no per_config block
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
+import re
 import sys
 import time
 
@@ -23,47 +26,293 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size; taken from the summaries in profiles/ (same commands).
-# Share of the chip's vector issue slots the kernel uses and lanes switched on per vector instruction, from the SQ
-# counters in the same summaries (the entropy kernels are bound by dependent instruction issue, not by HBM).
-MEASURED_ISSUE = {
-    ("hd1088_444_q90", "sync_intra"): {"valu_issue_frac": 0.114, "lanes_per_valu_instr": 41.2},
-    ("uhd16k_420_q92_flat_random", "sync_intra"): {"valu_issue_frac": 0.429, "lanes_per_valu_instr": 40.6},
-}
-
-MEASURED_TRAFFIC = {
-    ("hd1088_444_q90", "sync_intra"): 1.747e6,
-    ("hd1088_444_q90", "write"): 14.65e6,
-    ("hd1088_444_q90", "pixels"): 18.89e6,
-    ("uhd16k_420_q92_flat_random", "sync_intra"): 84.75e6,
-    ("uhd16k_420_q92_flat_random", "write"): 1122.0e6,
-    ("uhd16k_420_q92_flat_random", "pixels"): 796.3e6,
-}
+# rocprofv3 kernel names of the kernels bench.py reports on (prefixes of the names in profiles/*.md)
+PROFILE_NAMES = {"unstuff_count": "jpgd::k_unstuff_count", "unstuff_scan": "jpgd::k_unstuff_scan",
+                 "unstuff_scatter": "jpgd::k_unstuff_scatter", "sync_intra": "jpgd::k_sync_intra",
+                 "sync_inter": "jpgd::k_sync_inter", "scan_totals": "jpgd::k_group_totals",
+                 "scan_prefix": "jpgd::k_group_scan", "write": "jpgd::k_write", "pixels": "jpgd::k_pixels"}
+PROFILE_FILES = {1: "decode_path_gray256_q75.md", 2: "decode_path_hd1088_444_q90.md", 3: "decode_path_4k_420_q95_opt.md",
+                 4: "decode_path_batch256_420.md", 5: "decode_path_uhd16k_420_q92.md"}
 
 
 def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: int) -> int:
-    """Bytes the method itself must move per launch ("Kernels"): Bs stuffed bytes, B unstuffed
-    bytes, S subsequences (16-byte records), K data units (128 bytes of int16 each), out_bytes of pixels."""
+    """Bytes the method itself must move per launch: Bs stuffed bytes, B unstuffed bytes, S subsequences (one
+    packed 8-byte state each: what Algorithm 1's s_info needs; the library's records are 16 bytes because the DC
+    sums of Section 4.2 ride along, which is not counted here), K data units (128 bytes of int16 each), out_bytes
+    of pixels."""
     return {
         "unstuff_count": Bs,
         "unstuff_scan": 8 * (Bs // 4096 + 1),
         "unstuff_scatter": Bs + B,
-        "sync_intra": B + 16 * S,
-        "sync_inter": 16 * (S // 256 + 1),
-        "scan_totals": 16 * S,
+        "sync_intra": B + 8 * S,
+        "sync_inter": 8 * (S // 256 + 1),
+        "scan_totals": 8 * S,
         "scan_prefix": 32 * (S // 256 + 1),
-        "write": B + 16 * S + 128 * K,
+        "write": B + 8 * S + 128 * K,
         "pixels": 128 * K + out_bytes,
     }[kernel]
+
+
+def kernel_sources_sha16() -> str:
+    """Fingerprint of the kernel sources: a profile summary made from other sources is marked stale."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2111_09219_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip", ".cpp")):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def profile_traffic(config: int):
+    """HBM bytes per launch (read + written) of every kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    summary of the same workload in profiles/ (already scaled by what the counters read for a plain copy).  Returns
+    ({kernel: bytes}, stale) or ({}, None) when there is no summary."""
+    path = os.path.join(ROOT, "profiles", PROFILE_FILES.get(config, ""))
+    if not os.path.isfile(path):
+        return {}, None
+    text = open(path).read()
+    m = re.search(r"kernel sources sha256/16: ([0-9a-f]{16})", text)
+    stale = (m.group(1) != kernel_sources_sha16()) if m else True
+    out = {}
+    in_table = False
+    for line in text.splitlines():
+        if line.startswith("| kernel | FETCH_SIZE | WRITE_SIZE |"):
+            in_table = True
+            continue
+        if in_table:
+            if not line.startswith("|"):
+                in_table = False
+                continue
+            cells = [c.strip() for c in line.strip("|").split("|")]
+            if len(cells) == 5 and not cells[0].startswith("-"):
+                for short, prefix in PROFILE_NAMES.items():
+                    if cells[0] == prefix or cells[0].startswith(prefix + "<"):
+                        out[short] = (float(cells[3]) + float(cells[4])) * 1e6
+    return out, stale
+
+
+def load_workload(c: int, args):
+    from workloads import CONFIGS, config_jpeg
+    wl = CONFIGS[c]
+    ri = args.restart_interval
+    if ri < 0:
+        mcu_w = 8 if wl["subsampling"] in ("gray", "444") else 16
+        ri = (wl["width"] + mcu_w - 1) // mcu_w
+    if c == 4:
+        enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri)
+    else:
+        enc = config_jpeg(c, restart_interval=ri, quality=args.quality or None)
+    files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
+    return wl, ri, files
+
+
+def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: bool):
+    """Times `steps` decode calls of workload c after `warmup` untimed ones; per-kernel durations from HIP events
+    in the last warm-up calls."""
+    wl, ri, files = load_workload(c, args)
+    flags = (J.F_PLANAR if args.planar else 0) | {1: 0, 2: J.F_SCALE_2, 4: J.F_SCALE_4, 8: J.F_SCALE_8}[args.scale]
+    ov = None if args.overlap < 0 else args.overlap
+    cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=ov, flags=flags)
+    batch = J.prepare_batch(files, cfg, device="cuda:0")
+    Bs = batch.compressed_bytes
+    K = int(sum(i.total_units for i in batch.infos))
+    d = args.scale
+    if args.planar:   # luma plane plus (ncomp - 1) chroma planes at their own resolution
+        out_bytes = int(sum(-(-i.width // d) * -(-i.height // d) + (i.ncomp - 1) * -(-(-(-i.width // i.hsamp[0])) // d) *
+                            -(-(-(-i.height // i.vsamp[0])) // d) for i in batch.infos))
+    else:
+        out_bytes = int(sum(-(-i.width // d) * -(-i.height // d) * i.ncomp for i in batch.infos))
+
+    # warm-up; its last calls time every kernel
+    cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=ov, flags=flags, timing_mask=(1 << len(J.KERNELS)) - 1)
+    split = np.zeros(len(J.KERNELS))
+    nsplit = max(1, min(5, warmup))
+    nwarm = max(warmup, nsplit + 1)
+    rep = None
+    for w in range(nwarm):
+        if w >= nwarm - nsplit:   # the last warm-up calls: clocks and caches are settled by then
+            rep = batch.decode(cfg=cfg_all)
+            split += np.array(list(rep.kernel_ms)) / np.maximum(1, np.array(list(rep.launches)))
+        else:
+            rep = batch.decode()
+    split /= nsplit
+    dominant = int(np.argmax(split))
+    S = rep.n_subseq
+    B = Bs  # the unstuffed length is within 0.5 % of the stuffed one; the bound is used for the byte counts
+
+    cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=ov, flags=flags, timing_mask=1 << dominant)
+    dom_ms, dom_launches = 0.0, 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        # the dominant kernel is bracketed with HIP events (on the stream the library launches on) in every fourth
+        # step of the timed region: the two event records cost the stream about ten microseconds
+        if bracket_dominant and k % 4 == 0:
+            rep = batch.decode(cfg=cfg_dom)
+            dom_ms += rep.kernel_ms[dominant]
+            dom_launches += rep.launches[dominant]
+        else:
+            rep = batch.decode(cfg=cfg)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / steps
+
+    traffic, stale = profile_traffic(c) if not (args.subseq_bits or ri or args.quality or args.planar or args.scale != 1
+                                                or args.limit or args.overlap >= 0) else ({}, None)
+    kernels = {}
+    for k, name in enumerate(J.KERNELS):
+        if rep.launches[k] == 0:
+            continue
+        ab = algorithmic_bytes(name, Bs, B, S, K, out_bytes)
+        gbs = ab / 1e9 / (split[k] / 1e3) if split[k] > 0 else 0.0
+        kernels[name] = {"ms": round(float(split[k]), 5), "alg_bytes": ab, "achieved_gbs": round(gbs, 2),
+                         "frac": round(gbs / HBM_PEAK_GBS, 5), "traffic": traffic.get(name)}
+    res = {
+        "config": c, "wl": wl, "ri": ri, "files": files, "batch": batch, "rep": rep, "cfg": cfg,
+        "Bs": Bs, "B": B, "S": S, "K": K, "out_bytes": out_bytes, "pixels": batch.pixels_total,
+        "ms_per_step": ms_per_step, "kernels": kernels, "dominant": J.KERNELS[dominant],
+        "dom_avg_ms": dom_ms / max(1, dom_launches), "dom_launches": dom_launches, "traffic_stale": stale,
+        "split_sum_ms": float(split.sum()),
+    }
+    return res
+
+
+def workload_text(r, args) -> str:
+    wl, c = r["wl"], r["config"]
+    return "configs[%d] %s: %d image(s) %dx%d %s q%s%s, %d compressed bytes" % (
+        c - 1, wl["name"], len(r["files"]), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
+        (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % r["ri"] if r["ri"] else "") +
+        (" re-encoded at q%d" % args.quality if args.quality else ""), r["Bs"])
+
+
+def h2d_block(J, torch, r, steps: int):
+    """The job as the paper times it (Section 5: the transfer of the compressed data, and at the far end parsing and
+    allocation, are inside the measured time).  Three settings: the copy in front of every decode on the same
+    stream; two sets of buffers with the copy of the next batch overlapping the decode of this one (the library
+    hands the host back before the verdict: jpgd_decode_batch_async / jpgd_wait); and from the files in host memory."""
+    batch, files, cfg, Bs = r["batch"], r["files"], r["cfg"], r["Bs"]
+    host = batch.d_scans.cpu().pin_memory()
+    for _ in range(3):
+        batch.d_scans.copy_(host, non_blocking=True)
+        batch.decode()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        batch.d_scans.copy_(host, non_blocking=True)
+        batch.decode()
+    torch.cuda.synchronize()
+    ms_h = (time.perf_counter() - t1) * 1e3 / steps
+    out = {"serial_ms_per_step": round(ms_h, 5), "serial_mb_per_s": round(Bs / 1e6 / (ms_h / 1e3), 2)}
+
+    other = J.prepare_batch(files, cfg, device="cuda:0")
+    sets = [batch, other]
+    copy_stream, main = torch.cuda.Stream(), torch.cuda.current_stream()
+    ready = [torch.cuda.Event(), torch.cuda.Event()]
+    done = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def pipelined(n):
+        for k in (0, 1):
+            done[k].record(main)
+        prev = None
+        for i in range(n):
+            k = i & 1
+            with torch.cuda.stream(copy_stream):
+                copy_stream.wait_event(done[k])          # the set's previous decode has finished reading
+                sets[k].d_scans.copy_(host, non_blocking=True)
+                ready[k].record(copy_stream)
+            main.wait_event(ready[k])
+            call = sets[k].decode_async()
+            done[k].record(main)
+            if prev is not None:
+                J.jpgd_wait(prev)                        # the previous batch, while this one is already queued
+            prev = call
+        J.jpgd_wait(prev)
+        torch.cuda.synchronize()
+
+    pipelined(6)
+    t2 = time.perf_counter()
+    pipelined(steps)
+    ms_o = (time.perf_counter() - t2) * 1e3 / steps
+    out["overlapped_ms_per_step"] = round(ms_o, 5)
+    out["overlapped_mb_per_s"] = round(Bs / 1e6 / (ms_o / 1e3), 2)
+    del other, sets
+    # from the files: header parsing and packing of the entropy-coded segments on the host, tensors from torch's
+    # caching allocator (after the first step an allocation is a look-up), copy from pageable memory, decode
+    n_files = max(3, min(steps, 20))
+    for _ in range(2):
+        J.prepare_batch(files, cfg, device="cuda:0").decode()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(n_files):
+        J.prepare_batch(files, cfg, device="cuda:0").decode()
+    torch.cuda.synchronize()
+    ms_f = (time.perf_counter() - t3) * 1e3 / n_files
+    out["from_files_ms_per_step"] = round(ms_f, 5)
+    out["from_files_mb_per_s"] = round(Bs / 1e6 / (ms_f / 1e3), 2)
+    out["note"] = ("serial: pinned copy then decode on one stream; overlapped: two buffer sets, next copy on a second stream, "
+                   "calls enqueued with jpgd_decode_batch_async; from_files: parse + allocate + pageable copy + decode")
+    return out
+
+
+def _oracle_one(data):
+    """Worker of the all-core leg: full decode of one file by the oracle; returns (stuffed bytes, pixels)."""
+    from oracle import OracleImage
+    o = OracleImage(data)
+    coef = o.coefficients()
+    o.pixels(coef)
+    return int(o.info.scan_len), o.width * o.height
+
+
+def cpu_baseline(r, seconds: float, batch_files):
+    """The oracle as it stands on the host's cores: whole decodes of the headline workload's file(s) on one core for
+    about `seconds` (entropy decode and pixels timed apart), and, if the batch workload's files are at hand, its
+    256 images spread over all cores."""
+    from oracle import OracleImage
+    files = r["files"]
+    t_start = time.perf_counter()
+    done_bytes = done_pixels = reps = 0
+    t_entropy = 0.0
+    imgs = files if len(files) > 1 else files * 1000
+    for f in imgs:
+        o = OracleImage(f)
+        t0 = time.perf_counter()
+        coef = o.coefficients()
+        t_entropy += time.perf_counter() - t0
+        o.pixels(coef)
+        done_bytes += int(o.info.scan_len)
+        done_pixels += o.width * o.height
+        reps += 1
+        if time.perf_counter() - t_start > seconds:
+            break
+    cpu_dt = time.perf_counter() - t_start
+    cpu = {"value": round(done_bytes / 1e6 / cpu_dt, 3), "unit": "MB/s", "cores": 1, "kind": "oracle",
+           "mpixel_per_s": round(done_pixels / 1e6 / cpu_dt, 3),
+           "entropy_only_mb_per_s": round(done_bytes / 1e6 / t_entropy, 3) if t_entropy > 0 else None,
+           "sample": "%d full decode(s) (sequential entropy decode + double-precision pixels) of the headline "
+                     "workload's file(s), %.1f s, single thread" % (reps, cpu_dt)}
+    if batch_files:
+        import multiprocessing as mp
+        cores = max(1, min(16, len(os.sched_getaffinity(0))))
+        sample = batch_files[:max(cores, min(len(batch_files), 256))]
+        with mp.get_context("spawn").Pool(cores) as pool:
+            pool.map(_oracle_one, sample[:cores])        # start-up of the workers is not part of the time
+            t0 = time.perf_counter()
+            got = pool.map(_oracle_one, sample, chunksize=max(1, len(sample) // (4 * cores)))
+            dt = time.perf_counter() - t0
+        cpu["batch_all_cores"] = {"value": round(sum(g[0] for g in got) / 1e6 / dt, 3), "unit": "MB/s", "cores": cores,
+                                  "mpixel_per_s": round(sum(g[1] for g in got) / 1e6 / dt, 3),
+                                  "sample": "configs[3]: %d of its 256 images, one image per task, %.1f s" % (len(sample), dt)}
+    return cpu
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 of BASELINE.json (default 2 = configs[1])")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=0,
+                    help="workload 1..5 of BASELINE.json as the headline; 0 (default) = configs[4], the largest, with "
+                         "the other four timed beside it")
     ap.add_argument("--subseq-bits", type=int, default=0)
     ap.add_argument("--overlap", type=int, default=-1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing; 0 skips it")
@@ -75,9 +324,9 @@ def main() -> int:
                     help="encode the (single-image) workload at this quality instead of the configuration's")
     ap.add_argument("--planar", action="store_true",
                     help="component planes instead of RGB (JPGD_F_PLANAR): the paper's own output format")
-    ap.add_argument("--include-h2d", action="store_true",
-                    help="also time steps that first copy the compressed bytes from pinned host memory (reported as "
-                         "'with_h2d'; never as 'value')")
+    ap.add_argument("--scale", type=int, default=1, choices=[1, 2, 4, 8],
+                    help="pixels at 1/N of the size (JPGD_F_SCALE_N)")
+    ap.add_argument("--no-h2d", action="store_true", help="skip the timings that include the host-to-device copy")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of decoding, run plain device copies of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -88,7 +337,6 @@ def main() -> int:
 
     import torch
     import paper_2111_09219_amd as J
-    from workloads import CONFIGS, config_jpeg
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the decoder has no CPU path", file=sys.stderr)
         return 2
@@ -107,164 +355,39 @@ def main() -> int:
         print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "copies": 5, "gbs": round(2 * n / 1e9 / dt, 1)}))
         return 0
 
-    c = args.config
-    wl = CONFIGS[c]
-    ri = args.restart_interval
-    if ri < 0:
-        mcu_w = 8 if wl["subsampling"] in ("gray", "444") else 16
-        ri = (wl["width"] + mcu_w - 1) // mcu_w
-    enc = config_jpeg(c, limit=args.limit or None, restart_interval=ri) if c == 4 else config_jpeg(c, restart_interval=ri, quality=args.quality or None)
-    files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
-    flags = J.F_PLANAR if args.planar else 0
-    cfg = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap, flags=flags)
-    batch = J.prepare_batch(files, cfg, device="cuda:0")
-    Bs = batch.compressed_bytes
-    pixels = batch.pixels_total
-    K = int(sum(i.total_units for i in batch.infos))
-    if args.planar:   # luma plane plus (ncomp - 1) chroma planes at their own resolution
-        out_bytes = int(sum(i.width * i.height + (i.ncomp - 1) * (-(-i.width // i.hsamp[0])) * (-(-i.height // i.vsamp[0]))
-                            for i in batch.infos))
-    else:
-        out_bytes = int(sum(i.width * i.height * i.ncomp for i in batch.infos))
+    everything = args.config == 0
+    head_c = 5 if everything else args.config
+    r = measure(J, torch, head_c, args, args.steps, args.warmup, bracket_dominant=True)
+    rep = r["rep"]
+    mbps = r["Bs"] / 1e6 / (r["ms_per_step"] / 1e3)
+    mpix = r["pixels"] / 1e6 / (r["ms_per_step"] / 1e3)
+    dom = r["dominant"]
+    alg = r["kernels"][dom]["alg_bytes"]
+    achieved = alg / 1e9 / (r["dom_avg_ms"] / 1e3) if r["dom_avg_ms"] > 0 else 0.0
 
-    # warm-up; its last steps time every kernel to find the dominant one
-    cfg_all = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            flags=flags, timing_mask=(1 << len(J.KERNELS)) - 1)
-    split = np.zeros(len(J.KERNELS))
-    nsplit = max(1, min(5, args.warmup))
-    rep = None
-    nwarm = max(args.warmup, nsplit + 1)
-    for w in range(nwarm):
-        if w >= nwarm - nsplit:   # the last warm-up steps: clocks and caches are settled by then
-            rep = batch.decode(cfg=cfg_all)
-            split += np.array(list(rep.kernel_ms))
-        else:
-            rep = batch.decode()
-    split /= nsplit
-    dominant = int(np.argmax(split))
-    S = rep.n_subseq
-    B = Bs  # unstuffed length is within 0.5 % of the stuffed one; the bound is used for the byte counts
+    with_h2d = None if args.no_h2d else h2d_block(J, torch, r, max(10, min(args.steps, 50)))
 
-    cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=None if args.overlap < 0 else args.overlap,
-                            flags=flags, timing_mask=1 << dominant)
-    dom_ms = 0.0
-    dom_launches = 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        # the dominant kernel is bracketed with HIP events in every fourth step of the timed region: the two
-        # event records cost the stream about ten microseconds, which is several percent of a small decode
-        if k % 4 == 0:
-            rep = batch.decode(cfg=cfg_dom)
-            dom_ms += rep.kernel_ms[dominant]
-            dom_launches += rep.launches[dominant]
-        else:
-            rep = batch.decode(cfg=cfg)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    mbps = Bs / 1e6 / (ms_per_step / 1e3)
-    mpix = pixels / 1e6 / (ms_per_step / 1e3)
+    per_config = None
+    batch_files = None
+    if everything:
+        per_config = {}
+        for c in (1, 2, 3, 4):
+            q = measure(J, torch, c, args, max(20, min(args.steps, 100)), max(6, min(args.warmup, 10)), bracket_dominant=False)
+            per_config["configs[%d]" % (c - 1)] = {
+                "workload": workload_text(q, args), "ms_per_step": round(q["ms_per_step"], 5),
+                "mb_per_s": round(q["Bs"] / 1e6 / (q["ms_per_step"] / 1e3), 2),
+                "mpixel_per_s": round(q["pixels"] / 1e6 / (q["ms_per_step"] / 1e3), 2),
+                "subseq_bits": q["rep"].subseq_bits, "subsequences": q["S"], "sequences": q["rep"].n_sequences,
+                "inter_rounds": q["rep"].inter_rounds, "redo": q["rep"].redo, "kernels": q["kernels"],
+                "traffic_stale": q["traffic_stale"]}
+            if c == 4:
+                batch_files = q["files"]
+            del q
+            torch.cuda.empty_cache()
+    elif head_c == 4:
+        batch_files = r["files"]
 
-    with_h2d = None
-    if args.include_h2d:
-        host = batch.d_scans.cpu().pin_memory()
-        for _ in range(5):
-            batch.d_scans.copy_(host, non_blocking=True)
-            batch.decode()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            batch.d_scans.copy_(host, non_blocking=True)
-            batch.decode()
-        torch.cuda.synchronize()
-        ms_h = (time.perf_counter() - t1) * 1e3 / args.steps
-        with_h2d = {"ms_per_step": round(ms_h, 5), "mb_per_s": round(Bs / 1e6 / (ms_h / 1e3), 2),
-                    "note": "each step copies the compressed bytes from pinned host memory on the same stream first"}
-        # the same with two sets of buffers: while one batch is decoded, the next one's bytes are copied on a
-        # second stream (the decode call holds the host until its verdict, so the copy is enqueued before it)
-        other = J.prepare_batch(files, cfg, device="cuda:0")
-        sets = [batch, other]
-        copy_stream = torch.cuda.Stream()
-        ready = [torch.cuda.Event(), torch.cuda.Event()]
-        done = [torch.cuda.Event(), torch.cuda.Event()]
-        main = torch.cuda.current_stream()
-
-        def enqueue_copy(k):
-            with torch.cuda.stream(copy_stream):
-                copy_stream.wait_event(done[k])          # the set's previous decode has finished reading
-                sets[k].d_scans.copy_(host, non_blocking=True)
-                ready[k].record(copy_stream)
-
-        def pipelined(steps):
-            for k in (0, 1):
-                done[k].record(main)
-            enqueue_copy(0)
-            for i in range(steps):
-                k = i & 1
-                enqueue_copy(k ^ 1)
-                main.wait_event(ready[k])
-                sets[k].decode()
-                done[k].record(main)
-            torch.cuda.synchronize()
-
-        pipelined(6)
-        t2 = time.perf_counter()
-        pipelined(args.steps)
-        ms_o = (time.perf_counter() - t2) * 1e3 / args.steps
-        with_h2d["overlapped_ms_per_step"] = round(ms_o, 5)
-        with_h2d["overlapped_mb_per_s"] = round(Bs / 1e6 / (ms_o / 1e3), 2)
-        # from the files, as the paper times it (Section 5: parsing, allocation and transfer included): header
-        # parsing and packing of the entropy-coded segments on the host, tensors from torch's caching allocator
-        # (after the first step an allocation is a look-up), copy from pageable memory, decode
-        del other, sets
-        n_files = max(3, min(args.steps, 30))
-        for _ in range(2):
-            J.prepare_batch(files, cfg, device="cuda:0").decode()
-        torch.cuda.synchronize()
-        t3 = time.perf_counter()
-        for _ in range(n_files):
-            J.prepare_batch(files, cfg, device="cuda:0").decode()
-        torch.cuda.synchronize()
-        ms_f = (time.perf_counter() - t3) * 1e3 / n_files
-        with_h2d["from_files_ms_per_step"] = round(ms_f, 5)
-        with_h2d["from_files_mb_per_s"] = round(Bs / 1e6 / (ms_f / 1e3), 2)
-
-    dom_name = J.KERNELS[dominant]
-    dom_avg_ms = dom_ms / max(1, dom_launches)
-    alg = algorithmic_bytes(dom_name, Bs, B, S, K, out_bytes)
-    achieved = alg / 1e9 / (dom_avg_ms / 1e3) if dom_avg_ms > 0 else 0.0
-
-    kernels = {}
-    for k, name in enumerate(J.KERNELS):
-        if rep.launches[k] == 0:
-            continue
-        ab = algorithmic_bytes(name, Bs, B, S, K, out_bytes)
-        kernels[name] = {"ms": round(float(split[k]), 5), "alg_bytes": ab,
-                         "hbm_gbs": round(ab / 1e9 / (split[k] / 1e3), 2) if split[k] > 0 else None}
-
-    cpu = None
-    if args.cpu_seconds > 0:
-        from oracle import OracleImage
-        t_start = time.perf_counter()
-        done_bytes = 0
-        done_pixels = 0
-        reps = 0
-        imgs = files if len(files) > 1 else files * 1000
-        for f in imgs:
-            o = OracleImage(f)
-            coef = o.coefficients()
-            o.pixels(coef)
-            done_bytes += int(o.info.scan_len)
-            done_pixels += o.width * o.height
-            reps += 1
-            if time.perf_counter() - t_start > args.cpu_seconds:
-                break
-        cpu_dt = time.perf_counter() - t_start
-        cpu = {"value": round(done_bytes / 1e6 / cpu_dt, 3), "unit": "MB/s", "cores": 1, "kind": "oracle",
-               "mpixel_per_s": round(done_pixels / 1e6 / cpu_dt, 3),
-               "sample": "%d full decode(s) (entropy decode + double-precision pixels) of the same file(s), %.1f s, "
-                         "single thread" % (reps, cpu_dt)}
+    cpu = cpu_baseline(r, args.cpu_seconds, batch_files) if args.cpu_seconds > 0 else None
 
     line = {
         "metric": "compressed MB/s per image (whole decode path, data resident in HBM)",
@@ -274,26 +397,28 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": round(r["ms_per_step"], 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "int32 bit-parsing + fp32 IDCT (int16 coefficients, u8 pixels)",
         "data": "synthetic",
-        "config": {"workload": "configs[%d] %s: %d image(s) %dx%d %s q%s%s, %d compressed bytes" % (
-            c - 1, wl["name"], len(files), wl["width"], wl["height"], wl["subsampling"], wl["quality"],
-            (" optimized Huffman" if wl["optimize"] else "") + (" restart interval %d MCUs" % ri if ri else "") + (" re-encoded at q%d" % args.quality if args.quality else ""), Bs),
-            "subseq_bits": rep.subseq_bits, "subsequences": S, "sequences": rep.n_sequences,
-            "inter_rounds": rep.inter_rounds, "redo": rep.redo, "output": "planes" if args.planar else "rgb"},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+        "config": {"workload": workload_text(r, args),
+                   "subseq_bits": rep.subseq_bits, "subsequences": r["S"], "sequences": rep.n_sequences,
+                   "inter_rounds": rep.inter_rounds, "redo": rep.redo,
+                   "output": ("planes" if args.planar else "rgb") + ("" if args.scale == 1 else " at 1/%d size" % args.scale)},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                     "traffic": MEASURED_TRAFFIC.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,
-                     "issue": MEASURED_ISSUE.get((wl["name"], dom_name)) if not (args.subseq_bits or ri or args.quality) else None,
-                     "avg_launch_ms": round(dom_avg_ms, 5), "timed_launches": dom_launches,
-                     "alg_bytes_per_launch": alg},
+                     "traffic": r["kernels"][dom]["traffic"], "traffic_stale": r["traffic_stale"],
+                     "avg_launch_ms": round(r["dom_avg_ms"], 5), "timed_launches": r["dom_launches"],
+                     "alg_bytes_per_launch": alg,
+                     "note": "the entropy kernels are bound by dependent instruction issue, not by HBM: see kernels{} "
+                             "for every kernel's fraction and profiles/ for the SQ counters"},
         "cpu_baseline": cpu,
-        "kernels": kernels,
+        "kernels": r["kernels"],
+        "kernel_sources_sha16": kernel_sources_sha16(),
         "with_h2d": with_h2d,
+        "per_config": per_config,
     }
     print(json.dumps(line))
     return 0

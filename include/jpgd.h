@@ -46,7 +46,8 @@ typedef enum {
     JPGD_E_TABLE = -5,       /* missing or malformed Huffman / quantisation table             */
     JPGD_E_CORRUPT = -6,     /* entropy-coded data inconsistent with the headers              */
     JPGD_E_WORKSPACE = -7,   /* workspace too small or misaligned                             */
-    JPGD_E_HIP = -8          /* a HIP runtime call failed                                     */
+    JPGD_E_HIP = -8,         /* a HIP runtime call failed                                     */
+    JPGD_E_BUSY = -9         /* too many calls in flight (jpgd_decode_batch_async without jpgd_wait) */
 } jpgd_status;
 
 /*
@@ -81,7 +82,7 @@ typedef struct {
                               must be < 192; 0xFFFFFFFF = library default (16 or 32)               */
     uint32_t max_rounds;   /* upper bound on inter-sequence synchronisation rounds; 0 = number of
                               sequences (always enough)                                             */
-    uint32_t flags;        /* JPGD_F_* */
+    uint32_t flags;        /* JPGD_F_*: at most one of the JPGD_F_SCALE_* */
     uint32_t timing_mask;  /* bit k set: bracket kernel k (JPGD_K_*) with HIP events on the stream
                               and report its duration; 0 = no events                               */
 } jpgd_config;
@@ -93,6 +94,16 @@ typedef struct {
                                3 components, Cb and Cr, each ceil(height / v) x ceil(width / h) for luma sampling
                                factors h x v; samples rounded once and clamped, no upsampling, no colour
                                conversion.  The planes never take more than height x width x ncomp bytes. */
+
+#define JPGD_F_SCALE_2 4u   /* d_pixels receives the image at 1/2 of its size: ceil(width / 2) x ceil(height / 2) pixels
+                               (with JPGD_F_PLANAR: every plane at ceil(plane size / 2)).  Of every data unit the 4 x 4
+                               lowest frequencies go through the 4-point inverse transform of the same family as the
+                               8-point one of Section 4.3 (same factor, so a flat unit keeps its value); all later
+                               steps as at full size.  The coefficients are always delivered in full.  For callers
+                               that want a smaller image than the file holds: the paper names the inverse transform
+                               as the stage that limits its decoder (Section 6), and this output skips most of it. */
+#define JPGD_F_SCALE_4 8u   /* the same at 1/4: 2 x 2 lowest frequencies, 2-point transform */
+#define JPGD_F_SCALE_8 12u  /* the same at 1/8: one sample per data unit, DC * Q / 8 + 128 */
 
 /* kernels of the pipeline, in launch order */
 enum {
@@ -143,7 +154,9 @@ int jpgd_parse(const uint8_t* file /*[host]*/, size_t len, jpgd_info* out /*[hos
 
 /*
  * Bytes of device workspace jpgd_decode_batch needs for these images and this
- * config (0 on bad arguments).  The workspace must be 256-byte aligned.  Its
+ * config (0 on bad arguments): the unstuffed streams, s_info with one record per
+ * subsequence (paper, Section 4.1; Algorithm 1 allocates it per call), the
+ * tables and the partial results of the scans.  The workspace must be 256-byte aligned.  Its
  * contents need not be preserved between calls and may be uninitialised.
  */
 size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, const jpgd_config* cfg /*[host], may be NULL*/);
@@ -166,7 +179,7 @@ size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, con
  *  coef_offsets   [host]
  *  d_pixels       [device] uint8 output or NULL: image i at byte offset pixel_offsets[i],
  *                          height x width x ncomp interleaved (gray or RGB), cropped to the
- *                          true size
+ *                          true size (other layouts and sizes: JPGD_F_PLANAR, JPGD_F_SCALE_*)
  *  pixel_offsets  [host]   may be NULL iff d_pixels is NULL
  *  d_workspace    [device] jpgd_workspace_bytes(...) bytes, 256-byte aligned
  *  cfg            [host]   may be NULL for defaults
@@ -180,7 +193,9 @@ size_t jpgd_workspace_bytes(const jpgd_info* infos /*[host]*/, int n_images, con
  * that point d_coef is complete; the kernel that fills d_pixels may still be
  * running, so d_pixels is complete in stream order like the output of any
  * kernel: work enqueued on `stream` afterwards sees it, a host that reads it
- * synchronises the stream first.  Calls are serialised inside the library.
+ * synchronises the stream first.  Calls from several threads, or several calls
+ * in flight (jpgd_decode_batch_async), do not wait for each other inside the
+ * library; each needs a workspace and outputs of its own.
  * On JPGD_E_CORRUPT the outputs hold unspecified values but nothing outside
  * them has been written.
  *
@@ -194,10 +209,59 @@ int jpgd_decode_batch(int n, const jpgd_info* infos, const uint8_t* d_scans, con
                       const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
                       const jpgd_config* cfg, void* stream, jpgd_report* report);
 
+/*
+ * The same call in two halves, for the end-to-end setting the paper times (Section 5, experimental setup:
+ * the transfer of the compressed data is part of the measured time, so a decoder that is fed batch after batch
+ * has to overlap the copy of the next batch with the decoding of this one).
+ *
+ * jpgd_decode_batch_async validates, builds the per-call tables and enqueues every kernel of the path on
+ * `stream`, then returns without waiting for the GPU; *call receives a handle.  infos and the offset arrays may be
+ * freed as soon as it returns; the device buffers and the workspace belong to the call until jpgd_wait returns.
+ * Several calls may be in flight at once, on the same stream or on different ones (at most 64: JPGD_E_BUSY),
+ * each with its own workspace and outputs.
+ *
+ * jpgd_wait blocks until the call's verdict has arrived, runs the further synchronisation rounds in the rare case
+ * that they are needed (it may therefore enqueue more work on the call's stream), fills *report (may be NULL)
+ * and releases the handle, whatever it returns.  Its return value is that of jpgd_decode_batch.  Every handle
+ * must be waited for exactly once, by any thread.
+ * jpgd_decode_batch is the one followed by the other.
+ */
+typedef struct jpgd_call jpgd_call;
+int jpgd_decode_batch_async(int n, const jpgd_info* infos, const uint8_t* d_scans, const uint64_t* scan_offsets,
+                            int16_t* d_coef, const uint64_t* coef_offsets, uint8_t* d_pixels,
+                            const uint64_t* pixel_offsets, void* d_workspace, size_t workspace_bytes,
+                            const jpgd_config* cfg, void* stream, jpgd_call** call /*[host]*/);
+int jpgd_wait(jpgd_call* call, jpgd_report* report /*[host], may be NULL*/);
+
 /* One image: jpgd_decode_batch with n = 1 and all offsets 0. */
 int jpgd_decode(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
                 void* d_workspace, size_t workspace_bytes, const jpgd_config* cfg, void* stream,
                 jpgd_report* report);
+
+/*
+ * For callers that cannot allocate: code between hipStreamBeginCapture and hipStreamEndCapture, serving loops
+ * with a fixed memory budget, harnesses that forbid hipMalloc.  jpgd_decode_static is jpgd_decode without the
+ * workspace argument: the workspace is an array of JPGD_STATIC_WORKSPACE_BYTES inside the library's device image
+ * (every GPU the library runs on holds one copy until the process ends), and the pinned parameter block was set
+ * up by jpgd_init.  It calls no hipMalloc, hipHostMalloc, hipFree or any other allocating routine, creates no
+ * events and changes no function attribute.
+ *
+ * jpgd_init: once per device, with that device current, before the first jpgd_decode_static there (calling it
+ * again is harmless).  It looks up the array's device address, allocates the pinned parameter and verdict blocks
+ * of the fixed slot and asks for the kernels' dynamic LDS.  Not needed by the other entry points.
+ *
+ * jpgd_decode_static: arguments as jpgd_decode.  JPGD_E_WORKSPACE if the image needs more workspace than the
+ * array holds (jpgd_workspace_bytes(info, 1, cfg) > JPGD_STATIC_WORKSPACE_BYTES: roughly, scans beyond 1.8 MB),
+ * JPGD_E_ARG if jpgd_init has not run on the current device or cfg->timing_mask is not 0.  Results are those of
+ * jpgd_decode.  All calls on one GPU share that GPU's array and the library lets them take turns: a second call
+ * blocks until the first has returned; the array keeps the last call's contents, and nothing in it has to be
+ * cleared by the caller.  Like jpgd_decode it returns when the verdict has arrived.
+ */
+#define JPGD_STATIC_WORKSPACE_BYTES (4u << 20)
+int jpgd_init(void);
+size_t jpgd_static_workspace_bytes(void);
+int jpgd_decode_static(const jpgd_info* info, const uint8_t* d_scan, int16_t* d_coef, uint8_t* d_pixels,
+                       const jpgd_config* cfg, void* stream, jpgd_report* report);
 
 /*
  * Stage-level entry points (used by the tests to check single steps against the oracle).
@@ -214,7 +278,8 @@ int jpgd_unstuff(const uint8_t* d_in /*[device]*/, size_t n, uint8_t* d_out /*[d
                  void* d_workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Copies the synchronisation result of the most recent decode call that used
+ * Copies the synchronisation result (paper, Section 4.1: the array s_info once
+ * Algorithm 3 has run) of the most recent decode call that used
  * this workspace to the host: for image `image`, subsequence i < *n_subseq,
  *   p[i]      bit position (unstuffed stream) of the first symbol starting at or after (i+1)*subseq_bits
  *   u[i],z[i] data unit inside the MCU and zig-zag index at that point

@@ -17,10 +17,19 @@ from . import build as _build
 _lib = None
 
 STATUS = {0: "OK", -1: "ARG", -2: "TRUNCATED", -3: "MARKER", -4: "UNSUPPORTED", -5: "TABLE", -6: "CORRUPT",
-          -7: "WORKSPACE", -8: "HIP"}
+          -7: "WORKSPACE", -8: "HIP", -9: "BUSY"}
 
 F_NO_PIXELS = 1
 F_PLANAR = 2
+F_SCALE_2 = 4
+F_SCALE_4 = 8
+F_SCALE_8 = 12
+STATIC_WORKSPACE_BYTES = 4 << 20
+
+
+def scale_denominator(flags: int) -> int:
+    """1, 2, 4 or 8: the JPGD_F_SCALE_* part of a flags word."""
+    return 1 << ((flags >> 2) & 3)
 
 
 class JpgdError(RuntimeError):
@@ -75,7 +84,8 @@ class Report(ctypes.Structure):
         return d
 
 
-EXPORTS = ["jpgd_parse", "jpgd_workspace_bytes", "jpgd_decode_batch", "jpgd_decode", "jpgd_unstuff",
+EXPORTS = ["jpgd_parse", "jpgd_workspace_bytes", "jpgd_decode_batch", "jpgd_decode_batch_async", "jpgd_wait",
+           "jpgd_decode", "jpgd_init", "jpgd_static_workspace_bytes", "jpgd_decode_static", "jpgd_unstuff",
            "jpgd_read_sync_info", "jpgd_strerror", "jpgd_abi_version"]
 
 
@@ -100,9 +110,20 @@ def _load():
     lib.jpgd_decode_batch.argtypes = [ctypes.c_int, ctypes.POINTER(Info), vp, u64p, vp, u64p, vp, u64p, vp,
                                       ctypes.c_size_t, ctypes.POINTER(Config), vp, ctypes.POINTER(Report)]
     lib.jpgd_decode_batch.restype = ctypes.c_int
+    lib.jpgd_decode_batch_async.argtypes = [ctypes.c_int, ctypes.POINTER(Info), vp, u64p, vp, u64p, vp, u64p, vp,
+                                            ctypes.c_size_t, ctypes.POINTER(Config), vp, ctypes.POINTER(vp)]
+    lib.jpgd_decode_batch_async.restype = ctypes.c_int
+    lib.jpgd_wait.argtypes = [vp, ctypes.POINTER(Report)]
+    lib.jpgd_wait.restype = ctypes.c_int
     lib.jpgd_decode.argtypes = [ctypes.POINTER(Info), vp, vp, vp, vp, ctypes.c_size_t, ctypes.POINTER(Config), vp,
                                 ctypes.POINTER(Report)]
     lib.jpgd_decode.restype = ctypes.c_int
+    lib.jpgd_init.argtypes = []
+    lib.jpgd_init.restype = ctypes.c_int
+    lib.jpgd_static_workspace_bytes.argtypes = []
+    lib.jpgd_static_workspace_bytes.restype = ctypes.c_size_t
+    lib.jpgd_decode_static.argtypes = [ctypes.POINTER(Info), vp, vp, vp, ctypes.POINTER(Config), vp, ctypes.POINTER(Report)]
+    lib.jpgd_decode_static.restype = ctypes.c_int
     lib.jpgd_unstuff.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_size_t), vp, ctypes.c_size_t, vp]
     lib.jpgd_unstuff.restype = ctypes.c_int
     lib.jpgd_read_sync_info.argtypes = [vp, ctypes.c_int, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32), vp, vp, vp,
@@ -203,6 +224,66 @@ def jpgd_decode(info, d_scan, d_coef, d_pixels, d_workspace, cfg: Config | None 
     return rep
 
 
+def jpgd_decode_batch_async(infos, d_scans, scan_offsets, d_coef, coef_offsets, d_pixels, pixel_offsets, d_workspace,
+                            cfg: Config | None = None, stream=None):
+    """See include/jpgd.h: enqueues the call and returns its handle without waiting for the GPU."""
+    lib = _load()
+    n = len(infos)
+    _require_cuda(d_scans, "d_scans")
+    _require_cuda(d_coef, "d_coef")
+    _require_cuda(d_workspace, "d_workspace")
+    if d_pixels is not None:
+        _require_cuda(d_pixels, "d_pixels")
+    so = (ctypes.c_uint64 * n)(*[int(v) for v in scan_offsets])
+    co = (ctypes.c_uint64 * n)(*[int(v) for v in coef_offsets])
+    po = (ctypes.c_uint64 * n)(*[int(v) for v in pixel_offsets]) if d_pixels is not None else None
+    call = ctypes.c_void_p()
+    _check(lib.jpgd_decode_batch_async(n, _info_array(infos), d_scans.data_ptr(), so, d_coef.data_ptr(), co,
+                                       d_pixels.data_ptr() if d_pixels is not None else None, po, d_workspace.data_ptr(),
+                                       d_workspace.numel() * d_workspace.element_size(),
+                                       ctypes.byref(cfg) if cfg is not None else None, _stream_handle(stream),
+                                       ctypes.byref(call)), "jpgd_decode_batch_async")
+    return call
+
+
+def jpgd_wait(call) -> Report:
+    """Waits for a call started with jpgd_decode_batch_async; returns its report."""
+    rep = Report()
+    rc = _load().jpgd_wait(call, ctypes.byref(rep))
+    if rc != 0:
+        err = JpgdError(rc, "jpgd_wait")
+        err.report = rep.as_dict()
+        raise err
+    return rep
+
+
+def jpgd_init() -> None:
+    """Per-device set-up of jpgd_decode_static (the current torch device)."""
+    _check(_load().jpgd_init(), "jpgd_init")
+
+
+def jpgd_static_workspace_bytes() -> int:
+    return int(_load().jpgd_static_workspace_bytes())
+
+
+def jpgd_decode_static(info, d_scan, d_coef, d_pixels, cfg: Config | None = None, stream=None) -> Report:
+    """jpgd_decode on the library's built-in workspace; allocates nothing (see include/jpgd.h)."""
+    lib = _load()
+    _require_cuda(d_scan, "d_scan")
+    _require_cuda(d_coef, "d_coef")
+    if d_pixels is not None:
+        _require_cuda(d_pixels, "d_pixels")
+    rep = Report()
+    rc = lib.jpgd_decode_static(ctypes.byref(info), d_scan.data_ptr(), d_coef.data_ptr(),
+                                d_pixels.data_ptr() if d_pixels is not None else None,
+                                ctypes.byref(cfg) if cfg is not None else None, _stream_handle(stream), ctypes.byref(rep))
+    if rc != 0:
+        err = JpgdError(rc, "jpgd_decode_static")
+        err.report = rep.as_dict()
+        raise err
+    return rep
+
+
 def jpgd_unstuff(d_in, d_out, d_workspace, stream=None) -> int:
     """Unstuffs d_in into d_out (which must hold len(d_in) + 256 bytes); returns the unstuffed length."""
     _require_cuda(d_in, "d_in")
@@ -253,9 +334,7 @@ class Batch:
     compressed_bytes: int
     pixels_total: int
 
-    def decode(self, stream=None, cfg: Config | None = None) -> Report:
-        """One jpgd_decode_batch call on the prepared buffers (argument arrays are marshalled once and reused)."""
-        lib = _load()
+    def _args(self):
         c = getattr(self, "_cargs", None)
         if c is None:
             n = len(self.infos)
@@ -266,7 +345,30 @@ class Batch:
                 scans=self.d_scans.data_ptr(), coef=self.d_coef.data_ptr(),
                 pix=self.d_pixels.data_ptr() if self.d_pixels is not None else None,
                 ws=self.d_workspace.data_ptr(), ws_bytes=self.d_workspace.numel())
+        return c
+
+    def decode_async(self, stream=None, cfg: Config | None = None):
+        """jpgd_decode_batch_async on the prepared buffers; returns the handle for wait()."""
+        lib = _load()
+        c = self._args()
         cfg = self.cfg if cfg is None else cfg
+        self._last_flags = cfg.flags
+        call = ctypes.c_void_p()
+        _check(lib.jpgd_decode_batch_async(c["n"], c["infos"], c["scans"], c["so"], c["coef"], c["co"], c["pix"], c["po"],
+                                           c["ws"], c["ws_bytes"], ctypes.byref(cfg), _stream_handle(stream),
+                                           ctypes.byref(call)), "jpgd_decode_batch_async")
+        return call
+
+    @staticmethod
+    def wait(call) -> Report:
+        return jpgd_wait(call)
+
+    def decode(self, stream=None, cfg: Config | None = None) -> Report:
+        """One jpgd_decode_batch call on the prepared buffers (argument arrays are marshalled once and reused)."""
+        lib = _load()
+        c = self._args()
+        cfg = self.cfg if cfg is None else cfg
+        self._last_flags = cfg.flags
         rep = Report()
         rc = lib.jpgd_decode_batch(c["n"], c["infos"], c["scans"], c["so"], c["coef"], c["co"], c["pix"], c["po"],
                                    c["ws"], c["ws_bytes"], ctypes.byref(cfg), _stream_handle(stream), ctypes.byref(rep))
@@ -286,19 +388,23 @@ class Batch:
         height x width, then Cb and Cr at their own resolution."""
         info = self.infos[i]
         off = self.pixel_offsets[i]
+        d = scale_denominator(getattr(self, "_last_flags", self.cfg.flags))
         out = []
         for c in range(info.ncomp):
             h = info.height if c == 0 else -(-info.height // info.vsamp[0])
             w = info.width if c == 0 else -(-info.width // info.hsamp[0])
+            h, w = -(-h // d), -(-w // d)
             out.append(self.d_pixels[off:off + h * w].view(h, w))
             off += h * w
         return out
 
     def pixels(self, i: int = 0):
+        """Image i as the last decode left it: [H, W, 3] or [H, W], at the size the JPGD_F_SCALE_* flag asked for."""
         info = self.infos[i]
-        n = info.width * info.height * info.ncomp
-        v = self.d_pixels[self.pixel_offsets[i]:self.pixel_offsets[i] + n]
-        return v.view(info.height, info.width, info.ncomp) if info.ncomp == 3 else v.view(info.height, info.width)
+        d = scale_denominator(getattr(self, "_last_flags", self.cfg.flags))
+        h, w = -(-info.height // d), -(-info.width // d)
+        v = self.d_pixels[self.pixel_offsets[i]:self.pixel_offsets[i] + h * w * info.ncomp]
+        return v.view(h, w, info.ncomp) if info.ncomp == 3 else v.view(h, w)
 
 
 def prepare_batch(files, cfg: Config | None = None, device="cuda:0", want_pixels: bool = True) -> Batch:

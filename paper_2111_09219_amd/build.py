@@ -26,10 +26,11 @@ def stale() -> bool:
 
 
 def build(force: bool = True) -> str:
-    """Build libjpgd.so; with force=False only if it is missing."""
-    if not force and os.path.exists(LIB):
-        return LIB
+    """Build libjpgd.so; with force=False only if it is missing or older than one of its sources (and a compiler
+    is at hand: a box without hipcc runs what was built)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not force and os.path.exists(LIB) and (not stale() or not os.path.exists(hipcc)):
+        return LIB
     tmp = LIB + ".tmp%d" % os.getpid()
     cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", tmp]
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

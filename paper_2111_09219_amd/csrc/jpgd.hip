@@ -94,6 +94,7 @@ uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
 // Validates arguments that do not need the GPU and lays the workspace out.
 int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     if (!infos || n < 1) return JPGD_E_ARG;
+    pl = Plan();  // (a slot's plan is used again by the slot's next call)
     uint32_t L = cfg && cfg->subseq_bits ? cfg->subseq_bits : choose_subseq_bits(infos, n);
     if (L < 128u || L > 2048u || (L & (L - 1u))) return JPGD_E_ARG;
     // default overlap: enough warm-up lanes that the chain entering a sequence is almost always synchronised,
@@ -240,6 +241,7 @@ struct jpgd_call {
     std::vector<hipEvent_t> timers;  // pairs of events for timing_mask
     bool busy = false;
     bool fixed = false;            // the slot of the entry point that allocates nothing: never grown, never shared
+    bool launched = false;         // something of the current call is in the stream
     // the call in flight
     Plan pl;
     Params P;
@@ -531,7 +533,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     if (rc) return rc;
     if (ws_cap < pl.h.total_bytes) return JPGD_E_WORKSPACE;
     const uint32_t flags_in = cfg ? cfg->flags : 0u;
-    const uint32_t scale_log2 = (flags_in & JPGD_F_SCALE_8) == JPGD_F_SCALE_8 ? 3u : (flags_in & JPGD_F_SCALE_4) ? 2u : (flags_in & JPGD_F_SCALE_2) ? 1u : 0u;
+    const uint32_t scale_log2 = (flags_in >> 2) & 3u;  // JPGD_F_SCALE_2, _4, _8 = 1, 2, 3 in bits 2..3
     c.want_pixels = d_pixels && !(flags_in & JPGD_F_NO_PIXELS);
     for (int i = 0; i < n; ++i) {
         if (scan_offsets[i] & 15u) return JPGD_E_ARG;
@@ -645,6 +647,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     c.rounds = c.redo = 0u;
     c.max_rounds = cfg && cfg->max_rounds ? cfg->max_rounds : pl.seqs + 1;
 
+    c.launched = true;
     if (n > 1)
         hipLaunchKernelGGL(k_upload, dim3(up_wgs), dim3(kWG), 0, stream, (const uint4*)c.buf_dev, (uint4*)ws, up_n16);
     LAUNCH(JPGD_K_UNSTUFF_COUNT, k_unstuff_count, pl.tiles + P.up_wgs, kWG, 0);
@@ -727,7 +730,8 @@ bool bad_pointers(int n, const jpgd_info* infos, const uint8_t* d_scans, const u
 // A call that failed after its first launch: kernels already queued may still read the slot's pinned buffer, so
 // the stream is drained before the slot goes back.
 void abandon_call(Call* c) {
-    if (c->stream || c->launches[JPGD_K_UNSTUFF_COUNT]) (void)hipStreamSynchronize(c->stream);
+    if (c->launched) (void)hipStreamSynchronize(c->stream);
+    c->launched = false;
     call_release(c);
 }
 
@@ -764,8 +768,7 @@ extern "C" int jpgd_decode_batch_async(int n, const jpgd_info* infos, const uint
     Call* c = nullptr;
     int rc = call_acquire(&c);
     if (rc) return rc;
-    c->stream = nullptr;
-    memset(c->launches, 0, sizeof c->launches);
+    c->launched = false;
     rc = enqueue_call(*c, n, infos, d_scans, scan_offsets, d_coef, coef_offsets, d_pixels, pixel_offsets, d_workspace,
                       workspace_bytes, cfg, (hipStream_t)stream);
     if (rc) {
@@ -876,12 +879,11 @@ extern "C" int jpgd_decode_static(const jpgd_info* info, const uint8_t* d_scan, 
     }
     Call& c = *D.call;
     c.busy = true;
-    c.stream = nullptr;
-    memset(c.launches, 0, sizeof c.launches);
+    c.launched = false;
     int rc = enqueue_call(c, 1, info, d_scan, &zero, d_coef, &zero, d_pixels, &zero, D.scratch_ptr, kStaticWsBytes, cfg,
                           (hipStream_t)stream);
     if (!rc) rc = finish_call(c, report);
-    if (rc != JPGD_OK && rc != JPGD_E_CORRUPT && (c.stream || c.launches[JPGD_K_UNSTUFF_COUNT])) (void)hipStreamSynchronize(c.stream);
+    if (rc != JPGD_OK && rc != JPGD_E_CORRUPT && c.launched) (void)hipStreamSynchronize(c.stream);
     c.busy = false;
     return rc;
 }

@@ -36,6 +36,7 @@ struct Params {
     uint32_t seq_len;       // kWG - H: subsequences a sequence owns
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
+    uint32_t scale_log2;    // pixel kernel: output at 1/2^scale_log2 of the size (0..3)
     uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
     uint32_t sync_waves;    // wavefronts per workgroup of that kernel: kWG / 64 that hold the lanes, the rest only take chains
     // A call with one image has the last up_wgs workgroups of k_unstuff_count copy the call's parameter block
@@ -117,11 +118,12 @@ __device__ __forceinline__ uint32_t wg_excl_scan(uint32_t v, uint32_t* scratch, 
 // sum of the DC differences): data units, and the DC sums of the three components.  With restart intervals
 // the DC sums are a segmented sum: a record whose subsequence holds the first symbol of an interval (flag)
 // starts them afresh.  join(a, b) = a followed by b; it is associative, so the usual scans apply.
+// (the sums are kept unsigned: only their low 16 bits are used and they may wrap on the way)
 struct Seg {
     uint32_t units, flag;
-    int32_t d0, d1, d2;
+    uint32_t d0, d1, d2;
 };
-__device__ __forceinline__ Seg seg_zero() { return Seg{0u, 0u, 0, 0, 0}; }
+__device__ __forceinline__ Seg seg_zero() { return Seg{0u, 0u, 0u, 0u, 0u}; }
 __device__ __forceinline__ Seg seg_join(const Seg& a, const Seg& b) {
     Seg r;
     r.units = a.units + b.units;
@@ -131,14 +133,14 @@ __device__ __forceinline__ Seg seg_join(const Seg& a, const Seg& b) {
     r.d2 = b.flag ? b.d2 : a.d2 + b.d2;
     return r;
 }
-__device__ __forceinline__ int32_t sx16(uint32_t v) { return (int32_t)(int16_t)(v & 0xFFFFu); }
+__device__ __forceinline__ uint32_t sx16(uint32_t v) { return (uint32_t)(int32_t)(int16_t)(v & 0xFFFFu); }
 __device__ __forceinline__ Seg seg_of_record(const SInfo& r) {
     return Seg{rec_units(r.y), rec_restarted(r.y), sx16(r.z), sx16(r.z >> 16), sx16(r.w)};
 }
 // group totals travel as int4: units with the flag in bit 31, then the three sums
-__device__ __forceinline__ int4 seg_pack(const Seg& s) { return make_int4((int)(s.units | (s.flag << 31)), s.d0, s.d1, s.d2); }
+__device__ __forceinline__ int4 seg_pack(const Seg& s) { return make_int4((int)(s.units | (s.flag << 31)), (int)s.d0, (int)s.d1, (int)s.d2); }
 __device__ __forceinline__ Seg seg_unpack(const int4& v) {
-    return Seg{(uint32_t)v.x & 0x7FFFFFFFu, (uint32_t)v.x >> 31, v.y, v.z, v.w};
+    return Seg{(uint32_t)v.x & 0x7FFFFFFFu, (uint32_t)v.x >> 31, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w};
 }
 __device__ __forceinline__ Seg seg_shfl_up(const Seg& v, int d) {
     Seg o;
@@ -160,14 +162,14 @@ __device__ __forceinline__ Seg wg_excl_segscan(Seg v, uint32_t* scratch, Seg* to
     __syncthreads();  // scratch may still be read from a previous use
     if (lane == 63u) {
         uint32_t* s5 = scratch + wave * 5u;
-        s5[0] = inc.units; s5[1] = inc.flag; s5[2] = (uint32_t)inc.d0; s5[3] = (uint32_t)inc.d1; s5[4] = (uint32_t)inc.d2;
+        s5[0] = inc.units; s5[1] = inc.flag; s5[2] = inc.d0; s5[3] = inc.d1; s5[4] = inc.d2;
     }
     __syncthreads();
     Seg carry = seg_zero(), all = seg_zero();
 #pragma unroll
     for (uint32_t k = 0; k < 4u; ++k) {
         const uint32_t* s5 = scratch + k * 5u;
-        const Seg t = Seg{s5[0], s5[1], (int32_t)s5[2], (int32_t)s5[3], (int32_t)s5[4]};
+        const Seg t = Seg{s5[0], s5[1], s5[2], s5[3], s5[4]};
         if (k < wave) carry = seg_join(carry, t);
         all = seg_join(all, t);
     }
@@ -811,9 +813,12 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     // nothing to do where the sequence behind the boundary already continues the state the one before ends in
     uint32_t g = 0u, x0 = 0u;
     bool work = false;
+    // The state words of records at a boundary are read here while the lane of the boundary before may be rewriting
+    // them (and read again by the totals kernel, which opens another round if the two did not agree): single
+    // 32-bit accesses, marked as such, with the rest of a record written before its state word.
     if (gfirst < nsub) {
         g = (uint32_t)gfirst;
-        x0 = rec[g - 1u].x;
+        x0 = __atomic_load_n(&rec[g - 1u].x, __ATOMIC_RELAXED);
         work = *warm != x0;
     }
     if (!__syncthreads_or(work)) return;
@@ -848,10 +853,13 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
         r.y = l.nb | (crossed << 31);
         r.z = pack_dc01(dcacc);
         r.w = pack_dc2(dcacc);
-        const bool synced = r.x == rec[g].x;
+        const bool synced = r.x == __atomic_load_n(&rec[g].x, __ATOMIC_RELAXED);
         if (first && !synced) atomicAdd(&P.status->inter_changed, 1u);
         first = false;
-        rec[g] = r;
+        rec[g].y = r.y;
+        rec[g].z = r.z;
+        rec[g].w = r.w;
+        __atomic_store_n(&rec[g].x, r.x, __ATOMIC_RELAXED);
         ++g;
         if (synced || g >= gend) break;
     }
@@ -887,7 +895,7 @@ __global__ __launch_bounds__(kWG) void k_group_totals(Params P) {
         const uint32_t g = (first + threadIdx.x) * P.seq_len;
         if (threadIdx.x < 4u && g > 0u && g < nsub && g < i0 + (uint32_t)kWG) {
             const uint32_t seq = first + threadIdx.x;
-            if (P.warm_x[D.seq0 + seq] != P.sinfo[D.sub0 + g - 1u].x) atomicOr(&P.status->pending, 1u);
+            if (P.warm_x[D.seq0 + seq] != __atomic_load_n(&P.sinfo[D.sub0 + g - 1u].x, __ATOMIC_RELAXED)) atomicOr(&P.status->pending, 1u);
         }
     }
 }
@@ -981,7 +989,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const Seg ex = seg_join(gp, wg_excl_segscan(seg_of_record(mine), scratch, &grp_tot));
     const uint32_t grp_units = grp_tot.units;
     uint32_t unit = ex.units;
-    int32_t pred0 = ex.d0, pred1 = ex.d1, pred2 = ex.d2;
+    int32_t pred0 = (int32_t)ex.d0, pred1 = (int32_t)ex.d1, pred2 = (int32_t)ex.d2;
 
     // The group clears the coefficients it is about to fill: those from where its first subsequence takes
     // over (data unit and zig-zag index) to where the next group's does; the last group goes on to the end of
@@ -1240,6 +1248,170 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
                 dst[e] = (uint8_t)(w >> (8u * (e & 3u)));
             }
         }
+    }
+}
+
+// ---- pixels at reduced size ------------------------------------------------------------------------------
+// Output at 1/2, 1/4 or 1/8 of the size straight from the coefficients: of every data unit only the N x N lowest
+// frequencies are read, N = 4, 2, 1, and the N-point inverse transform is applied to them,
+//   f(y,x) = 1/4 sum_{u<N} sum_{v<N} C(u) C(v) F(v,u) cos((2x+1) u pi/(2N)) cos((2y+1) v pi/(2N)),
+// with the 8-point transform's factor, so that a unit holding only a DC term keeps its value.  Everything after
+// that is as at full size: level shift, chroma replicated by the sampling factors, colour matrix, one rounding,
+// crop to ceil(width / d) x ceil(height / d).  (The paper's decoder ends with the full-size transform, Section 4.3,
+// and names it as the stage that now limits the decoder; this path reads the same coefficients and skips most of it.)
+
+// c_basis*[x * N + u] = 1/2 C(u) cos((2x+1) u pi / (2N))
+__device__ __constant__ float c_basis4[16] = {
+    0.35355339059327379f, 0.46193976625564337f, 0.35355339059327379f, 0.19134171618254489f,
+    0.35355339059327379f, 0.19134171618254489f, -0.35355339059327379f, -0.46193976625564337f,
+    0.35355339059327379f, -0.19134171618254489f, -0.35355339059327379f, 0.46193976625564337f,
+    0.35355339059327379f, -0.46193976625564337f, 0.35355339059327379f, -0.19134171618254489f};
+__device__ __constant__ float c_basis2[4] = {0.35355339059327379f, 0.35355339059327379f,
+                                             0.35355339059327379f, -0.35355339059327379f};
+
+template <int N>
+__global__ __launch_bounds__(kWG) void k_pixels_scaled(Params P) {
+    constexpr uint32_t NN = N * N;
+    constexpr uint32_t lN = N == 4 ? 2u : (N == 2 ? 1u : 0u);   // log2 N
+    __shared__ float fin[kPixBlocks * NN];   // dequantised low frequencies, [unit][v * N + u]
+    __shared__ float smp[kPixBlocks * NN];   // samples, level shift applied, [unit][y * N + x]
+    __shared__ float qf[3 * NN];
+    __shared__ float bs[NN];
+    __shared__ uint32_t zpos[NN];            // zig-zag position of frequency (v, u)
+    const uint32_t wg = blockIdx.x;
+    const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.pix_wg0; });
+    const ImgDesc D = image_desc_uniform(P, ii);
+    const uint32_t lw = wg - D.pix_wg0;
+    const uint32_t mrow = lw / D.pix_runs, run = lw % D.pix_runs;
+    const uint32_t upm = D.upm;
+    const uint32_t M = (uint32_t)kPixBlocks / upm;
+    const uint32_t m0 = run * M;
+    const uint32_t nm = min(M, D.mcus_x - m0);
+    const uint32_t nblk = nm * upm;
+    const uint32_t t = threadIdx.x;
+    if (wg == 0u && t == 0u && P.verdict) {  // the verdict of the write kernel, as in k_pixels
+        volatile uint32_t* host = P.verdict;
+        host[0] = P.status->flags;
+        host[1] = P.status->inter_changed;
+        host[2] = P.status->pending;
+        __threadfence_system();
+        host[15] = P.ticket;
+    }
+    if (t < 64u) {
+        const uint32_t rc = c_zigzag[t];
+        if ((rc >> 3) < (uint32_t)N && (rc & 7u) < (uint32_t)N) zpos[(rc >> 3) * N + (rc & 7u)] = t;
+    }
+    if (t < NN) bs[t] = N == 4 ? c_basis4[t] : (N == 2 ? c_basis2[t & 3u] : 0.35355339059327379f);
+    __syncthreads();
+    if (t < 3u * NN) qf[t] = (float)P.qts[D.qt_off + (t / NN) * 64u + zpos[t % NN]];
+    __syncthreads();
+    const int16_t* coef = P.coef + D.coef_off + (size_t)((size_t)mrow * D.mcus_x + m0) * upm * 64u;
+    for (uint32_t j = t; j < nblk * NN; j += kWG) {
+        const uint32_t k = j >> (2u * lN), e = j & (NN - 1u);
+        const uint32_t ku = upm == 1u ? 0u : (upm == 3u ? k % 3u : (upm == 4u ? (k & 3u) : k % 6u));
+        const uint32_t comp = (D.sched_comp >> (ku * 4u)) & 15u;
+        fin[j] = (float)coef[(size_t)k * 64u + zpos[e]] * qf[comp * NN + e];
+    }
+    __syncthreads();
+    for (uint32_t j = t; j < nblk * NN; j += kWG) {
+        const uint32_t k = j >> (2u * lN), y = (j >> lN) & (N - 1u), x = j & (N - 1u);
+        const float* F = fin + k * NN;
+        float acc = 128.0f;
+#pragma unroll
+        for (uint32_t v = 0; v < (uint32_t)N; ++v) {
+            float row = 0.0f;
+#pragma unroll
+            for (uint32_t u = 0; u < (uint32_t)N; ++u) row = __builtin_fmaf(bs[x * N + u], F[v * N + u], row);
+            acc = __builtin_fmaf(bs[y * N + v], row, acc);
+        }
+        smp[j] = acc;
+    }
+    __syncthreads();
+
+    const uint32_t hs = D.hs, vs = D.vs, ncomp = D.ncomp;
+    const uint32_t lhs = hs >> 1, lvs = vs >> 1;
+    const uint32_t ls = 3u - lN;                                  // log2 of the scale denominator
+    const uint32_t ow = (D.width + (1u << ls) - 1u) >> ls, oh = (D.height + (1u << ls) - 1u) >> ls;
+    uint8_t* pix = P.pixels + D.pix_off;
+    // sample (py, px) of the rectangle that component units [u0, u0 + ux * uy) of the workgroup's MCUs cover
+    // (ux x uy units of N x N samples per MCU)
+    auto sample = [&](uint32_t u0, uint32_t lux, uint32_t py, uint32_t px) {
+        const uint32_t lmw = lN + lux;                            // log2 of the samples per MCU row
+        const uint32_t m = px >> lmw, xin = px & ((1u << lmw) - 1u);
+        const uint32_t unit = m * upm + u0 + ((py >> lN) << lux) + (xin >> lN);
+        return smp[unit * NN + ((py & (N - 1u)) << lN) + (xin & (N - 1u))];
+    };
+    auto put = [&](uint8_t* dst, const uint32_t* w, uint32_t nbytes, bool words) {
+        if (words) {
+            for (uint32_t e = 0; e < nbytes / 4u; ++e) reinterpret_cast<uint32_t*>(dst)[e] = w[e];
+        } else {
+            for (uint32_t e = 0; e < nbytes; ++e) dst[e] = (uint8_t)(w[e >> 2] >> (8u * (e & 3u)));
+        }
+    };
+    if (P.planar) {
+        // component planes at reduced size, one after the other: plane c has ceil(plane_w / d) x ceil(plane_h / d) samples
+        size_t plane_off = 0;
+        for (uint32_t c = 0; c < ncomp; ++c) {
+            const uint32_t lux = c == 0u ? lhs : 0u, luy = c == 0u ? lvs : 0u;
+            const uint32_t u0 = c == 0u ? 0u : hs * vs + c - 1u;
+            const uint32_t full_w = c == 0u ? D.width : (D.width + hs - 1u) >> lhs;
+            const uint32_t full_h = c == 0u ? D.height : (D.height + vs - 1u) >> lvs;
+            const uint32_t pw = (full_w + (1u << ls) - 1u) >> ls, ph = (full_h + (1u << ls) - 1u) >> ls;
+            uint8_t* plane = pix + plane_off;
+            plane_off += (size_t)pw * ph;
+            const uint32_t region_w = nm << (lN + lux), region_h = 1u << (lN + luy);
+            const uint32_t gpr = (region_w + 3u) >> 2;
+            const uint32_t x_base = m0 << (lN + lux), y_base = mrow << (lN + luy);
+            const bool words_ok = (pw & 3u) == 0u && (reinterpret_cast<size_t>(plane) & 3u) == 0u;
+            for (uint32_t j = t; j < gpr * region_h; j += kWG) {
+                const uint32_t py = j / gpr, px0 = (j - py * gpr) * 4u;
+                const uint32_t gy = y_base + py, gx0 = x_base + px0;
+                if (gy >= ph || gx0 >= pw) continue;
+                const uint32_t cnt = min(4u, min(region_w - px0, pw - gx0));
+                uint32_t w[1] = {0u};
+                w[0] = pack_u8(sample(u0, lux, py, px0), 0u, w[0]);
+                w[0] = pack_u8(sample(u0, lux, py, min(px0 + 1u, region_w - 1u)), 1u, w[0]);
+                w[0] = pack_u8(sample(u0, lux, py, min(px0 + 2u, region_w - 1u)), 2u, w[0]);
+                w[0] = pack_u8(sample(u0, lux, py, min(px0 + 3u, region_w - 1u)), 3u, w[0]);
+                put(plane + (size_t)gy * pw + gx0, w, cnt, cnt == 4u && words_ok);
+            }
+        }
+        return;
+    }
+    // gray or RGB: a lane produces four horizontally adjacent pixels
+    const uint32_t region_w = nm << (lN + lhs), region_h = 1u << (lN + lvs);
+    const uint32_t gpr = (region_w + 3u) >> 2;
+    const uint32_t x_base = m0 << (lN + lhs), y_base = mrow << (lN + lvs);
+    const uint32_t row_bytes = ow * ncomp;
+    const bool words_ok = (row_bytes & 3u) == 0u && (reinterpret_cast<size_t>(pix) & 3u) == 0u;
+    for (uint32_t j = t; j < gpr * region_h; j += kWG) {
+        const uint32_t py = j / gpr, px0 = (j - py * gpr) * 4u;
+        const uint32_t gy = y_base + py, gx0 = x_base + px0;
+        if (gy >= oh || gx0 >= ow) continue;
+        const uint32_t cnt = min(4u, min(region_w - px0, ow - gx0));
+        uint32_t w[3] = {0u, 0u, 0u};
+        float yv[4];
+        ChromaTerms ct[4];
+#pragma unroll
+        for (uint32_t e = 0; e < 4u; ++e) {
+            const uint32_t px = min(px0 + e, region_w - 1u);
+            yv[e] = sample(0u, lhs, py, px);
+            if (ncomp == 3u) {
+                const float cb = sample(hs * vs, 0u, py >> lvs, px >> lhs), cr = sample(hs * vs + 1u, 0u, py >> lvs, px >> lhs);
+                ct[e] = chroma_terms(cb, cr);
+            }
+        }
+        if (ncomp == 1u) {
+            w[0] = pack_u8(yv[0], 0u, w[0]); w[0] = pack_u8(yv[1], 1u, w[0]);
+            w[0] = pack_u8(yv[2], 2u, w[0]); w[0] = pack_u8(yv[3], 3u, w[0]);
+        } else {
+            // bytes in memory: R0 G0 B0 R1 | G1 B1 R2 G2 | B2 R3 G3 B3
+            w[0] = pack_u8(yv[0] + ct[0].r, 0u, w[0]); w[0] = pack_u8(yv[0] + ct[0].g, 1u, w[0]); w[0] = pack_u8(yv[0] + ct[0].b, 2u, w[0]);
+            w[0] = pack_u8(yv[1] + ct[1].r, 3u, w[0]); w[1] = pack_u8(yv[1] + ct[1].g, 0u, w[1]); w[1] = pack_u8(yv[1] + ct[1].b, 1u, w[1]);
+            w[1] = pack_u8(yv[2] + ct[2].r, 2u, w[1]); w[1] = pack_u8(yv[2] + ct[2].g, 3u, w[1]); w[2] = pack_u8(yv[2] + ct[2].b, 0u, w[2]);
+            w[2] = pack_u8(yv[3] + ct[3].r, 1u, w[2]); w[2] = pack_u8(yv[3] + ct[3].g, 2u, w[2]); w[2] = pack_u8(yv[3] + ct[3].b, 3u, w[2]);
+        }
+        put(pix + (size_t)gy * row_bytes + (size_t)gx0 * ncomp, w, cnt * ncomp, cnt == 4u && words_ok);
     }
 }
 

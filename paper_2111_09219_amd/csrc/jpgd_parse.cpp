@@ -164,6 +164,7 @@ extern "C" const char* jpgd_strerror(int status) {
         case JPGD_E_CORRUPT: return "entropy-coded data inconsistent with the headers";
         case JPGD_E_WORKSPACE: return "workspace too small or misaligned";
         case JPGD_E_HIP: return "HIP runtime error";
+        case JPGD_E_BUSY: return "too many calls in flight";
         default: return "unknown status";
     }
 }

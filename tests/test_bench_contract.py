@@ -26,10 +26,27 @@ def test_algorithmic_bytes_follow_the_stated_formulas():
     Bs, B, S, K, out = 1000, 990, 62, 40, 2560
     assert bench.algorithmic_bytes("unstuff_count", Bs, B, S, K, out) == Bs
     assert bench.algorithmic_bytes("unstuff_scatter", Bs, B, S, K, out) == Bs + B
-    assert bench.algorithmic_bytes("sync_intra", Bs, B, S, K, out) == B + 16 * S
-    assert bench.algorithmic_bytes("write", Bs, B, S, K, out) == B + 16 * S + 128 * K
+    assert bench.algorithmic_bytes("sync_intra", Bs, B, S, K, out) == B + 8 * S
+    assert bench.algorithmic_bytes("write", Bs, B, S, K, out) == B + 8 * S + 128 * K
     assert bench.algorithmic_bytes("pixels", Bs, B, S, K, out) == 128 * K + out
     assert bench.HBM_PEAK_GBS == 8000.0
+
+
+def test_traffic_figures_come_from_the_committed_profile_summaries():
+    """bench.py takes the measured HBM traffic per kernel from the rocprofv3 summaries in profiles/ (no figures of
+    its own), and marks them stale when the kernel sources have changed since the summary was made."""
+    sys.path.insert(0, ROOT)
+    import bench
+    for c, name in bench.PROFILE_FILES.items():
+        path = os.path.join(ROOT, "profiles", name)
+        traffic, stale = bench.profile_traffic(c)
+        if not os.path.isfile(path):
+            assert traffic == {} and stale is None
+            continue
+        assert stale in (True, False)
+        for k in ("sync_intra", "write", "pixels"):
+            assert traffic[k] > 0
+    assert len(bench.kernel_sources_sha16()) == 16
 
 
 @pytest.mark.gpu
@@ -55,3 +72,9 @@ def test_the_json_line_has_the_agreed_fields():
         assert key in cpu, key
     assert cpu["kind"] == "oracle" and cpu["cores"] == 1 and cpu["value"] > 0
     assert d["value"] > 0 and d["ms_per_step"] > 0
+    # every kernel of the path with its share of the HBM roofline, the sync and the write kernel among them
+    for k in ("sync_intra", "write", "pixels"):
+        e = d["kernels"][k]
+        assert e["ms"] > 0 and abs(e["frac"] - e["achieved_gbs"] / 8000.0) < 1e-4 and "traffic" in e
+    h = d["with_h2d"]
+    assert h["serial_ms_per_step"] > 0 and h["overlapped_ms_per_step"] > 0 and h["from_files_ms_per_step"] > 0

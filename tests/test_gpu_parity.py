@@ -38,7 +38,9 @@ def _check_image(batch, i, data, pixel_rects=None):
     if pixel_rects is None:
         want = o.pixels(ref)
         assert pix.shape == want.shape
-        assert np.abs(pix.astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL
+        for y0 in range(0, pix.shape[0], 512):       # in strips: the largest frame has 400 MB of pixels
+            d = np.abs(pix[y0:y0 + 512].astype(np.int16) - want[y0:y0 + 512].astype(np.int16))
+            assert d.max() <= PIXEL_TOL, "pixel rows %d..%d" % (y0, y0 + 512)
     else:
         mw, mh = o.info.hmax * 8, o.info.vmax * 8
         for (mx0, mx1, my0, my1) in pixel_rects:
@@ -318,8 +320,10 @@ def test_sequences_that_need_several_inter_sequence_rounds():
     batch, rep = _decode([other, data, other], subseq_bits=128)
     for i, f in enumerate([other, data, other]):
         _check_image(batch, i, f)
-    with pytest.raises(J.JpgdError):
-        _decode([data], subseq_bits=128, max_rounds=2)
+    for few in (1, 2):
+        with pytest.raises(J.JpgdError) as e:
+            _decode([data], subseq_bits=128, max_rounds=few)
+        assert e.value.name == "CORRUPT" and e.value.report["inter_rounds"] == few
 
 
 def test_randomised_calls_in_the_regime_of_many_inter_sequence_rounds():
@@ -404,8 +408,8 @@ def test_decode_on_a_stream_of_the_callers():
 
 
 def test_calls_from_two_threads():
-    """Two host threads, each with its own buffers and stream, call the library at the same time: calls are
-    serialised inside (one staging buffer, one verdict), and every result is the oracle's."""
+    """Two host threads, each with its own buffers and stream, call the library at the same time: every call has a
+    slot of its own inside (parameter block, verdict), and every result is the oracle's."""
     import threading
     import torch
     files = [encode_jpeg(small_image(95 + k, 260 + 40 * k, 380, sigma=9.0), 85 + 5 * k, sub, bool(k)).data
@@ -534,9 +538,13 @@ def test_output_buffers_need_not_be_cleared():
             _check_image(b2, 0, other)
 
 
-def test_config4_batch_slice():
-    files = [e.data for e in config_jpeg(4, limit=24)]
+def test_config4_whole_batch_in_one_call():
+    """All 256 images of the batch workload in one call (one launch of every kernel covers them all, 256
+    descriptors, one shared set of tables): every image's coefficients and pixels against the oracle."""
+    files = [e.data for e in config_jpeg(4)]
+    assert len(files) == 256
     batch, rep = _decode(files)
+    assert rep.redo == 0
     for i, f in enumerate(files):
         _check_image(batch, i, f)
 
@@ -619,7 +627,7 @@ def test_random_damage_is_reported_or_decoded_like_the_oracle(sub, opt, ri):
 def test_config3_4096_optimized_tables():
     data = config_jpeg(3).data
     batch, rep = _decode([data])
-    _check_image(batch, 0, data, pixel_rects=[(0, 16, 0, 8), (120, 136, 100, 104), (240, 256, 250, 256)])
+    _check_image(batch, 0, data)      # every coefficient and every pixel of the frame
 
 
 def test_large_image_with_restart_intervals_and_small_subsequences():
@@ -633,8 +641,116 @@ def test_large_image_with_restart_intervals_and_small_subsequences():
 
 @pytest.mark.slow
 def test_config5_flat_and_random_halves():
-    """Full size: 15360x8640.  All coefficients are compared (the oracle's entropy decode takes seconds);
-    pixels on sampled MCU rectangles from both halves, the seam and the last rows."""
+    """Full size: 15360x8640, in the launch configuration the bench times.  Every coefficient and every pixel of
+    the frame is compared with the oracle."""
     data = config_jpeg(5).data
     batch, rep = _decode([data])
-    _check_image(batch, 0, data, pixel_rects=[(0, 24, 0, 4), (470, 490, 270, 273), (940, 960, 536, 540)])
+    _check_image(batch, 0, data)
+
+
+# ------------------------------------------------------------------------------------ reduced-size output
+
+@pytest.mark.parametrize("sub", ["gray", "444", "422", "420"])
+def test_reduced_size_output(sub):
+    """JPGD_F_SCALE_2/4/8 against the oracle's definition (n-point inverse transform of the n x n lowest
+    frequencies): RGB and planes, sizes that are and are not multiples of the MCU and of the scale, a size that
+    allows word stores and sizes that do not, alone and as one batch; the coefficients are unaffected."""
+    files = []
+    for seed, (h, w), q in [(71, (37, 51), 85), (72, (200, 336), 94), (73, (8, 8), 40), (74, (129, 70), 75),
+                            (75, (64, 64), 90), (76, (1, 1), 90), (77, (403, 1031), 97)]:
+        px = small_image(seed, h, w, ncomp=1 if sub == "gray" else 3, sigma=10.0)
+        files.append(encode_jpeg(px, q, sub, bool(seed & 1)).data)
+    oracles = [OracleImage(f) for f in files]
+    refs = [o.coefficients() for o in oracles]
+    for flag, d in ((J.F_SCALE_2, 2), (J.F_SCALE_4, 4), (J.F_SCALE_8, 8)):
+        for planar in (0, J.F_PLANAR):
+            for group in ([[k] for k in range(len(files))] + [list(range(len(files)))]):
+                batch = J.prepare_batch([files[k] for k in group], J.Config.make(flags=flag | planar))
+                batch.d_pixels.fill_(0x5A)
+                batch.decode()
+                for i, k in enumerate(group):
+                    o = oracles[k]
+                    assert np.array_equal(batch.coefficients(i).cpu().numpy(), refs[k])
+                    if planar:
+                        want = o.planes_scaled(d, refs[k])
+                        got = [p.cpu().numpy() for p in batch.planes(i)]
+                        assert [g.shape for g in got] == [x.shape for x in want]
+                        for g, x in zip(got, want):
+                            assert np.abs(g.astype(np.int16) - x.astype(np.int16)).max() <= PIXEL_TOL, (sub, d, k)
+                        used = sum(x.size for x in want)
+                    else:
+                        want = o.pixels_scaled(d, refs[k])
+                        got = batch.pixels(i).cpu().numpy()
+                        assert got.shape == want.shape
+                        assert np.abs(got.astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL, (sub, d, k)
+                        used = want.size
+                    # nothing written behind the reduced image inside this image's share of the buffer
+                    info = batch.infos[i]
+                    room = info.width * info.height * info.ncomp
+                    tail = batch.d_pixels[batch.pixel_offsets[i] + used:batch.pixel_offsets[i] + room].cpu().numpy()
+                    assert (tail == 0x5A).all(), (sub, d, k)
+
+
+def test_reduced_size_output_of_the_hd_workload():
+    """configs[1] (1920x1088 4:4:4) at every reduced size, whole frame."""
+    data = config_jpeg(2).data
+    o = OracleImage(data)
+    ref = o.coefficients()
+    for flag, d in ((J.F_SCALE_2, 2), (J.F_SCALE_4, 4), (J.F_SCALE_8, 8)):
+        batch, rep = _decode([data], flags=flag)
+        want = o.pixels_scaled(d, ref)
+        got = batch.pixels(0).cpu().numpy()
+        assert got.shape == want.shape == (1088 // d, 1920 // d, 3)
+        assert np.abs(got.astype(np.int16) - want.astype(np.int16)).max() <= PIXEL_TOL
+
+
+# ------------------------------------------------------------------------------------ calls in flight
+
+def test_two_batches_in_flight_with_the_next_copy_overlapping():
+    """The end-to-end setting of the paper's measurements (Section 5: the transfer of the compressed data is part
+    of the job): two sets of buffers; while one batch is being decoded on its stream, the host -- which
+    jpgd_decode_batch_async has already handed back -- copies the next batch's bytes from pinned memory on another
+    stream and enqueues its decode.  Both calls are in flight before the first is waited for.  Every result is the
+    oracle's; the batches differ (different images, different tables)."""
+    import torch
+    sets = [[encode_jpeg(small_image(200 + 10 * s + k, 300 + 40 * k, 420, sigma=9.0 + 3 * s), 80 + 5 * s, sub, bool(k & 1)).data
+             for k, sub in enumerate(("420", "444", "gray", "422"))] for s in range(2)]
+    batches = [J.prepare_batch(fs) for fs in sets]
+    hosts = [b.d_scans.cpu().pin_memory() for b in batches]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rounds in range(3):
+        for b in batches:
+            b.d_scans.zero_()
+            b.d_coef.fill_(-5)
+            b.d_pixels.fill_(9)
+        torch.cuda.synchronize()
+        calls = []
+        for k in (0, 1):
+            with torch.cuda.stream(streams[k]):
+                batches[k].d_scans.copy_(hosts[k], non_blocking=True)
+                calls.append(batches[k].decode_async(stream=streams[k]))
+        reps = [J.jpgd_wait(c) for c in calls]
+        for k in (0, 1):
+            streams[k].synchronize()
+            assert reps[k].redo == 0
+            for i, f in enumerate(sets[k]):
+                _check_image(batches[k], i, f)
+    # a handle can be waited for only once, and a corrupt stream is reported by the wait, not by the enqueue
+    with pytest.raises(J.JpgdError) as e:
+        J.jpgd_wait(calls[0])
+    assert e.value.name == "ARG"
+    enc = encode_jpeg(small_image(5, 128, 128), 85, "420")
+    short = np.concatenate([enc.data[:enc.scan_offset + enc.scan_len // 2], np.array([0xFF, 0xD9], np.uint8)])
+    bad = J.prepare_batch([short])
+    call = bad.decode_async()
+    with pytest.raises(J.JpgdError) as e:
+        J.jpgd_wait(call)
+    assert e.value.name == "CORRUPT"
+    # many calls in flight on one stream, each with buffers of its own, waited for in reverse order
+    many = [J.prepare_batch([sets[k & 1][k % 4]]) for k in range(6)]
+    calls = [b.decode_async() for b in many]
+    for b, c in reversed(list(zip(many, calls))):
+        J.jpgd_wait(c)
+    torch.cuda.synchronize()
+    for k, b in enumerate(many):
+        _check_image(b, 0, sets[k & 1][k % 4])
