@@ -1021,7 +1021,39 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t* gwords = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off) + first_word;
     auto fetch = [&](uint32_t c) { return STAGED ? strm[c] : __builtin_bswap32(gwords[c]); };
     int16_t* coef = P.coef + D.coef_off;
-    auto store = [&](uint32_t k, uint32_t at, int16_t v) { coef[(size_t)(k * 64u + at)] = v; };
+    // Coefficients leave the lane four at a time.  Every value as a store of its own makes 64 two-byte requests per
+    // dense data unit, and the number of requests, not of bytes, is what the memory system charges for: the values
+    // of four neighbouring slots (one aligned 8-byte chunk of the output) are gathered in a register pair and
+    // stored together when the lane moves on to another chunk.  The zeros among them are the lane's own (the chunk
+    // lies inside the range of slots this lane covers), except in the chunk the lane starts in, if it starts in
+    // the middle of one, and in the chunk it ends in: those are shared with the neighbouring lanes and get their
+    // non-zero values one by one, onto the zeros the workgroup has laid down.  (Eight slots per store were measured
+    // too: no faster on dense units, slower on sparse ones.)
+    uint64_t acc = 0ull;
+    uint32_t cur = 0xFFFFFFFFu;  // chunk being gathered: 16 * data unit + (slot >> 2)
+    const uint32_t shared0 = (state_z(xprev) & 3u) ? unit * 16u + (state_z(xprev) >> 2) : 0xFFFFFFFFu;
+    auto flush = [&](bool last) {
+        if (cur == 0xFFFFFFFFu) return;
+        int16_t* dst = coef + (size_t)cur * 4u;
+        if (last || cur == shared0) {
+#pragma unroll
+            for (uint32_t e = 0; e < 4u; ++e) {
+                const int16_t v = (int16_t)(uint16_t)(acc >> (16u * e));
+                if (v != 0) dst[e] = v;
+            }
+        } else {
+            *reinterpret_cast<uint64_t*>(dst) = acc;
+        }
+    };
+    auto store = [&](uint32_t k, uint32_t at, int16_t v) {
+        const uint32_t ck = k * 16u + (at >> 2);
+        if (ck != cur) {
+            flush(false);
+            acc = 0ull;
+            cur = ck;
+        }
+        acc |= (uint64_t)(uint16_t)v << ((at & 3u) * 16u);
+    };
     Lane l;
     BitWin w;
     l.p = (i << P.logL) + state_prel(xprev);
@@ -1039,6 +1071,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
         if (restart) decode_span_write_rst(l, w, limit, unit, total, D.restart * D.upm, pred0, pred1, pred2, sx, fetch, lut_s, store, flags, bword);
         else decode_span_write(l, w, limit, unit, total, pred0, pred1, pred2, sx, fetch, lut_s, store, flags);
     }
+    flush(true);
     // all restart markers must have been there (the first lane of the image speaks for it)
     if (RST && D.restart && i == 0u && P.st[ii].markers != D.nint - 1u) flags |= kStInvalid;
     // every lane checks the chain: unless the image is complete it must end in the recorded state
