@@ -145,6 +145,9 @@ struct Status {
     uint32_t pad;
 };
 
+// write kernel: from this many bits of stream per data unit on, a workgroup's lanes lay down their own zeros instead
+// of the workgroup clearing its stretch of the output first
+constexpr uint32_t kDenseBitsPerUnit = 256u;
 constexpr int kUnstuffTile = 4096;  // bytes per workgroup of the unstuff kernels (256 lanes x 16 bytes)
 constexpr int kPixBlocks = 48;      // data units per workgroup of the pixel kernel
 

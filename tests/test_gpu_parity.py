@@ -538,6 +538,41 @@ def test_output_buffers_need_not_be_cleared():
             _check_image(b2, 0, other)
 
 
+def test_dense_and_sparse_stretches_in_one_image():
+    """The write pass treats a workgroup's stretch of the output in one of two ways: where data units are dense the
+    lanes lay down the zeros of their own ranges, where they are sparse the workgroup clears its stretch first.
+    Images that switch between the two (flat and noise halves like configs[4], noise stripes, every subsequence
+    size), into buffers full of stale values: every slot must end up defined, zeros included."""
+    rng = np.random.default_rng(55)
+    imgs = []
+    h, w = 203, 333
+    half = np.full((h, w, 3), 128, np.uint8)
+    half[:, w // 2:] = rng.integers(0, 256, size=(h, w - w // 2, 3), dtype=np.uint8)
+    imgs.append((half, 92, "420"))
+    stripes = np.full((h, w, 3), 90, np.uint8)
+    for y0 in range(0, h, 48):
+        stripes[y0:y0 + 16] = rng.integers(0, 256, size=(min(16, h - y0), w, 3), dtype=np.uint8)
+    imgs.append((stripes, 97, "444"))
+    imgs.append((rng.integers(0, 256, size=(h, w), dtype=np.uint8), 100, "gray"))
+    imgs.append((rng.integers(0, 256, size=(64, 40, 3), dtype=np.uint8), 99, "422"))
+    for px, q, sub in imgs:
+        for opt in (False, True):
+            data = encode_jpeg(px, q, sub, opt).data
+            for L in (128, 256, 1024, 2048):
+                batch = J.prepare_batch([data], J.Config.make(subseq_bits=L))
+                batch.d_coef.fill_(0x7777)
+                batch.d_pixels.fill_(0x5A)
+                batch.decode()
+                _check_image(batch, 0, data)
+    # all of them in one call
+    files = [encode_jpeg(px, q, sub).data for px, q, sub in imgs]
+    batch = J.prepare_batch(files)
+    batch.d_coef.fill_(0x7777)
+    batch.decode()
+    for i, f in enumerate(files):
+        _check_image(batch, i, f)
+
+
 def test_config4_whole_batch_in_one_call():
     """All 256 images of the batch workload in one call (one launch of every kernel covers them all, 256
     descriptors, one shared set of tables): every image's coefficients and pixels against the oracle."""
