@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # rocprofv3 kernel names of the kernels bench.py reports on (prefixes of the names in profiles/*.md)
 PROFILE_NAMES = {"unstuff_count": "jpgd::k_unstuff_count", "unstuff_scan": "jpgd::k_unstuff_scan",
-                 "unstuff_scatter": "jpgd::k_unstuff_scatter", "sync_intra": "jpgd::k_sync_intra",
+                 "unstuff_scatter": "jpgd::k_unstuff_scatter", "sync_intra": "jpgd::k_sync_intra", "sync_tail": "jpgd::k_sync_intra",
                  "sync_inter": "jpgd::k_sync_inter", "scan_totals": "jpgd::k_group_totals",
                  "scan_prefix": "jpgd::k_group_scan", "write": "jpgd::k_write", "pixels": "jpgd::k_pixels"}
 PROFILE_FILES = {1: "decode_path_gray256_q75.md", 2: "decode_path_hd1088_444_q90.md", 3: "decode_path_4k_420_q95_opt.md",
@@ -45,6 +45,7 @@ def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: i
         "unstuff_scan": 8 * (Bs // 4096 + 1),
         "unstuff_scatter": Bs + B,
         "sync_intra": B + 8 * S,
+        "sync_tail": 8 * S,
         "sync_inter": 8 * (S // 256 + 1),
         "scan_totals": 8 * S,
         "scan_prefix": 32 * (S // 256 + 1),

@@ -85,6 +85,13 @@ typedef struct {
     uint32_t flags;        /* JPGD_F_*: at most one of the JPGD_F_SCALE_* */
     uint32_t timing_mask;  /* bit k set: bracket kernel k (JPGD_K_*) with HIP events on the stream
                               and report its duration; 0 = no events                               */
+    uint32_t sync_split;   /* intra-sequence synchronisation (Algorithm 3, first loop) in one kernel or in
+                              two (the second one takes over when few chains of a sequence are left and
+                              runs them without the LDS copy of the stream, so that a CU holds more
+                              sequences): 0 = the library decides (two for calls with many more sequences
+                              than the chip holds at a time), 1 = one kernel, 2 = two kernels wherever
+                              the call allows it (no restart intervals, at most four tables per image).
+                              The result does not depend on it.                                     */
 } jpgd_config;
 
 #define JPGD_F_NO_PIXELS 1u /* stop after the coefficients even if a pixel buffer is given */
@@ -111,6 +118,7 @@ enum {
     JPGD_K_UNSTUFF_SCAN,      /* unstuff: exclusive scan of the tile counts, unstuffed length      */
     JPGD_K_UNSTUFF_SCATTER,   /* unstuff: compaction                                               */
     JPGD_K_SYNC_INTRA,        /* Algorithm 3, first loop                                           */
+    JPGD_K_SYNC_TAIL,         /* Algorithm 3, first loop: its late rounds, when run as a kernel of their own */
     JPGD_K_SYNC_INTER,        /* Algorithm 3, second loop                                          */
     JPGD_K_SCAN_TOTALS,       /* exclusive scan over s_info: totals per group of 256 records       */
     JPGD_K_SCAN_PREFIX,       /* exclusive scan over s_info: prefix of the group totals            */

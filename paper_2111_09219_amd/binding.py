@@ -59,15 +59,15 @@ class Info(ctypes.Structure):
 class Config(ctypes.Structure):
     """jpgd_config"""
     _fields_ = [("subseq_bits", ctypes.c_uint32), ("overlap", ctypes.c_uint32), ("max_rounds", ctypes.c_uint32),
-                ("flags", ctypes.c_uint32), ("timing_mask", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("timing_mask", ctypes.c_uint32), ("sync_split", ctypes.c_uint32)]
 
     @staticmethod
     def make(subseq_bits: int = 0, overlap: int | None = None, max_rounds: int = 0, flags: int = 0,
-             timing_mask: int = 0) -> "Config":
-        return Config(subseq_bits, 0xFFFFFFFF if overlap is None else overlap, max_rounds, flags, timing_mask)
+             timing_mask: int = 0, sync_split: int = 0) -> "Config":
+        return Config(subseq_bits, 0xFFFFFFFF if overlap is None else overlap, max_rounds, flags, timing_mask, sync_split)
 
 
-KERNELS = ["unstuff_count", "unstuff_scan", "unstuff_scatter", "sync_intra", "sync_inter", "scan_totals",
+KERNELS = ["unstuff_count", "unstuff_scan", "unstuff_scatter", "sync_intra", "sync_tail", "sync_inter", "scan_totals",
            "scan_prefix", "write", "pixels"]
 
 
@@ -75,7 +75,7 @@ class Report(ctypes.Structure):
     """jpgd_report"""
     _fields_ = [("subseq_bits", ctypes.c_uint32), ("n_subseq", ctypes.c_uint32), ("n_sequences", ctypes.c_uint32),
                 ("inter_rounds", ctypes.c_uint32), ("redo", ctypes.c_uint32), ("device_flags", ctypes.c_uint32),
-                ("launches", ctypes.c_uint32 * 9), ("kernel_ms", ctypes.c_float * 9)]
+                ("launches", ctypes.c_uint32 * 10), ("kernel_ms", ctypes.c_float * 10)]
 
     def as_dict(self):
         d = {k: int(getattr(self, k)) for k, _ in self._fields_[:6]}

@@ -25,7 +25,7 @@ constexpr uint32_t kMagic = 0x4A504744u;  // "JPGD"
 struct WsHeader {
     uint32_t magic, nimg, logL, overlap;
     uint64_t off_status, off_state, off_img, off_lut, off_qt;       // uploaded region
-    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref, off_bmap, off_warm; // device-written regions
+    uint64_t off_tiles, off_stream, off_sinfo, off_gtot, off_gpref, off_bmap, off_warm, off_seqrec; // device-written regions
     uint64_t upload_bytes, total_bytes;
 };
 
@@ -37,6 +37,7 @@ struct Plan {
     uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, nsub_total = 0;
     uint32_t bmap_words = 0;  // interval-start bitmaps of the images that have restart intervals
     uint32_t L = 0;
+    bool split = false;  // intra-sequence synchronisation as two kernels
 };
 
 size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -191,6 +192,16 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         pl.img[i].qt_off = (uint32_t)i * 192u;
     }
     if (pl.nsub_total > 0x7FFFFFF0u || pl.tiles > 0x7FFFFFF0u) return JPGD_E_ARG;
+    // Intra-sequence synchronisation in two kernels: when the call has many more sequences than the chip holds at a
+    // time (three per CU with 1024-bit subsequences staged in LDS) and the staged stream is what limits that number.
+    // Measured on the 15360x8640 image (2320 sequences): 2.80 -> 2.65 ms per call; on calls the chip holds at once
+    // the second kernel only adds its launch.
+    {
+        const uint32_t mode = cfg ? cfg->sync_split : 0u;
+        if (mode > 2u) return JPGD_E_ARG;
+        const bool can = pl.bmap_words == 0u && pl.lut_slots <= 4u;
+        pl.split = can && (mode == 2u || (mode == 0u && L >= 512u && pl.seqs >= (uint32_t)kSplitMinSeqs));
+    }
 
     WsHeader& h = pl.h;
     memset(&h, 0, sizeof h);
@@ -209,6 +220,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     h.off_gpref = off;  off = up256(off + (size_t)pl.grps * 16);
     h.off_bmap = off;   off = up256(off + (size_t)pl.bmap_words * 4);
     h.off_warm = off;   off = up256(off + (size_t)pl.seqs * 4);
+    h.off_seqrec = off; off = up256(off + (pl.split ? (size_t)pl.seqs * kHandWords * 4u : 0u));
     h.total_bytes = off;
     return JPGD_OK;
 }
@@ -442,6 +454,8 @@ size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
     return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
 }
+// the second of the two synchronisation kernels keeps the tables and the records, not the stream
+size_t lds_tail_bytes(uint32_t lut_slots) { return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + 16; }
 size_t lds_write_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
     return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
@@ -556,7 +570,8 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
                                          (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
     if ((rc = grant_lds(c.device, c.variant, sync_kernels[c.variant], c.lds_sync)) ||
         (rc = grant_lds(c.device, c.staged ? 4 : 5, c.staged ? (const void*)k_write<true> : (const void*)k_write<false>, c.lds_write)) ||
-        (rc = grant_lds(c.device, 8, (const void*)k_sync_inter, c.lds_inter)))
+        (rc = grant_lds(c.device, 8, (const void*)k_sync_inter, c.lds_inter)) ||
+        (pl.split && c.staged && (rc = grant_lds(c.device, 6, (const void*)k_sync_head<true, false>, c.lds_sync))))
         return rc;
     rc = call_reserve(c, pl.h.upload_bytes + 16);
     if (rc) return rc;
@@ -608,6 +623,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     P.grp_pref = (int4*)(ws + pl.h.off_gpref);
     P.bmap = (uint32_t*)(ws + pl.h.off_bmap);
     P.warm_x = (uint32_t*)(ws + pl.h.off_warm);
+    P.seq_rec = (uint32_t*)(ws + pl.h.off_seqrec);
     P.luts = (const uint16_t*)(ws + pl.h.off_lut);
     P.qts = (const uint16_t*)(ws + pl.h.off_qt);
     P.coef = d_coef;
@@ -633,6 +649,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     }
     P.sync_waves = sync_waves;
     P.coop_max = kCoopMax * sync_waves / (uint32_t)(kWG / 64);
+    P.handoff = 0u;
     P.verdict = nullptr;
     P.ticket = 0u;
     P.up_src = (const uint4*)c.buf_dev;
@@ -660,6 +677,16 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     }
     if (big_tiles) LAUNCH(JPGD_K_UNSTUFF_SCAN, k_unstuff_scan, n, kWG, 0);
     LAUNCH(JPGD_K_UNSTUFF_SCATTER, k_unstuff_scatter, pl.tiles, kWG, 0);
+    if (pl.split) {
+        // first kernel: until at most kHandoff chains of a sequence are left; second kernel: the rest, four
+        // wavefronts per sequence, the chains from kCoopMax down one per wavefront
+        P.handoff = kHandoff;
+        if (c.staged) LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_head<true, false>), pl.seqs, kWG, c.lds_sync);
+        else LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_head<false, false>), pl.seqs, kWG, c.lds_sync);
+        P.sync_waves = (uint32_t)(kWG / 64);
+        P.coop_max = kCoopMax;
+        LAUNCH(JPGD_K_SYNC_TAIL, (k_sync_tail<false>), pl.seqs, kWG, lds_tail_bytes(pl.lut_slots));
+    } else
     switch (c.variant) {
         case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
         case 1: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<false, false>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
@@ -836,6 +863,7 @@ extern "C" int jpgd_init(void) {
                                          (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
     for (int v = 0; v < 4; ++v)
         if ((rc = grant_lds(dev, v, sync_kernels[v], lds_sync_bytes(2048u, kMaxSlots, v >= 2)))) break;
+    if (!rc) rc = grant_lds(dev, 6, (const void*)k_sync_head<true, false>, lds_sync_bytes(2048u, kMaxSlots, false));
     if (!rc) rc = grant_lds(dev, 4, (const void*)k_write<true>, lds_write_bytes(2048u, kMaxSlots, true));
     if (!rc) rc = grant_lds(dev, 5, (const void*)k_write<false>, lds_write_bytes(2048u, kMaxSlots, true));
     if (!rc) rc = grant_lds(dev, 8, (const void*)k_sync_inter, (size_t)kMaxSlots * kLutEntries * 2);

@@ -50,6 +50,11 @@ constexpr uint32_t kCoopMax = 6u;  // for the kWG / 64 wavefronts that hold the 
 // The workgroup may have more wavefronts than those: the others do nothing but take chains in these rounds, so
 // that fewer chains share a wavefront (a CU has 32 wavefront slots and a sequence's tail leaves most of them idle).
 constexpr int kSyncWavesMax = 16;
+// Intra-sequence synchronisation as two kernels: calls with at least this many sequences (twice what the chip holds
+// at a time with 1024-bit subsequences), and the number of running chains at which a sequence changes kernel
+// (48 and 64 are within a percent of each other on the 15360x8640 image; 100 and more lose the gain).
+constexpr int kSplitMinSeqs = 1536;
+constexpr uint32_t kHandoff = 48u;
 
 JPGD_HD bool lut_esc(uint32_t e) { return e >= 0x8000u; }
 JPGD_HD uint32_t lut_total(uint32_t e) { return e & 31u; }

@@ -24,6 +24,8 @@ struct Params {
     int4* grp_tot;          // per group of kWG subsequences: (units, dc0, dc1, dc2) totals
     int4* grp_pref;         // exclusive prefix of grp_tot inside the image
     uint32_t* bmap;         // interval-start bitmaps of images with restart intervals (ImgDesc::bmap_off)
+    uint32_t* seq_rec;      // split synchronisation: per sequence 4 x kWG words, the records of all its lanes after their
+                            // own subsequence (state, units, DC sums), handed from the first kernel to the second
     uint32_t* warm_x;       // per sequence: the state at its first subsequence's start that its records continue
                             // (packed like SInfo::x; 0xFFFFFFFF = none)
     const uint16_t* luts;
@@ -37,6 +39,7 @@ struct Params {
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     uint32_t scale_log2;    // pixel kernel: output at 1/2^scale_log2 of the size (0..3)
+    uint32_t handoff;       // intra-sequence kernel, split in two: chains left at which the first hands over (at most 64)
     uint32_t coop_max;      // intra-sequence kernel: with at most this many chains left, one wavefront per chain
     uint32_t sync_waves;    // wavefronts per workgroup of that kernel: kWG / 64 that hold the lanes, the rest only take chains
     // A call with one image has the last up_wgs workgroups of k_unstuff_count copy the call's parameter block
@@ -571,8 +574,19 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
 // workgroups share a CU (large subsequences).
 // RST: the call has images with restart intervals.  Calls without get a kernel with none of that code in it (the
 // intra-sequence kernel was measured 3 % slower on plain streams with it: registers and code layout).
-template <bool STAGED, bool RST>
-__global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
+// PHASE: kSyncAll = the whole of it in one kernel.  For calls with many more sequences than the chip holds at a time
+// the work is split in two kernels.  kSyncHead is the same code up to the round in which at most P.handoff chains
+// are still running; it leaves the records of all its lanes and the list of those chains in memory.  kSyncTail picks
+// them up and runs the remaining rounds with the lanes reading the stream from memory (a handful of chains, each
+// reading its words once).  The late rounds are chains of dependent symbols in a single wavefront or in one
+// wavefront per chain, and what keeps the chip busy then is the number of sequences in flight: without the staged
+// stream a workgroup needs a third of the LDS, and a CU holds eight of them instead of three.
+constexpr int kSyncAll = 0, kSyncHead = 1, kSyncTail = 2;
+constexpr uint32_t kHandMax = 128u;       // most chains a sequence may hand over
+constexpr uint32_t kHandWords = 6u * kWG;  // per sequence: 4 x kWG record words, 3 x kHandMax chain words, the chain count
+template <bool STAGED, bool RST, int PHASE>
+__device__ __forceinline__ void sync_intra_body(const Params& P) {
+    static_assert(PHASE != kSyncTail || !STAGED, "the second kernel reads the stream from memory");
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
@@ -622,7 +636,30 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
     Lane l;
     BitWin w;
     int64_t dcacc = 0;
-    if (valid) {
+    uint32_t* handed = P.seq_rec + (size_t)wg * kHandWords;
+    bool active = false;
+    uint32_t tt = t + 1u;
+    uint32_t waves_used = kWG / 64u;
+    if (PHASE == kSyncTail) {
+        // the records the first kernel left, and the chains that were still running
+        if (valid) {
+            sw[t] = handed[t];
+            pnb[t] = handed[kWG + t];
+            pdc01[t] = handed[2 * kWG + t];
+            pdc2[t] = handed[3 * kWG + t];
+        }
+        const uint32_t n = handed[4u * kWG + 384u];
+        active = t < n;
+        if (active) {
+            l.p = handed[4u * kWG + t];
+            const uint32_t uz = handed[4u * kWG + 128u + t];
+            l.u = uz >> 8;
+            l.z = uz & 255u;
+            l.nb = 0u;
+            tt = handed[4u * kWG + 256u + t];
+        }
+        waves_used = (n + 63u) >> 6; if (waves_used == 0u) waves_used = 1u;
+    } else if (valid) {
         const uint32_t i = (uint32_t)(base + (int32_t)t);
         l.p = i << P.logL; l.u = 0u; l.z = 0u; l.nb = 0u;
         win_init(w, l.p, (l.p >> 5) - first_word, fetch);
@@ -635,6 +672,7 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
         pnb[t] = l.nb | (crossed << 31);
         pdc01[t] = pack_dc01(dcacc);
         pdc2[t] = pack_dc2(dcacc);
+        active = t + 1u < t1;
     }
     // Overflow rounds: in round r the chain that started at subsequence c decodes subsequence c+r from its own
     // state and compares with the record left there one round earlier by the chain that started at c+1.
@@ -642,14 +680,12 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
     // that frees a whole wavefront: a chain is (p, u, z, target), everything else is rebuilt from the staged
     // stream, so moving one costs three LDS words.  Between packings a round costs one barrier: the count of
     // running chains goes through one LDS word per wavefront, double-buffered by the parity of the round.
-    bool active = valid && (t + 1u < t1);
-    uint32_t tt = t + 1u;
-    uint32_t waves_used = kWG / 64u;
     // The wavefront-per-chain code does not know more than four tables.  In a workgroup that sees restart intervals
     // a chain may fall back to a single lane for a round (below): at most one chain per wavefront then, so that
     // such rounds never take longer than the packed ones they replace.
     const uint32_t coop_max = P.lut_slots > 4u ? 0u : (restart ? min(P.coop_max, P.sync_waves) : P.coop_max);
     uint32_t coop_n = 0u;
+    bool first_tail_round = PHASE == kSyncTail;
     for (uint32_t round = 0u;; ++round) {
         const uint64_t bal = __ballot(active);
         uint32_t* cnt = scratch + ((round & 1u) << 2);
@@ -657,6 +693,24 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
         __syncthreads();  // also orders the records written in the previous round before their readers
         const uint32_t c0 = cnt[0], c1 = cnt[1], c2 = cnt[2], c3 = cnt[3];
         const uint32_t now = c0 + c1 + c2 + c3;
+        if (PHASE == kSyncHead && now <= P.handoff) {  // the rest is the second kernel's
+            const uint32_t wave = t >> 6;
+            const uint32_t before = wave == 0u ? 0u : wave == 1u ? c0 : wave == 2u ? c0 + c1 : c0 + c1 + c2;
+            const uint32_t rank = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            if (active) {
+                handed[4u * kWG + rank] = l.p;
+                handed[4u * kWG + 128u + rank] = (l.u << 8) | l.z;
+                handed[4u * kWG + 256u + rank] = tt;
+            }
+            if (t == 0u) handed[4u * kWG + 384u] = now;
+            if (valid) {
+                handed[t] = sw[t];
+                handed[kWG + t] = pnb[t];
+                handed[2 * kWG + t] = pdc01[t];
+                handed[3 * kWG + t] = pdc2[t];
+            }
+            return;
+        }
         if (now == 0u) break;
         if (now <= coop_max) {  // few chains left: hand them to whole wavefronts (below)
             const uint32_t wave = t >> 6;
@@ -698,6 +752,10 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
             dcacc = 0;
             const uint32_t limit = ((uint32_t)(base + (int32_t)tt) + 1u) << P.logL;
             uint32_t crossed = 0u;
+            if (PHASE == kSyncTail && first_tail_round) {
+                win_init(w, l.p, (l.p >> 5) - first_word, fetch);
+                prime(l, w, sx, lut_s);
+            }
             if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
             else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
             const uint32_t x = pack_state(l.p - limit, l.z, l.u);
@@ -709,6 +767,7 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
             ++tt;
             active = !synced && tt < t1;
         }
+        first_tail_round = false;
     }
     // The same rounds with one chain per wavefront.  The chains keep their slot k < coop_n in a list held twice
     // (read from one copy, written to the other, swapped every round; mv_tt = kCoopDone once a chain has
@@ -794,6 +853,19 @@ __global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
     // in that very state, the two sequences already form one chain and the inter-sequence kernel has nothing
     // to decode at this boundary.
     if (t == 0u) P.warm_x[wg] = (P.overlap > 0u && P.overlap - 1u >= t0) ? sw[P.overlap - 1u] : 0xFFFFFFFFu;
+}
+
+template <bool STAGED, bool RST>
+__global__ __launch_bounds__(64 * kSyncWavesMax) void k_sync_intra(Params P) {
+    sync_intra_body<STAGED, RST, kSyncAll>(P);
+}
+template <bool STAGED, bool RST>
+__global__ __launch_bounds__(kWG) void k_sync_head(Params P) {
+    sync_intra_body<STAGED, RST, kSyncHead>(P);
+}
+template <bool RST>
+__global__ __launch_bounds__(kWG) void k_sync_tail(Params P) {
+    sync_intra_body<false, RST, kSyncTail>(P);
 }
 
 // ---- synchronisation, inter-sequence (paper, Algorithm 3, second loop) ------------------------------

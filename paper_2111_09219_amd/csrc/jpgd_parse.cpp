@@ -169,4 +169,4 @@ extern "C" const char* jpgd_strerror(int status) {
     }
 }
 
-extern "C" int jpgd_abi_version(void) { return 1; }
+extern "C" int jpgd_abi_version(void) { return 2; }

@@ -538,6 +538,54 @@ def test_output_buffers_need_not_be_cleared():
             _check_image(b2, 0, other)
 
 
+def test_synchronisation_split_in_two_kernels():
+    """jpgd_config.sync_split = 2: the intra-sequence rounds run as two kernels (the second takes over the chains a
+    sequence has left and reads the stream from memory).  Records, coefficients and pixels must be what the single
+    kernel and the oracle give: all layouts, small and large subsequences, overlaps, sequences that finish before the
+    hand-over and sequences that hand over their full share of chains, a batch, and the regime of many
+    inter-sequence rounds.  Calls the split does not cover (restart intervals, more than four tables) fall back."""
+    cases = [("420", False, 93, 1024, None), ("420", True, 97, 128, None), ("444", True, 96, 128, 0), ("gray", False, 80, 256, 64),
+             ("422", False, 60, 512, None), ("420", False, 100, 2048, 8)]
+    files = []
+    for k, (sub, opt, q, L, ov) in enumerate(cases):
+        px = small_image(310 + k, 480, 640, ncomp=1 if sub == "gray" else 3, sigma=12.0 + 10 * k)
+        data = encode_jpeg(px, q, sub, opt).data
+        files.append(data)
+        cfg = dict(subseq_bits=L, sync_split=2)
+        if ov is not None:
+            cfg["overlap"] = ov
+        batch, rep = _decode([data], **cfg)
+        assert rep.launches[J.KERNELS.index("sync_tail")] == 1
+        o = _check_image(batch, 0, data)
+        rec = J.jpgd_read_sync_info(batch.d_workspace, 0, rep.n_subseq + 8)
+        bs = o.boundary_states(L)
+        n = len(bs["p"])
+        live = np.cumsum(bs["units"]) < o.total_units
+        assert np.array_equal(rec["p"][:n][live].astype(np.int64), bs["p"][live])
+        assert np.array_equal(rec["u"][:n][live], bs["u"][live]) and np.array_equal(rec["z"][:n][live], bs["z"][live])
+        assert np.array_equal(rec["units"][:n][live], bs["units"][live])
+        assert np.array_equal(rec["dcsum"][:n][live].astype(np.int16), bs["dcsum"][live].astype(np.int16))
+    batch, rep = _decode(files, sync_split=2)
+    for i, f in enumerate(files):
+        _check_image(batch, i, f)
+    # many inter-sequence rounds
+    data = encode_jpeg(small_image(16352, 303, 231, sigma=80.0), 100, "420", False).data
+    batch, rep = _decode([data], subseq_bits=128, sync_split=2)
+    assert rep.inter_rounds >= 3
+    _check_image(batch, 0, data)
+    # tiny images: one sequence, fewer chains than the hand-over threshold from the start
+    tiny = encode_jpeg(small_image(3, 16, 24, sigma=5.0), 80, "420").data
+    batch, rep = _decode([tiny], sync_split=2)
+    _check_image(batch, 0, tiny)
+    # not covered by the split: falls back to the single kernel
+    rst = encode_jpeg(small_image(8, 200, 333, sigma=12.0), 92, "422", False, restart_interval=5).data
+    batch, rep = _decode([rst], sync_split=2)
+    assert rep.launches[J.KERNELS.index("sync_tail")] == 0
+    _check_image(batch, 0, rst)
+    with pytest.raises(J.JpgdError):
+        J.jpgd_workspace_bytes([J.jpgd_parse(tiny)], J.Config.make(sync_split=3))
+
+
 def test_dense_and_sparse_stretches_in_one_image():
     """The write pass treats a workgroup's stretch of the output in one of two ways: where data units are dense the
     lanes lay down the zeros of their own ranges, where they are sparse the workgroup clears its stretch first.

@@ -30,7 +30,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     lib = ctypes.CDLL(J.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
-    assert lib.jpgd_abi_version() == 1
+    assert lib.jpgd_abi_version() == 2
     lib.jpgd_strerror.restype = ctypes.c_char_p
     assert b"corrupt" not in lib.jpgd_strerror(0) and lib.jpgd_strerror(-6)
     # the product must not link the oracle or the input encoder
