@@ -27,10 +27,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 # rocprofv3 kernel names of the kernels bench.py reports on (prefixes of the names in profiles/*.md)
-PROFILE_NAMES = {"unstuff_count": "jpgd::k_unstuff_count", "unstuff_scan": "jpgd::k_unstuff_scan",
-                 "unstuff_scatter": "jpgd::k_unstuff_scatter", "sync_intra": "jpgd::k_sync_intra", "sync_tail": "jpgd::k_sync_intra",
-                 "sync_inter": "jpgd::k_sync_inter", "scan_totals": "jpgd::k_group_totals",
-                 "scan_prefix": "jpgd::k_group_scan", "write": "jpgd::k_write", "pixels": "jpgd::k_pixels"}
+# (the intra-sequence synchronisation is one kernel, k_sync_intra, or, for calls with very many sequences, two that
+# share its work, k_sync_head and k_sync_tail: bench.py reports them as one stage, "sync_intra")
+PROFILE_NAMES = {"unstuff_count": ("jpgd::k_unstuff_count",), "unstuff_scan": ("jpgd::k_unstuff_scan",),
+                 "unstuff_scatter": ("jpgd::k_unstuff_scatter",),
+                 "sync_intra": ("jpgd::k_sync_intra", "jpgd::k_sync_head", "jpgd::k_sync_tail"),
+                 "sync_inter": ("jpgd::k_sync_inter",), "scan_totals": ("jpgd::k_group_totals",),
+                 "scan_prefix": ("jpgd::k_group_scan",), "write": ("jpgd::k_write",), "pixels": ("jpgd::k_pixels",)}
 PROFILE_FILES = {1: "decode_path_gray256_q75.md", 2: "decode_path_hd1088_444_q90.md", 3: "decode_path_4k_420_q95_opt.md",
                  4: "decode_path_batch256_420.md", 5: "decode_path_uhd16k_420_q92.md"}
 
@@ -45,7 +48,6 @@ def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: i
         "unstuff_scan": 8 * (Bs // 4096 + 1),
         "unstuff_scatter": Bs + B,
         "sync_intra": B + 8 * S,
-        "sync_tail": 8 * S,
         "sync_inter": 8 * (S // 256 + 1),
         "scan_totals": 8 * S,
         "scan_prefix": 32 * (S // 256 + 1),
@@ -86,9 +88,9 @@ def profile_traffic(config: int):
                 continue
             cells = [c.strip() for c in line.strip("|").split("|")]
             if len(cells) == 5 and not cells[0].startswith("-"):
-                for short, prefix in PROFILE_NAMES.items():
-                    if cells[0] == prefix or cells[0].startswith(prefix + "<"):
-                        out[short] = (float(cells[3]) + float(cells[4])) * 1e6
+                for short, prefixes in PROFILE_NAMES.items():
+                    if any(cells[0] == pre or cells[0].startswith(pre + "<") for pre in prefixes):
+                        out[short] = out.get(short, 0.0) + (float(cells[3]) + float(cells[4])) * 1e6
     return out, stale
 
 
@@ -137,11 +139,18 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
         else:
             rep = batch.decode()
     split /= nsplit
+    # the two kernels of a split intra-sequence synchronisation count as the one stage they are
+    i_intra, i_tail = J.KERNELS.index("sync_intra"), J.KERNELS.index("sync_tail")
+    two_kernels = rep.launches[i_tail] > 0
+    sync_parts = {"k_sync_head_ms": round(float(split[i_intra]), 5), "k_sync_tail_ms": round(float(split[i_tail]), 5)} if two_kernels else None
+    split[i_intra] += split[i_tail]
+    split[i_tail] = 0.0
     dominant = int(np.argmax(split))
     S = rep.n_subseq
     B = Bs  # the unstuffed length is within 0.5 % of the stuffed one; the bound is used for the byte counts
 
-    cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=ov, flags=flags, timing_mask=1 << dominant)
+    dom_mask = (1 << dominant) | ((1 << i_tail) if dominant == i_intra else 0)
+    cfg_dom = J.Config.make(subseq_bits=args.subseq_bits, overlap=ov, flags=flags, timing_mask=dom_mask)
     dom_ms, dom_launches = 0.0, 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -150,7 +159,7 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
         # step of the timed region: the two event records cost the stream about ten microseconds
         if bracket_dominant and k % 4 == 0:
             rep = batch.decode(cfg=cfg_dom)
-            dom_ms += rep.kernel_ms[dominant]
+            dom_ms += rep.kernel_ms[dominant] + (rep.kernel_ms[i_tail] if dominant == i_intra else 0.0)
             dom_launches += rep.launches[dominant]
         else:
             rep = batch.decode(cfg=cfg)
@@ -162,12 +171,14 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
                                                 or args.limit or args.overlap >= 0) else ({}, None)
     kernels = {}
     for k, name in enumerate(J.KERNELS):
-        if rep.launches[k] == 0:
+        if rep.launches[k] == 0 or k == i_tail:
             continue
         ab = algorithmic_bytes(name, Bs, B, S, K, out_bytes)
         gbs = ab / 1e9 / (split[k] / 1e3) if split[k] > 0 else 0.0
         kernels[name] = {"ms": round(float(split[k]), 5), "alg_bytes": ab, "achieved_gbs": round(gbs, 2),
                          "frac": round(gbs / HBM_PEAK_GBS, 5), "traffic": traffic.get(name)}
+        if name == "sync_intra" and sync_parts:
+            kernels[name]["two_kernels"] = sync_parts
     res = {
         "config": c, "wl": wl, "ri": ri, "files": files, "batch": batch, "rep": rep, "cfg": cfg,
         "Bs": Bs, "B": B, "S": S, "K": K, "out_bytes": out_bytes, "pixels": batch.pixels_total,

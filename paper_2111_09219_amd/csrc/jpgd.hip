@@ -96,6 +96,7 @@ uint32_t choose_subseq_bits(const jpgd_info* infos, int n) {
 int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     if (!infos || n < 1) return JPGD_E_ARG;
     pl = Plan();  // (a slot's plan is used again by the slot's next call)
+    const bool scaled = cfg && ((cfg->flags >> 2) & 3u) != 0u;  // reduced-size pixels: larger runs per workgroup
     uint32_t L = cfg && cfg->subseq_bits ? cfg->subseq_bits : choose_subseq_bits(infos, n);
     if (L < 128u || L > 2048u || (L & (L - 1u))) return JPGD_E_ARG;
     // default overlap: enough warm-up lanes that the chain entering a sequence is almost always synchronised,
@@ -148,7 +149,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         d.mcus_x = in.mcus_x; d.mcus_y = in.mcus_y;
         if (d.upm != (in.ncomp == 1 ? 1u : d.hs * d.vs + 2u)) return JPGD_E_ARG;
         if ((uint64_t)d.mcus_x * d.mcus_y * d.upm != d.total_units) return JPGD_E_ARG;
-        const uint32_t M = kPixBlocks / d.upm;
+        const uint32_t M = (uint32_t)(scaled ? kPixBlocksScaled : kPixBlocks) / d.upm;
         d.pix_runs = (d.mcus_x + M - 1) / M;
         d.pix_wg0 = pl.pixwgs;
         if ((uint64_t)pl.pixwgs + (uint64_t)d.pix_runs * d.mcus_y > 0x7FFFFFFFull) return JPGD_E_ARG;  // grid size

@@ -155,6 +155,7 @@ struct Status {
 constexpr uint32_t kDenseBitsPerUnit = 256u;
 constexpr int kUnstuffTile = 4096;  // bytes per workgroup of the unstuff kernels (256 lanes x 16 bytes)
 constexpr int kPixBlocks = 48;      // data units per workgroup of the pixel kernel
+constexpr int kPixBlocksScaled = 192;  // ... of the reduced-size pixel kernels (a unit needs 16, 4 or 1 floats of LDS there)
 
 JPGD_HD uint32_t align_up(uint32_t v, uint32_t a) { return (v + a - 1) / a * a; }
 

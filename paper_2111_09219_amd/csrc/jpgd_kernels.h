@@ -1405,6 +1405,16 @@ __global__ __launch_bounds__(kWG) void k_pixels(Params P) {
 // and names it as the stage that now limits the decoder; this path reads the same coefficients and skips most of it.)
 
 // c_basis*[x * N + u] = 1/2 C(u) cos((2x+1) u pi / (2N))
+#define JPGD_BASIS4_LITERAL                                                                            \
+    {0.35355339059327379f, 0.46193976625564337f, 0.35355339059327379f, 0.19134171618254489f,            \
+     0.35355339059327379f, 0.19134171618254489f, -0.35355339059327379f, -0.46193976625564337f,          \
+     0.35355339059327379f, -0.19134171618254489f, -0.35355339059327379f, 0.46193976625564337f,          \
+     0.35355339059327379f, -0.46193976625564337f, 0.35355339059327379f, -0.19134171618254489f}
+#define JPGD_BASIS2_LITERAL {0.35355339059327379f, 0.35355339059327379f, 0.35355339059327379f, -0.35355339059327379f}
+// (the same values twice: as compile-time constants for sums whose position is unrolled, and in constant memory for
+// the table a lane indexes with its row)
+constexpr float c_basis4_host[16] = JPGD_BASIS4_LITERAL;
+constexpr float c_basis2_host[4] = JPGD_BASIS2_LITERAL;
 __device__ __constant__ float c_basis4[16] = {
     0.35355339059327379f, 0.46193976625564337f, 0.35355339059327379f, 0.19134171618254489f,
     0.35355339059327379f, 0.19134171618254489f, -0.35355339059327379f, -0.46193976625564337f,
@@ -1413,22 +1423,30 @@ __device__ __constant__ float c_basis4[16] = {
 __device__ __constant__ float c_basis2[4] = {0.35355339059327379f, 0.35355339059327379f,
                                              0.35355339059327379f, -0.35355339059327379f};
 
+// natural (row-major) position -> zig-zag position: the inverse of the zig-zag literal, made at compile time
+struct UnZigzag {
+    uint8_t at[64];
+    constexpr UnZigzag() : at{} {
+        constexpr uint8_t zz[64] = JPGD_ZIGZAG_LITERAL;
+        for (int i = 0; i < 64; ++i) at[zz[i]] = (uint8_t)i;
+    }
+};
+__device__ __constant__ UnZigzag c_unzigzag = UnZigzag();
+
 template <int N>
 __global__ __launch_bounds__(kWG) void k_pixels_scaled(Params P) {
     constexpr uint32_t NN = N * N;
     constexpr uint32_t lN = N == 4 ? 2u : (N == 2 ? 1u : 0u);   // log2 N
-    __shared__ float fin[kPixBlocks * NN];   // dequantised low frequencies, [unit][v * N + u]
-    __shared__ float smp[kPixBlocks * NN];   // samples, level shift applied, [unit][y * N + x]
-    __shared__ float qf[3 * NN];
+    __shared__ float fin[kPixBlocksScaled * NN];   // dequantised low frequencies, [unit][v * N + u]
+    __shared__ float smp[kPixBlocksScaled * NN];   // samples, level shift applied, [unit][y * N + x]
     __shared__ float bs[NN];
-    __shared__ uint32_t zpos[NN];            // zig-zag position of frequency (v, u)
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.pix_wg0; });
     const ImgDesc D = image_desc_uniform(P, ii);
     const uint32_t lw = wg - D.pix_wg0;
     const uint32_t mrow = lw / D.pix_runs, run = lw % D.pix_runs;
     const uint32_t upm = D.upm;
-    const uint32_t M = (uint32_t)kPixBlocks / upm;
+    const uint32_t M = (uint32_t)kPixBlocksScaled / upm;
     const uint32_t m0 = run * M;
     const uint32_t nm = min(M, D.mcus_x - m0);
     const uint32_t nblk = nm * upm;
@@ -1441,34 +1459,42 @@ __global__ __launch_bounds__(kWG) void k_pixels_scaled(Params P) {
         __threadfence_system();
         host[15] = P.ticket;
     }
-    if (t < 64u) {
-        const uint32_t rc = c_zigzag[t];
-        if ((rc >> 3) < (uint32_t)N && (rc & 7u) < (uint32_t)N) zpos[(rc >> 3) * N + (rc & 7u)] = t;
-    }
     if (t < NN) bs[t] = N == 4 ? c_basis4[t] : (N == 2 ? c_basis2[t & 3u] : 0.35355339059327379f);
-    __syncthreads();
-    if (t < 3u * NN) qf[t] = (float)P.qts[D.qt_off + (t / NN) * 64u + zpos[t % NN]];
-    __syncthreads();
+    // A lane always fetches the same frequency (256 is a multiple of N * N): its zig-zag position is looked up once.
+    const uint32_t e = t & (NN - 1u);
+    const uint32_t zpos = c_unzigzag.at[(e >> lN) * 8u + (e & (N - 1u))];
     const int16_t* coef = P.coef + D.coef_off + (size_t)((size_t)mrow * D.mcus_x + m0) * upm * 64u;
+    const uint16_t* qt = P.qts + D.qt_off + zpos;
+    const float q0 = (float)qt[0], q1 = (float)qt[64], q2 = (float)qt[128];
     for (uint32_t j = t; j < nblk * NN; j += kWG) {
-        const uint32_t k = j >> (2u * lN), e = j & (NN - 1u);
+        const uint32_t k = j >> (2u * lN);
         const uint32_t ku = upm == 1u ? 0u : (upm == 3u ? k % 3u : (upm == 4u ? (k & 3u) : k % 6u));
         const uint32_t comp = (D.sched_comp >> (ku * 4u)) & 15u;
-        fin[j] = (float)coef[(size_t)k * 64u + zpos[e]] * qf[comp * NN + e];
+        fin[j] = (float)coef[(size_t)k * 64u + zpos] * (comp == 0u ? q0 : (comp == 1u ? q1 : q2));
     }
     __syncthreads();
-    for (uint32_t j = t; j < nblk * NN; j += kWG) {
-        const uint32_t k = j >> (2u * lN), y = (j >> lN) & (N - 1u), x = j & (N - 1u);
+    // one lane per row of a unit's N x N samples: first the sum over the vertical frequencies for its row (weights
+    // from the basis table in LDS, they depend on the row), then the N outputs (weights are constants)
+    for (uint32_t j = t; j < nblk * N; j += kWG) {
+        const uint32_t k = j >> lN, y = j & (N - 1u);
         const float* F = fin + k * NN;
-        float acc = 128.0f;
+        float g[N];
+#pragma unroll
+        for (uint32_t u = 0; u < (uint32_t)N; ++u) g[u] = 0.0f;
 #pragma unroll
         for (uint32_t v = 0; v < (uint32_t)N; ++v) {
-            float row = 0.0f;
+            const float w = bs[y * N + v];
 #pragma unroll
-            for (uint32_t u = 0; u < (uint32_t)N; ++u) row = __builtin_fmaf(bs[x * N + u], F[v * N + u], row);
-            acc = __builtin_fmaf(bs[y * N + v], row, acc);
+            for (uint32_t u = 0; u < (uint32_t)N; ++u) g[u] = __builtin_fmaf(w, F[v * N + u], g[u]);
         }
-        smp[j] = acc;
+#pragma unroll
+        for (uint32_t x = 0; x < (uint32_t)N; ++x) {
+            float acc = 128.0f;
+#pragma unroll
+            for (uint32_t u = 0; u < (uint32_t)N; ++u)
+                acc = __builtin_fmaf(N == 4 ? c_basis4_host[x * 4u + u] : (N == 2 ? c_basis2_host[(x * 2u + u) & 3u] : 0.35355339059327379f), g[u], acc);
+            smp[k * NN + y * N + x] = acc;
+        }
     }
     __syncthreads();
 
