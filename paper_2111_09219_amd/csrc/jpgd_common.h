@@ -55,6 +55,9 @@ constexpr int kSyncWavesMax = 16;
 // (48 and 64 are within a percent of each other on the 15360x8640 image; 100 and more lose the gain).
 constexpr int kSplitMinSeqs = 1536;
 constexpr uint32_t kHandoff = 48u;
+// Inter-sequence kernel: a workgroup with at most this many boundaries to decode from walks them with the whole
+// wavefront, one after the other (the walk takes about half the time of a lane's loop per subsequence).
+constexpr int kInterCoopMax = 2;
 
 JPGD_HD bool lut_esc(uint32_t e) { return e >= 0x8000u; }
 JPGD_HD uint32_t lut_total(uint32_t e) { return e & 31u; }

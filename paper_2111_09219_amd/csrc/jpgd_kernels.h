@@ -899,10 +899,49 @@ __global__ __launch_bounds__(64) void k_sync_inter(Params P) {
     stage_luts(P, D, lut_s);
     const Syntax sx = stage_syntax(D, rows);
     __syncthreads();
-    if (!work) return;
-    const uint32_t gend = min(nsub, g + P.seq_len);
     const uint32_t* words = reinterpret_cast<const uint32_t*>(P.stream + D.stream_off);
     auto fetch = [&](uint32_t w) { return __builtin_bswap32(words[w]); };
+    // Usually a handful of boundaries in a whole image have something to decode, and the kernel lasts as long as
+    // the slowest of them.  With few in this workgroup, each is walked by the whole wavefront, one after the other
+    // (same results as the lane's loop below; the wavefront's decoder does not know restart intervals).
+    const uint64_t workers = __ballot(work);
+    if (!D.restart && P.lut_slots <= 4u && __popcll(workers) <= kInterCoopMax) {
+        const uint32_t lane = threadIdx.x;
+        const uint32_t unit_word = coop_unit_word(sx, lane);
+        const uint32_t u_upm = __builtin_amdgcn_readfirstlane(sx.upm);
+        const uint32_t u_nsub = __builtin_amdgcn_readfirstlane(nsub);
+        const uint32_t u_nwords = (u_nsub << (P.logL - 5u)) + 4u;
+        for (uint64_t m = workers; m; m &= m - 1ull) {
+            const uint32_t k = (uint32_t)__ffsll((long long)m) - 1u;
+            uint32_t cg = __builtin_amdgcn_readlane(g, k);
+            const uint32_t cx0 = __builtin_amdgcn_readlane(x0, k);
+            const uint32_t cend = min(u_nsub, cg + P.seq_len);
+            uint32_t cp = (cg << P.logL) + state_prel(cx0), cz = state_z(cx0), cu = state_u(cx0);
+            bool first = true;
+            for (;;) {
+                uint32_t cnb = 0u;
+                int64_t cdc = 0;
+                const uint32_t limit = (cg + 1u) << P.logL;
+                coop_span_sync(cp, cu, cz, cnb, cdc, limit, 0u, u_nwords, unit_word, u_upm, P.lut_slots, fetch, lut_s);
+                const uint32_t x = pack_state(cp - limit, cz, cu);
+                const bool synced = x == __atomic_load_n(&rec[cg].x, __ATOMIC_RELAXED);
+                if (lane == 0u) {
+                    if (first && !synced) atomicAdd(&P.status->inter_changed, 1u);
+                    rec[cg].y = cnb;
+                    rec[cg].z = pack_dc01(cdc);
+                    rec[cg].w = pack_dc2(cdc);
+                    __atomic_store_n(&rec[cg].x, x, __ATOMIC_RELAXED);
+                }
+                first = false;
+                ++cg;
+                if (synced || cg >= cend) break;
+            }
+        }
+        if (work) *warm = x0;
+        return;
+    }
+    if (!work) return;
+    const uint32_t gend = min(nsub, g + P.seq_len);
     const uint32_t* bmap_img = P.bmap + D.bmap_off;
     auto bword = [&](uint32_t k) { return bmap_img[k]; };
     Lane l;
