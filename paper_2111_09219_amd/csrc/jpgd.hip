@@ -33,7 +33,7 @@ struct Plan {
     WsHeader h;
     std::vector<ImgDesc> img;
     std::vector<uint32_t> lut_of_img;  // index of the table set of image i
-    uint32_t nsets = 0, lut_slots = 0;
+    uint32_t nsets = 0, lut_slots = 0, pair_slots = 0;
     uint32_t tiles = 0, seqs = 0, grps = 0, bnds = 0, pixwgs = 0, nsub_total = 0;
     uint32_t bmap_words = 0;  // interval-start bitmaps of the images that have restart intervals
     uint32_t L = 0;
@@ -169,6 +169,8 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
             comp_ac[c] = k;
         }
         d.nslots = ndc + nac;
+        d.ndc = ndc;
+        if (nac > pl.pair_slots) pl.pair_slots = nac;
         d.sched_dc = d.sched_ac = d.sched_comp = 0;
         uint32_t u = 0;
         for (uint32_t c = 0; c < in.ncomp; ++c) {
@@ -189,7 +191,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
         if (d.nslots > pl.lut_slots) pl.lut_slots = d.nslots;
     }
     for (int i = 0; i < n; ++i) {
-        pl.img[i].lut_off = pl.lut_of_img[i] * (uint32_t)kMaxSlots * kLutEntries;
+        pl.img[i].lut_off = pl.lut_of_img[i] * (uint32_t)kLutSetEntries;
         pl.img[i].qt_off = (uint32_t)i * 192u;
     }
     if (pl.nsub_total > 0x7FFFFFF0u || pl.tiles > 0x7FFFFFF0u) return JPGD_E_ARG;
@@ -211,7 +213,7 @@ int make_plan(const jpgd_info* infos, int n, const jpgd_config* cfg, Plan& pl) {
     h.off_status = off; off = up256(off + sizeof(Status));
     h.off_state = off;  off = up256(off + sizeof(ImgState) * (size_t)n);
     h.off_img = off;    off = up256(off + sizeof(ImgDesc) * (size_t)n);
-    h.off_lut = off;    off = up256(off + (size_t)pl.nsets * kMaxSlots * kLutEntries * 2);
+    h.off_lut = off;    off = up256(off + (size_t)pl.nsets * kLutSetEntries * 2);
     h.off_qt = off;     off = up256(off + (size_t)n * 192 * 2);
     h.upload_bytes = off;
     h.off_tiles = off;  off = up256(off + (size_t)pl.tiles * 4);
@@ -368,13 +370,15 @@ struct LutCacheEntry {
     uint32_t nvals;
     uint64_t stamp;
     uint16_t lut[kLutEntries];
+    uint8_t pairs[kPairBytes];  // AC tables
 };
 std::mutex g_lut_mu;
 std::vector<LutCacheEntry> g_lut_cache;
 uint64_t g_lut_clock = 0;
 constexpr size_t kLutCacheMax = 32;
 
-bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_t* out) {
+// pairs: where the pair bytes of an AC table go (null for a DC table)
+bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_t* out, uint8_t* pairs) {
     uint32_t nvals = 0;
     for (int k = 0; k < 16; ++k) nvals += bits[k];
     if (nvals > 256u) return false;
@@ -383,9 +387,11 @@ bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_
         if (e.is_dc == is_dc && e.nvals == nvals && !memcmp(e.bits, bits, 16) && !memcmp(e.vals, vals, nvals)) {
             e.stamp = ++g_lut_clock;
             memcpy(out, e.lut, sizeof e.lut);
+            if (pairs) memcpy(pairs, e.pairs, sizeof e.pairs);
             return true;
         }
     if (!build_lut(bits, vals, is_dc, out)) return false;
+    if (pairs) build_pairs(out, pairs);
     LutCacheEntry* victim;
     if (g_lut_cache.size() < kLutCacheMax) {
         g_lut_cache.emplace_back();
@@ -401,6 +407,7 @@ bool cached_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, uint16_
     victim->nvals = nvals;
     victim->stamp = ++g_lut_clock;
     memcpy(victim->lut, out, sizeof victim->lut);
+    if (pairs) memcpy(victim->pairs, pairs, sizeof victim->pairs);
     return true;
 }
 
@@ -451,12 +458,16 @@ uint32_t staged_max_bits() {
 size_t lds_bitmap_bytes(uint32_t L, bool restart) {
     return restart && L <= (uint32_t)kBitmapLdsMaxL ? ((size_t)(kWG * (L / 32) + 4 + 7) / 8 + 2) * 4 : 0;
 }
-size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
+// (the kernels for calls without restart intervals also keep the pair bytes of the AC tables)
+size_t lds_sync_bytes(uint32_t L, uint32_t lut_slots, uint32_t pair_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
-    return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
+    return (size_t)lut_slots * kLutEntries * 2 + (restart ? 0 : (size_t)pair_slots * kPairBytes) + 6 * kWG * 4 +
+           (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
 }
 // the second of the two synchronisation kernels keeps the tables and the records, not the stream
-size_t lds_tail_bytes(uint32_t lut_slots) { return (size_t)lut_slots * kLutEntries * 2 + 7 * kWG * 4 + 16; }
+size_t lds_tail_bytes(uint32_t lut_slots, uint32_t pair_slots) {
+    return (size_t)lut_slots * kLutEntries * 2 + (size_t)pair_slots * kPairBytes + 4 * kWG * 4 + 2 * kHandMax * 4 + 16;
+}
 size_t lds_write_bytes(uint32_t L, uint32_t lut_slots, bool restart) {
     uint32_t nwords = L <= kStagedMaxL ? kWG * (L / 32) + 4 : 4;
     return (size_t)lut_slots * kLutEntries * 2 + (size_t)nwords * 4 + lds_bitmap_bytes(L, restart);
@@ -560,7 +571,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     c.stream = stream;
     c.ws = (uint8_t*)d_workspace;
     const bool any_restart = pl.bmap_words != 0u;
-    c.lds_sync = lds_sync_bytes(pl.L, pl.lut_slots, any_restart);
+    c.lds_sync = lds_sync_bytes(pl.L, pl.lut_slots, pl.pair_slots, any_restart);
     c.lds_write = lds_write_bytes(pl.L, pl.lut_slots, any_restart);
     c.lds_inter = (size_t)pl.lut_slots * kLutEntries * 2;
     if (c.lds_sync > 150 * 1024) return JPGD_E_ARG;
@@ -592,11 +603,12 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
                 uint32_t cc = (d.sched_comp >> (4 * u)) & 15u;
                 uint32_t sd = (d.sched_dc >> (4 * u)) & 15u, sa = (d.sched_ac >> (4 * u)) & 15u;
                 if (!(built & (1u << sd)) &&
-                    !cached_lut(in.dht_bits[0][in.td[cc]], in.dht_vals[0][in.td[cc]], true, set + sd * kLutEntries))
+                    !cached_lut(in.dht_bits[0][in.td[cc]], in.dht_vals[0][in.td[cc]], true, set + sd * kLutEntries, nullptr))
                     return JPGD_E_TABLE;
                 built |= 1u << sd;
                 if (!(built & (1u << sa)) &&
-                    !cached_lut(in.dht_bits[1][in.ta[cc]], in.dht_vals[1][in.ta[cc]], false, set + sa * kLutEntries))
+                    !cached_lut(in.dht_bits[1][in.ta[cc]], in.dht_vals[1][in.ta[cc]], false, set + sa * kLutEntries,
+                                (uint8_t*)(set + kMaxSlots * kLutEntries) + (sa - d.ndc) * kPairBytes))
                     return JPGD_E_TABLE;
                 built |= 1u << sa;
             }
@@ -634,6 +646,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
     P.overlap = pl.h.overlap;
     P.seq_len = kWG - pl.h.overlap;
     P.lut_slots = pl.lut_slots;
+    P.pair_slots = pl.pair_slots;
     P.planar = (flags_in & JPGD_F_PLANAR) ? 1u : 0u;
     P.scale_log2 = scale_log2;
     // Wavefronts per workgroup of the intra-sequence kernel: as many as the CU's 32 slots allow beside the other
@@ -686,7 +699,7 @@ int enqueue_call(Call& c, int n, const jpgd_info* infos, const uint8_t* d_scans,
         else LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_head<false, false>), pl.seqs, kWG, c.lds_sync);
         P.sync_waves = (uint32_t)(kWG / 64);
         P.coop_max = kCoopMax;
-        LAUNCH(JPGD_K_SYNC_TAIL, (k_sync_tail<false>), pl.seqs, kWG, lds_tail_bytes(pl.lut_slots));
+        LAUNCH(JPGD_K_SYNC_TAIL, (k_sync_tail<false>), pl.seqs, kWG, lds_tail_bytes(pl.lut_slots, pl.pair_slots));
     } else
     switch (c.variant) {
         case 0: LAUNCH(JPGD_K_SYNC_INTRA, (k_sync_intra<true, false>), pl.seqs, 64u * P.sync_waves, c.lds_sync); break;
@@ -863,8 +876,8 @@ extern "C" int jpgd_init(void) {
     const void* const sync_kernels[4] = {(const void*)k_sync_intra<true, false>, (const void*)k_sync_intra<false, false>,
                                          (const void*)k_sync_intra<true, true>, (const void*)k_sync_intra<false, true>};
     for (int v = 0; v < 4; ++v)
-        if ((rc = grant_lds(dev, v, sync_kernels[v], lds_sync_bytes(2048u, kMaxSlots, v >= 2)))) break;
-    if (!rc) rc = grant_lds(dev, 6, (const void*)k_sync_head<true, false>, lds_sync_bytes(2048u, kMaxSlots, false));
+        if ((rc = grant_lds(dev, v, sync_kernels[v], lds_sync_bytes(2048u, kMaxSlots, kMaxPairs, v >= 2)))) break;
+    if (!rc) rc = grant_lds(dev, 6, (const void*)k_sync_head<true, false>, lds_sync_bytes(2048u, kMaxSlots, kMaxPairs, false));
     if (!rc) rc = grant_lds(dev, 4, (const void*)k_write<true>, lds_write_bytes(2048u, kMaxSlots, true));
     if (!rc) rc = grant_lds(dev, 5, (const void*)k_write<false>, lds_write_bytes(2048u, kMaxSlots, true));
     if (!rc) rc = grant_lds(dev, 8, (const void*)k_sync_inter, (size_t)kMaxSlots * kLutEntries * 2);

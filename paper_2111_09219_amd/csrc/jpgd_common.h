@@ -41,6 +41,12 @@ constexpr int kLutL2 = 512;
 constexpr int kLutEntries = kLutL1 + kLutL2;
 constexpr int kMaxSlots = 6;  // up to 3 DC and 3 AC tables per image (one pair per component)
 constexpr uint32_t kAdvEob = 63u;
+// Per AC table, one byte per first-level index: the symbol behind the one the entry describes, where the index
+// holds it (build_pairs; used by the synchronisation pass).  In memory the pair bytes of an image's tables follow
+// its kMaxSlots table slots: a set of tables takes kLutSetEntries uint16.
+constexpr int kPairBytes = kLutL1;
+constexpr int kMaxPairs = kMaxSlots / 2;
+constexpr int kLutSetEntries = kMaxSlots * kLutEntries + kMaxPairs * kPairBytes / 2;
 
 // Intra-sequence synchronisation: with at most one and a half chains per wavefront of the workgroup still running,
 // each chain is decoded by a whole wavefront.  Measured on 1920x1088 4:4:4 (128-bit subsequences) and on 4096x4096
@@ -129,7 +135,8 @@ struct ImgDesc {
     uint32_t nint;         // intervals in the scan
     uint32_t bmap_off;     // word offset of this image's interval-start bitmap (one bit per unstuffed byte,
                            // 128 words per unstuff tile plus 128 of slack)
-    uint32_t pad_[2];
+    uint32_t ndc;          // DC tables of this image: slots 0 .. ndc-1; its AC tables follow, AC table k with pair bytes k
+    uint32_t pad_;
 };
 
 // written by the unstuff kernels

@@ -37,6 +37,7 @@ struct Params {
     uint32_t overlap;       // H: warm-up lanes in front of each sequence
     uint32_t seq_len;       // kWG - H: subsequences a sequence owns
     uint32_t lut_slots;     // max tables of any image (sizes the LDS copy)
+    uint32_t pair_slots;    // max AC tables of any image (sizes the LDS copy of their pair bytes)
     uint32_t planar;        // pixel kernel: component planes (no upsampling, no colour conversion) instead of RGB
     uint32_t scale_log2;    // pixel kernel: output at 1/2^scale_log2 of the size (0..3)
     uint32_t handoff;       // intra-sequence kernel, split in two: chains left at which the first hands over (at most 64)
@@ -187,6 +188,16 @@ __device__ __forceinline__ void stage_luts(const Params& P, const ImgDesc& D, ui
     const uint4* src = reinterpret_cast<const uint4*>(P.luts + D.lut_off);
     uint4* dst = reinterpret_cast<uint4*>(lut_s);
     for (uint32_t k = threadIdx.x; k < n16 / 8u; k += blockDim.x) dst[k] = src[k];
+}
+
+// pair bytes of the image's AC tables, behind its table slots in memory; pair_of_unit: 8 words of LDS
+__device__ __forceinline__ void stage_pairs(const Params& P, const ImgDesc& D, uint8_t* pair_s, uint32_t* pair_of_unit) {
+    const uint32_t n16 = (D.nslots - D.ndc) * (uint32_t)(kPairBytes / 16);
+    const uint4* src = reinterpret_cast<const uint4*>(P.luts + D.lut_off + (uint32_t)(kMaxSlots * kLutEntries));
+    uint4* dst = reinterpret_cast<uint4*>(pair_s);
+    for (uint32_t k = threadIdx.x; k < n16; k += blockDim.x) dst[k] = src[k];
+    if (threadIdx.x < D.upm)
+        pair_of_unit[threadIdx.x] = (((D.sched_ac >> (4u * threadIdx.x)) & 15u) - D.ndc) * (uint32_t)kPairBytes;
 }
 
 // rows: 8 entries of LDS, complete after the next barrier
@@ -587,6 +598,11 @@ constexpr uint32_t kHandWords = 6u * kWG;  // per sequence: 4 x kWG record words
 template <bool STAGED, bool RST, int PHASE>
 __device__ __forceinline__ void sync_intra_body(const Params& P) {
     static_assert(PHASE != kSyncTail || !STAGED, "the second kernel reads the stream from memory");
+    // Two symbols per step where the tables allow it (sync_symbol_pair), except in the kernels for calls with
+    // restart intervals, whose rules look at every symbol.  Measured on the 15360x8640 image: first kernel 0.85 ->
+    // 0.75 ms, second 1.00 -> 0.87 ms; 4096x4096 0.67 -> 0.59 ms; the 256-image batch 0.40 -> 0.36 ms; nothing on
+    // images whose rounds are mostly walked by whole wavefronts (1920x1088 with 128-bit subsequences).
+    constexpr bool PAIRS = !RST;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
@@ -596,14 +612,17 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
     if (base >= (int32_t)nsub || (int32_t)((wg - D.seq0) * P.seq_len) >= (int32_t)nsub) return;  // nothing owned
 
     uint16_t* lut_s = reinterpret_cast<uint16_t*>(lds_raw);
-    uint32_t* sw = reinterpret_cast<uint32_t*>(lut_s + P.lut_slots * (uint32_t)kLutEntries);
+    uint8_t* pair_s = reinterpret_cast<uint8_t*>(lut_s + P.lut_slots * (uint32_t)kLutEntries);
+    uint32_t* sw = reinterpret_cast<uint32_t*>(pair_s + (PAIRS ? P.pair_slots * (uint32_t)kPairBytes : 0u));
     uint32_t* pnb = sw + kWG;
     uint32_t* pdc01 = pnb + kWG;
     uint32_t* pdc2 = pdc01 + kWG;
-    uint32_t* mv_p = pdc2 + kWG;     // staging for packing the running chains
-    uint32_t* mv_uz = mv_p + kWG;
-    uint32_t* mv_tt = mv_uz + kWG;
-    uint32_t* strm = mv_tt + kWG;
+    // staging for packing the running chains: position; z (bits 0..7), u (8..11), target subsequence (12..).
+    // The second kernel never has more than kHandMax chains.
+    constexpr uint32_t kMv = PHASE == kSyncTail ? kHandMax : (uint32_t)kWG;
+    uint32_t* mv_p = pdc2 + kWG;
+    uint32_t* mv_s = mv_p + kMv;
+    uint32_t* strm = mv_s + kMv;
     __shared__ uint32_t scratch[8];
 
     const uint32_t L = 1u << P.logL, wps = L >> 5;  // words per subsequence
@@ -613,8 +632,13 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
     const uint32_t first_word = first * wps;
     const uint32_t nwords = (t1 - t0) * wps + 4u;
     __shared__ UnitRow rows[8];
+    __shared__ uint32_t pair_of_unit[8];
     stage_luts(P, D, lut_s);
-    const Syntax sx = stage_syntax(D, rows);
+    Syntax sx = stage_syntax(D, rows);
+    if (PAIRS) {
+        stage_pairs(P, D, pair_s, pair_of_unit);
+        sx.pair_of_unit = pair_of_unit;
+    }
     if (STAGED) stage_stream(P.stream + D.stream_off, first_word, nwords, strm);
     // scans with restart intervals: the bitmap of interval starts, for the bytes staged above
     uint32_t* bm_s = strm + (STAGED ? kWG * wps + 4u : 4u);
@@ -667,6 +691,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
         const uint32_t limit = (i + 1u) << P.logL;
         uint32_t crossed = 0u;
         if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
+        else if (PAIRS) decode_span_sync_pairs(l, w, limit, dcacc, sx, fetch, lut_s, pair_s);
         else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
         sw[t] = pack_state(l.p - limit, l.z, l.u);
         pnb[t] = l.nb | (crossed << 31);
@@ -718,8 +743,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
             const uint32_t rank = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
             if (active) {
                 mv_p[rank] = l.p;
-                mv_uz[rank] = (l.u << 8) | l.z;
-                mv_tt[rank] = tt;
+                mv_s[rank] = (tt << 12) | (l.u << 8) | l.z;
             }
             coop_n = now;
             __syncthreads();
@@ -731,17 +755,16 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
             const uint32_t rank = before + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
             if (active) {
                 mv_p[rank] = l.p;
-                mv_uz[rank] = (l.u << 8) | l.z;
-                mv_tt[rank] = tt;
+                mv_s[rank] = (tt << 12) | (l.u << 8) | l.z;
             }
             __syncthreads();
             active = t < now;
             if (active) {
                 l.p = mv_p[t];
-                const uint32_t uz = mv_uz[t];
-                l.u = uz >> 8;
-                l.z = uz & 255u;
-                tt = mv_tt[t];
+                const uint32_t ms = mv_s[t];
+                l.u = (ms >> 8) & 15u;
+                l.z = ms & 255u;
+                tt = ms >> 12;
                 win_init(w, l.p, (l.p >> 5) - first_word, fetch);
                 prime(l, w, sx, lut_s);
             }
@@ -757,6 +780,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
                 prime(l, w, sx, lut_s);
             }
             if (restart) decode_span_sync_rst(l, w, limit, dcacc, crossed, sx, fetch, lut_s, bword);
+            else if (PAIRS) decode_span_sync_pairs(l, w, limit, dcacc, sx, fetch, lut_s, pair_s);
             else decode_span_sync(l, w, limit, dcacc, sx, fetch, lut_s);
             const uint32_t x = pack_state(l.p - limit, l.z, l.u);
             const bool synced = x == sw[tt];
@@ -770,7 +794,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
         first_tail_round = false;
     }
     // The same rounds with one chain per wavefront.  The chains keep their slot k < coop_n in a list held twice
-    // (read from one copy, written to the other, swapped every round; mv_tt = kCoopDone once a chain has
+    // (read from one copy, written to the other, swapped every round; mv_s = kCoopDone once a chain has
     // synchronised or reached the end of the sequence).  Every wavefront reads the whole list and takes the
     // running chains whose rank among them is its own number modulo the number of wavefronts (the four that hold
     // the lanes and the ones that are only here for this), so the work stays spread as chains drop out;
@@ -788,18 +812,18 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
         const uint32_t unit_word = coop_unit_word(sx, lane);
         for (uint32_t par = 0u;; par ^= 1u) {
             const uint32_t rd = par << 6, wr = (par ^ 1u) << 6;
-            const uint32_t mine = lane < u_n ? mv_tt[rd + lane] : kCoopDone;
+            const uint32_t mine = lane < u_n ? mv_s[rd + lane] : kCoopDone;
             const uint64_t running = __ballot(mine != kCoopDone);
             if (running == 0ull) break;
-            if (wave == 0u && lane < u_n && mine == kCoopDone) mv_tt[wr + lane] = kCoopDone;
+            if (wave == 0u && lane < u_n && mine == kCoopDone) mv_s[wr + lane] = kCoopDone;
             uint32_t rank = 0u;
             for (uint64_t m = running; m; m &= m - 1ull, ++rank) {
                 if ((rank & (u_waves - 1u)) != wave) continue;
                 const uint32_t k = (uint32_t)__ffsll((long long)m) - 1u;
                 uint32_t cp = mv_p[rd + k];
-                const uint32_t uz = mv_uz[rd + k];
-                uint32_t cu = uz >> 8, cz = uz & 255u, cnb = 0u;
-                const uint32_t ctt = __builtin_amdgcn_readfirstlane(mv_tt[rd + k]);
+                const uint32_t ms = __builtin_amdgcn_readfirstlane(mv_s[rd + k]);
+                uint32_t cu = (ms >> 8) & 15u, cz = ms & 255u, cnb = 0u;
+                const uint32_t ctt = ms >> 12;
                 int64_t cdc = 0;
                 const uint32_t limit = ((uint32_t)(u_base + (int32_t)ctt) + 1u) << P.logL;
                 // The wavefront's decoder does not know the rules of restart intervals.  A chain whose stretch holds
@@ -837,8 +861,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
                     pdc01[ctt] = pack_dc01(cdc);
                     pdc2[ctt] = pack_dc2(cdc);
                     mv_p[wr + k] = cp;
-                    mv_uz[wr + k] = (cu << 8) | cz;
-                    mv_tt[wr + k] = (synced || ctt + 1u >= u_t1) ? kCoopDone : ctt + 1u;
+                    mv_s[wr + k] = (synced || ctt + 1u >= u_t1) ? kCoopDone : ((ctt + 1u) << 12) | (cu << 8) | cz;
                 }
             }
             __syncthreads();

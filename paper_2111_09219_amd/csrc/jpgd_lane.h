@@ -48,6 +48,9 @@ struct Lane {
     // pipeline registers (prime)
     uint32_t e;    // table entry already read for the symbol at p (possibly a first-level escape)
     uint32_t base; // table that entry came from
+    // synchronisation pass with two symbols per step (decode_span_sync_pairs)
+    uint32_t pair; // where the pair bytes of unit u's AC table start
+    uint32_t pb;   // pair byte read for the symbol at p, as if that symbol came from unit u's AC table
 };
 
 // Window on the stream: two consecutive big-endian words and the offset of the next unread bit in the
@@ -70,6 +73,7 @@ JPGD_HD uint32_t win_stop(const BitWin& w, uint32_t limit) { return ((limit - w.
 struct Syntax {
     const UnitRow* rows;  // one per data unit of the MCU
     uint32_t upm;         // units per MCU
+    const uint32_t* pair_of_unit = nullptr;  // per data unit: offset of its AC table's pair bytes (kernels that use them)
 };
 
 JPGD_HD uint32_t win_peek(const BitWin& w) {
@@ -199,6 +203,77 @@ template <class Fetch, class LutPtr>
 JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
                               LutPtr lut) {
     const uint32_t stop = win_stop(w, limit);
+    while (w.next < stop) sync_symbol(l, w, dcacc, sx, fetch, lut);
+    l.p = win_pos(w);
+}
+
+// ---- two symbols per step ---------------------------------------------------------------------------------
+// The synchronisation pass needs the state, the unit count and the DC sums, not the coefficients.  So where the
+// first-level index of an AC symbol also holds the whole codeword of the AC symbol after it, one step may take
+// both: the pair byte of that index (build_pairs) says how many bits the second symbol takes and how many slots it
+// covers.  The second symbol is taken only if the first one is an AC symbol that leaves its data unit open (the
+// second then belongs to the same unit and the same table); the step is exactly two steps of sync_symbol.
+template <class Fetch, class LutPtr, class PairPtr>
+JPGD_HD void sync_symbol_pair(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& sx, Fetch fetch, LutPtr lut,
+                              PairPtr pairs) {
+    const uint32_t e = l.e;
+    const uint32_t peek = w.peek;
+    const bool esc = lut_esc(e);
+    const uint32_t ee = esc ? 0u : e;
+    const uint32_t t1 = lut_total(ee), size = lut_size(ee), a1 = lut_adv(ee);
+    const bool is_dc = l.z == 0u;
+    const uint32_t zn1 = l.z + a1;
+    const uint32_t pb = (is_dc || zn1 >= 64u) ? 0u : l.pb;  // (an escape's index has pair byte 0)
+    const uint32_t a2c = pb >> 4;
+    const uint32_t total = t1 + (pb & 15u);
+    const uint32_t zn = zn1 + (a2c == 15u ? kAdvEob : a2c);
+    const bool done = zn >= 64u;
+    const uint32_t o2 = w.o + total;  // at most 31 + 20 + 15
+    const bool need = o2 >= 32u;
+    w.next += need ? 1u : 0u;
+    const uint32_t ahead = fetch(w.next);
+    const UnitRow old = l.row;
+    const uint32_t old_pair = l.pair;
+    const uint32_t dcmul = old.dcmul;
+    l.u = done ? old.next : l.u;
+    l.row = sx.rows[l.u];
+    l.pair = sx.pair_of_unit[l.u];
+    l.nb += done ? 1u : 0u;
+    w.o = o2 & 31u;
+    w.hi = need ? w.lo : w.hi;
+    w.lo = need ? w.ahead : w.lo;
+    w.ahead = ahead;
+    w.peek = win_peek(w);
+    l.z = done ? 0u : zn;
+    const uint32_t base2 = done ? old.tb_dc_next : old.tb_ac;
+    const uint32_t nb2 = lut_esc_bits(e);
+    const uint32_t sub = (uint32_t)kLutL1 + lut_esc_offset(e) + ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
+    const uint32_t i1 = w.peek >> (32 - kLutK);
+    const uint32_t idx = esc ? l.base + sub : base2 + i1;
+    l.base = esc ? l.base : base2;
+    l.e = lut[idx];
+    // asked as if the next symbol came from the AC table of the unit just left: if the unit is complete the next
+    // symbol is a DC symbol and the byte is not looked at
+    l.pb = pairs[old_pair + i1];
+    const int32_t v = symbol_value(peek, t1, size);
+    dcacc += (int64_t)v * (int64_t)(is_dc ? (int32_t)dcmul : 0);
+}
+
+// The synchronisation pass with pairs.  A second symbol must start before `limit` like any other: pairs are taken
+// while the step starts at least 32 bits before it (a first symbol with a pair byte has at most 20 bits), single
+// symbols from there on.  The lane must have been primed; sx.pair_of_unit must be set.
+template <class Fetch, class LutPtr, class PairPtr>
+JPGD_HD void decode_span_sync_pairs(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
+                                    LutPtr lut, PairPtr pairs) {
+    const uint32_t stop = win_stop(w, limit);
+    l.pair = sx.pair_of_unit[l.u];
+    l.pb = pairs[l.pair + (w.peek >> (32 - kLutK))];
+#if defined(__HIP_DEVICE_COMPILE__)
+    // (Keeps the compiler from merging this read with the one at the end of a step into a single read at the top of
+    // the loop, where every step would wait for it: the byte is asked for one step ahead, like the table entry.)
+    asm volatile("" : "+v"(l.pb));
+#endif
+    while (w.next + 1u < stop) sync_symbol_pair(l, w, dcacc, sx, fetch, lut, pairs);
     while (w.next < stop) sync_symbol(l, w, dcacc, sx, fetch, lut);
     l.p = win_pos(w);
 }

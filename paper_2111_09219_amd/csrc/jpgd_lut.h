@@ -88,4 +88,25 @@ inline bool build_lut(const uint8_t bits[16], const uint8_t* vals, bool is_dc, u
     return true;
 }
 
+// Pair bytes of an AC table (synchronisation pass, two symbols per step): for first-level index i, if the entry is
+// a coefficient or a run of sixteen zeros that takes t1 < kLutK bits and the rest of the index holds the whole
+// codeword of another symbol of the table -- taking t2 <= 15 bits with its value bits, covering at most 14 slots
+// or being end-of-block -- the byte is t2 | c << 4 with c = slots covered, 15 for end-of-block; otherwise 0.
+// lut: the table's kLutEntries entries (build_lut); pairs: kPairBytes bytes.
+inline void build_pairs(const uint16_t* lut, uint8_t* pairs) {
+    for (uint32_t i = 0; i < (uint32_t)kLutL1; ++i) {
+        pairs[i] = 0;
+        const uint32_t e1 = lut[i];
+        if (lut_esc(e1)) continue;
+        const uint32_t a1 = lut_adv(e1), t1 = lut_total(e1);
+        if (a1 == 0u || a1 == kAdvEob || t1 >= (uint32_t)kLutK) continue;
+        const uint32_t e2 = lut[(i << t1) & (uint32_t)(kLutL1 - 1)];  // the bits behind the first symbol, zeros appended
+        if (lut_esc(e2)) continue;
+        const uint32_t t2 = lut_total(e2), a2 = lut_adv(e2);
+        if (t2 - lut_size(e2) > (uint32_t)kLutK - t1) continue;        // the codeword reaches beyond the index
+        if (a2 == 0u || t2 > 15u || (a2 != kAdvEob && a2 > 14u)) continue;
+        pairs[i] = (uint8_t)(t2 | ((a2 == kAdvEob ? 15u : a2) << 4));
+    }
+}
+
 }  // namespace jpgd

@@ -30,6 +30,8 @@ struct Image {
     jpgd_info in;
     uint32_t sched_dc = 0, sched_ac = 0, sched_comp = 0, nslots = 0;
     std::vector<uint16_t> lut;
+    std::vector<uint8_t> pairs;    // pair bytes of the AC tables, AC table k at k * kPairBytes
+    uint32_t pair_of_unit[8] = {0};
     std::vector<uint8_t> stream;  // unstuffed + zero slack
     std::vector<uint32_t> bmap;   // restart intervals: one bit per unstuffed byte, set at the first byte of an interval
     uint32_t nbytes = 0, nsub = 0, markers = 0;
@@ -51,6 +53,7 @@ int prepare(const uint8_t* file, size_t len, Image& im) {
     }
     im.nslots = ndc + nac;
     im.lut.assign((size_t)im.nslots * kLutEntries, 0);
+    im.pairs.assign((size_t)nac * kPairBytes, 0);
     uint32_t u = 0;
     for (uint32_t c = 0; c < in.ncomp; ++c) {
         uint32_t nu = (in.ncomp == 1) ? 1u : (c == 0 ? (uint32_t)in.hsamp[0] * in.vsamp[0] : 1u);
@@ -58,10 +61,12 @@ int prepare(const uint8_t* file, size_t len, Image& im) {
             im.sched_dc |= cdc[c] << (4 * u);
             im.sched_ac |= (ndc + cac[c]) << (4 * u);
             im.sched_comp |= c << (4 * u);
+            im.pair_of_unit[u] = cac[c] * (uint32_t)kPairBytes;
         }
         if (!build_lut(in.dht_bits[0][in.td[c]], in.dht_vals[0][in.td[c]], true, &im.lut[(size_t)cdc[c] * kLutEntries]) ||
             !build_lut(in.dht_bits[1][in.ta[c]], in.dht_vals[1][in.ta[c]], false, &im.lut[(size_t)(ndc + cac[c]) * kLutEntries]))
             return JPGD_E_TABLE;
+        build_pairs(&im.lut[(size_t)(ndc + cac[c]) * kLutEntries], &im.pairs[(size_t)cac[c] * kPairBytes]);
     }
     return JPGD_OK;
 }
@@ -258,7 +263,7 @@ void sync_intra(Emul& E) {
             uint32_t limit = (i + 1) << logL;
             uint32_t crossed = 0;
             if (restart) decode_span_sync_rst(l[t], bw[t], limit, dcacc[t], crossed, E.sx, fetch, im.lut.data(), bword);
-            else decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
+            else decode_span_sync_pairs(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data(), im.pairs.data());
             sw[t] = pack_state(l[t].p - limit, l[t].z, l[t].u);
             pnb[t] = l[t].nb | (crossed << 31);
             pdc01[t] = pack_dc01(dcacc[t]);
@@ -310,7 +315,7 @@ void sync_intra(Emul& E) {
                 uint32_t limit = ((uint32_t)(base + (int32_t)tt[t]) + 1) << logL;
                 uint32_t crossed = 0;
                 if (restart) decode_span_sync_rst(l[t], bw[t], limit, dcacc[t], crossed, E.sx, fetch, im.lut.data(), bword);
-                else decode_span_sync(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data());
+                else decode_span_sync_pairs(l[t], bw[t], limit, dcacc[t], E.sx, fetch, im.lut.data(), im.pairs.data());
                 uint32_t x = pack_state(l[t].p - limit, l[t].z, l[t].u);
                 bool synced = x == sw[tt[t]];
                 sw[tt[t]] = x; pnb[tt[t]] = l[t].nb | (crossed << 31);
@@ -520,6 +525,7 @@ extern "C" int emul_decode(const uint8_t* file, size_t len, uint32_t L, uint32_t
         E.rows[u] = make_unit_row(u, E.im.in.units_per_mcu, E.im.sched_dc, E.im.sched_ac, E.im.sched_comp);
     E.sx.rows = E.rows;
     E.sx.upm = E.im.in.units_per_mcu;
+    E.sx.pair_of_unit = E.im.pair_of_unit;
     unstuff(file + E.im.in.scan_offset, (uint32_t)E.im.in.scan_bytes, E.logL, E.im);
     E.sinfo.assign(E.im.nsub, SInfo{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu});
     const uint32_t nseq = (E.im.nsub + E.seq_len - 1) / E.seq_len;
@@ -566,4 +572,59 @@ extern "C" void emul_zigzag(uint8_t out[64]) {
 // one table built by jpgd_lut.h
 extern "C" int emul_build_lut(const uint8_t* bits, const uint8_t* vals, int is_dc, uint16_t* out) {
     return build_lut(bits, vals, is_dc != 0, out) ? 0 : JPGD_E_TABLE;
+}
+
+// pair bytes of an AC table built by jpgd_lut.h (lut: the table's kLutEntries entries)
+extern "C" void emul_build_pairs(const uint16_t* lut, uint8_t* pairs) { build_pairs(lut, pairs); }
+
+// The synchronisation pass with two symbols per step against the one with single symbols, from decoder states that
+// need not lie on the true chain: `nstart` starts at pseudo-random subsequences in pseudo-random states, each
+// followed over `span` subsequences by both decoders (the lanes keep their window from one subsequence to the
+// next, as in the kernel's overflow rounds).  Returns the number of subsequences after which the two disagreed in
+// position, unit, zig-zag index, completed units or DC sums; stats[0] = steps of the single decoder,
+// stats[1] = steps of the pair decoder over the same stretches.
+extern "C" int emul_pairs_vs_single(const uint8_t* file, size_t len, uint32_t L, uint32_t nstart, uint32_t span,
+                                    uint32_t seed, uint32_t* stats) {
+    Emul E;
+    int rc = prepare(file, len, E.im);
+    if (rc) return -1;
+    Image& im = E.im;
+    if (im.in.restart_interval) return -1;
+    E.logL = 0;
+    while ((1u << E.logL) < L) ++E.logL;
+    for (uint32_t u = 0; u < im.in.units_per_mcu; ++u)
+        E.rows[u] = make_unit_row(u, im.in.units_per_mcu, im.sched_dc, im.sched_ac, im.sched_comp);
+    E.sx.rows = E.rows;
+    E.sx.upm = im.in.units_per_mcu;
+    E.sx.pair_of_unit = im.pair_of_unit;
+    unstuff(file + im.in.scan_offset, (uint32_t)im.in.scan_bytes, E.logL, im);
+    const uint32_t* words = (const uint32_t*)im.stream.data();
+    uint32_t steps[2] = {0u, 0u};
+    int which = 0;
+    auto fetch = [&](uint32_t w) { ++steps[which]; return bswap(words[w]); };  // one fetch per step (plus three per window)
+    uint64_t rng = 0x9E3779B97F4A7C15ull ^ seed;
+    auto next = [&]() { rng ^= rng << 13; rng ^= rng >> 7; rng ^= rng << 17; return (uint32_t)(rng >> 16); };
+    int bad = 0;
+    if (im.nsub < 2) return 0;
+    for (uint32_t k = 0; k < nstart; ++k) {
+        const uint32_t i0 = next() % (im.nsub - 1u);
+        const uint32_t prel = next() % 32u, z = next() % 64u, u = next() % im.in.units_per_mcu;
+        Lane a, b;
+        BitWin wa, wb;
+        a.p = (i0 << E.logL) + prel; a.z = z; a.u = u; a.nb = 0;
+        b = a;
+        which = 0; win_init(wa, a.p, a.p >> 5, fetch); prime(a, wa, E.sx, im.lut.data());
+        which = 1; win_init(wb, b.p, b.p >> 5, fetch); prime(b, wb, E.sx, im.lut.data());
+        for (uint32_t i = i0; i < std::min(im.nsub, i0 + span); ++i) {
+            const uint32_t limit = (i + 1u) << E.logL;
+            int64_t da = 0, db = 0;
+            a.nb = b.nb = 0;
+            which = 0; decode_span_sync(a, wa, limit, da, E.sx, fetch, im.lut.data());
+            which = 1; decode_span_sync_pairs(b, wb, limit, db, E.sx, fetch, im.lut.data(), im.pairs.data());
+            if (a.p != b.p || a.u != b.u || a.z != b.z || a.nb != b.nb || da != db) { ++bad; break; }
+        }
+    }
+    stats[0] = steps[0];
+    stats[1] = steps[1];
+    return bad;
 }

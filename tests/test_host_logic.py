@@ -159,6 +159,8 @@ def emul():
     lib.emul_set_coop_max.argtypes = [u32]
     lib.emul_set_sync_waves.argtypes = [u32]
     lib.emul_build_lut.argtypes = [vp, vp, ctypes.c_int, vp]
+    lib.emul_build_pairs.argtypes = [vp, vp]
+    lib.emul_pairs_vs_single.argtypes = [vp, ctypes.c_size_t, u32, u32, u32, u32, vp]
     return lib
 
 
@@ -239,6 +241,74 @@ def test_lookup_tables_decode_every_codeword(emul, optimize):
                         assert look(lo | tail) == (ln, want_size, want_adv)
                 for peek in np.flatnonzero(~covered)[::97]:
                     assert look(int(peek)) is None
+
+
+@pytest.mark.parametrize("optimize", [False, True])
+def test_pair_bytes_describe_the_symbol_behind_the_first(emul, optimize):
+    """For every 10-bit index of every AC table: the pair byte is set exactly when the index starts with the codeword
+    and value bits of a coefficient or a run of sixteen zeros and the whole codeword of a further symbol follows inside
+    the index (found here by matching the codewords the oracle derives, not through the tables), that symbol takes at
+    most 15 bits and covers at most 14 slots or ends the block; and then it holds that symbol's bits and slots."""
+    px2 = np.full((256, 256, 3), 128, np.uint8)
+    px2[::37, ::41] = (255, 0, 90)
+    files = [encode_jpeg(small_image(8, 160, 160, sigma=30), 97, "420", optimize).data,
+             encode_jpeg(small_image(9, 96, 96, sigma=8), 40, "444", optimize).data]
+    if optimize:
+        files.append(encode_jpeg(px2, 100, "444", True).data)
+    nset = 0
+    for data in files:
+        img = OracleImage(data)
+        for tid in (0, 1):
+            bits, vals = img.huffman(1, tid)
+            code, length = img.codes(1, tid)
+            vbuf = np.zeros(256, np.uint8); vbuf[:len(vals)] = vals
+            lut = np.zeros(1536, np.uint16)
+            assert emul.emul_build_lut(bits.ctypes.data, vbuf.ctypes.data, 0, lut.ctypes.data) == 0
+            pairs = np.full(1024, 0xEE, np.uint8)
+            emul.emul_build_pairs(lut.ctypes.data, pairs.ctypes.data)
+            by_code = {(int(length[s]), int(code[s])): int(s) for s in vals}
+
+            def first_symbol(bits10, nbits):
+                """symbol whose whole codeword is a prefix of the nbits bits given (left-aligned in 10), or None"""
+                for ln in range(1, nbits + 1):
+                    s = by_code.get((ln, bits10 >> (10 - ln)))
+                    if s is not None:
+                        return s, ln
+                return None
+            for i in range(1024):
+                want = 0
+                f = first_symbol(i, 10)
+                if f is not None:
+                    s1, l1 = f
+                    size1, run1 = s1 & 15, s1 >> 4
+                    t1 = l1 + size1
+                    if (size1 or run1 == 15) and t1 < 10:
+                        g = first_symbol((i << t1) & 1023, 10 - t1)
+                        if g is not None:
+                            s2, l2 = g
+                            size2, run2 = s2 & 15, s2 >> 4
+                            t2 = l2 + size2
+                            slots = run2 + 1 if size2 else (16 if run2 == 15 else 63)
+                            if t2 <= 15 and (slots == 63 or slots <= 14):
+                                want = t2 | ((15 if slots == 63 else slots) << 4)
+                assert int(pairs[i]) == want, (tid, i)
+                nset += want != 0
+    assert nset > 1000
+
+
+@pytest.mark.parametrize("sub,opt,q,shape,L", [("420", False, 92, (137, 251), 128), ("444", True, 75, (96, 120), 1024),
+                                                ("gray", False, 30, (200, 64), 256), ("422", True, 98, (64, 80), 512),
+                                                ("420", True, 10, (160, 160), 128)])
+def test_two_symbols_per_step_equal_two_steps_from_any_state(emul, sub, opt, q, shape, L):
+    """The synchronisation pass that takes two AC symbols per step where the tables allow it ends every subsequence
+    in the same position, unit, zig-zag index, unit count and DC sums as the pass that takes them one by one, also
+    from states that do not lie on the true chain (wrong offset, wrong unit, wrong zig-zag index), where symbols run
+    past the end of a unit and bits start no codeword."""
+    data = encode_jpeg(small_image(21, shape[0], shape[1], sigma=14.0), q, sub, opt).data
+    stats = np.zeros(2, np.uint32)
+    bad = emul.emul_pairs_vs_single(data.ctypes.data, data.size, L, 4000, 6, 5, stats.ctypes.data)
+    assert bad == 0
+    assert stats[1] < stats[0]          # fewer steps
 
 
 CASES = [("gray", False, 75, (64, 64)), ("444", False, 90, (40, 104)), ("420", True, 95, (96, 80)),
