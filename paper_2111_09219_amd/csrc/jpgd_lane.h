@@ -44,12 +44,10 @@ struct Lane {
     uint32_t u;    // data unit inside the MCU
     uint32_t z;    // zig-zag index of the next coefficient (0 = a DC symbol is next)
     uint32_t nb;   // data units completed since the counter was last cleared
-    UnitRow row;   // row of unit u (prime, step_and_request)
     // pipeline registers (prime)
     uint32_t e;    // table entry already read for the symbol at p (possibly a first-level escape)
     uint32_t base; // table that entry came from
     // synchronisation pass with two symbols per step (decode_span_sync_pairs)
-    uint32_t pair; // where the pair bytes of unit u's AC table start
     uint32_t pb;   // pair byte read for the symbol at p, as if that symbol came from unit u's AC table
 };
 
@@ -95,9 +93,8 @@ JPGD_HD void win_init(BitWin& w, uint32_t p, uint32_t cursor, Fetch fetch) {
 // Starts the pipeline: after (p, u, z) and the window are set, read the entry of the symbol at p.
 template <class LutPtr>
 JPGD_HD void prime(Lane& l, const BitWin& w, const Syntax& sx, LutPtr lut) {
-    l.row = sx.rows[l.u];
     const uint32_t tb_dc = sx.rows[l.u == 0u ? sx.upm - 1u : l.u - 1u].tb_dc_next;
-    l.base = l.z == 0u ? tb_dc : l.row.tb_ac;
+    l.base = l.z == 0u ? tb_dc : sx.rows[l.u].tb_ac;
     l.e = lut[l.base + (w.peek >> (32 - kLutK))];
 }
 
@@ -112,8 +109,8 @@ JPGD_HD int32_t symbol_value(uint32_t peek, uint32_t total, uint32_t size) {
     const uint32_t raw = (peek >> ((32u - total) & 31u)) & ((1u << size) - 1u);
     const int32_t s = size ? (int32_t)(raw << (32u - size)) >> (32u - size) : 0;
 #endif
-    const int32_t one = (int32_t)(1u << size);
-    return s + (s < 0 ? one : 1 - one);
+    // s + 2^size if s < 0, s - (2^size - 1) otherwise: subtract 2^size - 1 with all its bits flipped in the first case
+    return s - (int32_t)(((1u << size) - 1u) ^ (uint32_t)(s >> 31));
 }
 
 // DC-difference sums of the three components, kept in one 64-bit accumulator with 15-bit fields
@@ -140,14 +137,17 @@ struct Step {
     bool done;       // the symbol completed its data unit
     bool need;       // the window moved on by a word
     uint32_t z;      // zig-zag index the symbol started at
+    uint32_t dcmul;  // of the data unit the symbol belongs to
 };
 
-// LDS answers in the order it was asked, and the compiler waits for everything outstanding at once.  So the
-// two reads that are off the chain (the next stream word, the row of the unit now current) are issued first
-// and the table entry last: when the entry has arrived, so have they, and nothing waits for them.
+// The row of the current unit is read at the top of the step and used at its end (which table the next entry comes
+// from); the next stream word is asked for in the middle and used in the next step; the table entry is asked for
+// last and is what the next step starts with.  Nothing but the entry and the window is carried from step to step
+// in registers.
 template <class Fetch, class LutPtr>
 JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch, LutPtr lut) {
     Step s;
+    const UnitRow old = sx.rows[l.u];
     const uint32_t e = l.e;
     s.peek = w.peek;
     s.esc = lut_esc(e);
@@ -165,9 +165,8 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
     // unit does not change its row is
     w.next += s.need ? 1u : 0u;
     const uint32_t ahead = fetch(w.next);
-    const UnitRow old = l.row;
     l.u = s.done ? old.next : l.u;
-    l.row = sx.rows[l.u];
+    s.dcmul = old.dcmul;
     l.nb += s.done ? 1u : 0u;
     // window past the symbol
     w.o = o2 & 31u;
@@ -178,7 +177,12 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
     l.z = s.done ? 0u : zn;
     // request: next symbol from the DC table of the next unit or the AC table of this one; an escape asks
     // the second level of the table it came from
-    const uint32_t base2 = s.done ? old.tb_dc_next : old.tb_ac;
+    uint32_t base2 = s.done ? old.tb_dc_next : old.tb_ac;
+#if defined(__HIP_DEVICE_COMPILE__)
+    // (Only the arm for ordinary entries below uses base2, and the compiler would move the read of the row into that
+    // arm and wait for it there; this keeps the read at the top of the step.)
+    asm volatile("" : "+v"(base2));
+#endif
     const uint32_t nb2 = lut_esc_bits(e);
     const uint32_t sub = (uint32_t)kLutL1 + lut_esc_offset(e) + ((s.peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
     const uint32_t idx = s.esc ? l.base + sub : base2 + (w.peek >> (32 - kLutK));
@@ -191,10 +195,9 @@ JPGD_HD Step step_and_request(Lane& l, BitWin& w, const Syntax& sx, Fetch fetch,
 // (inside step_and_request) and the per-component sums of DC differences.
 template <class Fetch, class LutPtr>
 JPGD_HD void sync_symbol(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& sx, Fetch fetch, LutPtr lut) {
-    const uint32_t dcmul = l.row.dcmul;
     const Step s = step_and_request(l, w, sx, fetch, lut);
     const int32_t v = symbol_value(s.peek, s.total, s.size);
-    const int32_t mul = s.is_dc ? (int32_t)dcmul : 0;
+    const int32_t mul = s.is_dc ? (int32_t)s.dcmul : 0;
     dcacc += (int64_t)v * (int64_t)mul;
 }
 
@@ -216,6 +219,8 @@ JPGD_HD void decode_span_sync(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc
 template <class Fetch, class LutPtr, class PairPtr>
 JPGD_HD void sync_symbol_pair(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& sx, Fetch fetch, LutPtr lut,
                               PairPtr pairs) {
+    const UnitRow row = sx.rows[l.u];
+    const uint32_t pair = sx.pair_of_unit[l.u];
     const uint32_t e = l.e;
     const uint32_t peek = w.peek;
     const bool esc = lut_esc(e);
@@ -226,18 +231,12 @@ JPGD_HD void sync_symbol_pair(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& 
     const uint32_t pb = (is_dc || zn1 >= 64u) ? 0u : l.pb;  // (an escape's index has pair byte 0)
     const uint32_t a2c = pb >> 4;
     const uint32_t total = t1 + (pb & 15u);
-    const uint32_t zn = zn1 + (a2c == 15u ? kAdvEob : a2c);
-    const bool done = zn >= 64u;
+    const uint32_t zn = zn1 + a2c;
+    const bool done = zn >= 64u || a2c == 15u;  // 15: the second symbol is end-of-block
     const uint32_t o2 = w.o + total;  // at most 31 + 20 + 15
     const bool need = o2 >= 32u;
     w.next += need ? 1u : 0u;
     const uint32_t ahead = fetch(w.next);
-    const UnitRow old = l.row;
-    const uint32_t old_pair = l.pair;
-    const uint32_t dcmul = old.dcmul;
-    l.u = done ? old.next : l.u;
-    l.row = sx.rows[l.u];
-    l.pair = sx.pair_of_unit[l.u];
     l.nb += done ? 1u : 0u;
     w.o = o2 & 31u;
     w.hi = need ? w.lo : w.hi;
@@ -245,7 +244,13 @@ JPGD_HD void sync_symbol_pair(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& 
     w.ahead = ahead;
     w.peek = win_peek(w);
     l.z = done ? 0u : zn;
-    const uint32_t base2 = done ? old.tb_dc_next : old.tb_ac;
+    l.u = done ? row.next : l.u;
+    uint32_t base2 = done ? row.tb_dc_next : row.tb_ac;
+#if defined(__HIP_DEVICE_COMPILE__)
+    // (Only the arm for ordinary entries below uses base2, and the compiler would move the read of the row into that
+    // arm and wait for it there; this keeps the read at the top of the step.)
+    asm volatile("" : "+v"(base2));
+#endif
     const uint32_t nb2 = lut_esc_bits(e);
     const uint32_t sub = (uint32_t)kLutL1 + lut_esc_offset(e) + ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u));
     const uint32_t i1 = w.peek >> (32 - kLutK);
@@ -254,9 +259,9 @@ JPGD_HD void sync_symbol_pair(Lane& l, BitWin& w, int64_t& dcacc, const Syntax& 
     l.e = lut[idx];
     // asked as if the next symbol came from the AC table of the unit just left: if the unit is complete the next
     // symbol is a DC symbol and the byte is not looked at
-    l.pb = pairs[old_pair + i1];
+    l.pb = pairs[pair + i1];
     const int32_t v = symbol_value(peek, t1, size);
-    dcacc += (int64_t)v * (int64_t)(is_dc ? (int32_t)dcmul : 0);
+    dcacc += (int64_t)v * (int64_t)(is_dc ? (int32_t)row.dcmul : 0);
 }
 
 // The synchronisation pass with pairs.  A second symbol must start before `limit` like any other: pairs are taken
@@ -266,8 +271,7 @@ template <class Fetch, class LutPtr, class PairPtr>
 JPGD_HD void decode_span_sync_pairs(Lane& l, BitWin& w, uint32_t limit, int64_t& dcacc, const Syntax& sx, Fetch fetch,
                                     LutPtr lut, PairPtr pairs) {
     const uint32_t stop = win_stop(w, limit);
-    l.pair = sx.pair_of_unit[l.u];
-    l.pb = pairs[l.pair + (w.peek >> (32 - kLutK))];
+    l.pb = pairs[sx.pair_of_unit[l.u] + (w.peek >> (32 - kLutK))];
 #if defined(__HIP_DEVICE_COMPILE__)
     // (Keeps the compiler from merging this read with the one at the end of a step into a single read at the top of
     // the loop, where every step would wait for it: the byte is asked for one step ahead, like the table entry.)
@@ -285,8 +289,8 @@ JPGD_HD void decode_span_sync_pairs(Lane& l, BitWin& w, uint32_t limit, int64_t&
 template <class Fetch, class LutPtr, class Store>
 JPGD_HD void write_symbol(Lane& l, BitWin& w, uint32_t& unit, int32_t& pred0, int32_t& pred1, int32_t& pred2,
                           const Syntax& sx, Fetch fetch, LutPtr lut, Store store, uint32_t& flags) {
-    const bool comp0 = l.row.dcmul == 1u, comp1 = l.row.dcmul == (1u << 15);
     const Step s = step_and_request(l, w, sx, fetch, lut);
+    const bool comp0 = s.dcmul == 1u, comp1 = s.dcmul == (1u << 15);
     const int32_t value = symbol_value(s.peek, s.total, s.size);  // 0 for an escape
     const bool real = !s.esc;
     const bool dc = s.is_dc && real;
