@@ -703,7 +703,7 @@ __device__ __forceinline__ void sync_intra_body(const Params& P) {
     // state and compares with the record left there one round earlier by the chain that started at c+1.
     // Chains drop out as they synchronise.  The chains still running are packed into the lowest lanes whenever
     // that frees a whole wavefront: a chain is (p, u, z, target), everything else is rebuilt from the staged
-    // stream, so moving one costs three LDS words.  Between packings a round costs one barrier: the count of
+    // stream, so moving one costs two LDS words.  Between packings a round costs one barrier: the count of
     // running chains goes through one LDS word per wavefront, double-buffered by the parity of the round.
     // The wavefront-per-chain code does not know more than four tables.  In a workgroup that sees restart intervals
     // a chain may fall back to a single lane for a round (below): at most one chain per wavefront then, so that
@@ -1173,9 +1173,11 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     const uint32_t S = unit * 64u + state_z(xprev);  // first slot of this lane's range
     const uint32_t S_chunk = S >> 2, S_low = S & 3u;
     uint64_t acc = 0ull;
-    // chunk being gathered: 16 * data unit + (slot >> 2).  In a dense workgroup the lane starts with the chunk its
-    // range starts in, so that zeros are laid down from the first slot on.
-    uint32_t cur = dense ? S_chunk : 0xFFFFFFFFu;
+    // chunk being gathered: 16 * data unit + (slot >> 2), from the chunk the lane's range starts in on (in a dense
+    // workgroup zeros are laid down from the first slot on; in a sparse one a chunk left without a value costs a
+    // store of zeros onto the cleared background, once per lane at most, and saves a test per chunk)
+    uint32_t cur = S_chunk;
+    const uint32_t shared_first = S_low != 0u ? S_chunk : 0xFFFFFFFFu;  // the first chunk, if a neighbour holds its start
     auto store8 = [&](uint32_t c, uint64_t a) { *reinterpret_cast<uint64_t*>(coef + (size_t)c * 4u) = a; };
     // elements lo .. hi-1 of chunk c, zeros included (chunks shared with a neighbouring lane, dense workgroups)
     auto put_part = [&](uint32_t c, uint64_t a, uint32_t lo, uint32_t hi) {
@@ -1195,8 +1197,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
     };
     // the lane moves on to a later chunk: the one it leaves reaches up to its end inside the lane's range
     auto leave = [&]() {
-        if (cur == 0xFFFFFFFFu) return;
-        if (cur == S_chunk && S_low != 0u) {
+        if (cur == shared_first) {
             if (dense) put_part(cur, acc, S_low, 4u);
             else put_nonzero(cur, acc);
         } else {
@@ -1242,7 +1243,7 @@ __global__ __launch_bounds__(kWG) void k_write(Params P) {
             for (uint32_t c = cur + 1u; c < E_chunk; ++c) store8(c, 0ull);
             if (E_low != 0u && E_chunk > cur) put_part(E_chunk, 0ull, 0u, E_low);
         }
-    } else if (cur != 0xFFFFFFFFu) {
+    } else {
         put_nonzero(cur, acc);  // the last chunk may be shared with the next lane
     }
     // all restart markers must have been there (the first lane of the image speaks for it)
