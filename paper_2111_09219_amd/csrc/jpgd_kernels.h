@@ -464,6 +464,14 @@ __device__ __forceinline__ uint32_t coop_resolve(LutPtr lut, uint32_t slot, uint
     return __builtin_amdgcn_readfirstlane((uint32_t)lut[at]);
 }
 
+// the same for every lane's own entry and bits
+template <class LutPtr>
+__device__ __forceinline__ uint32_t coop_resolve_lane(LutPtr lut, uint32_t slot, uint32_t e, uint32_t peek) {
+    const uint32_t nb2 = lut_esc_bits(e);
+    return lut[slot * (uint32_t)kLutEntries + (uint32_t)kLutL1 + lut_esc_offset(e) +
+               ((peek >> (32 - kLutK - nb2)) & ((1u << nb2) - 1u))];
+}
+
 // A table entry as the walk adds it to its packed state (coop_span_sync): bits taken (at least one) in bits 0..4
 // and zig-zag slots covered in bits 9..14; for a first-level escape nothing but bit 16, which stops the walk.
 constexpr int kCoopUnroll = 8;
@@ -471,8 +479,45 @@ __device__ __forceinline__ uint32_t coop_step(uint32_t e) {
     return (e & 0x8000u) ? 0x10000u : ((e & 0x7E00u) | max(e & 31u, 1u));
 }
 
-// p, u, z: wave-uniform state of the chain, advanced until p >= limit (limit >= 64).  org_word: stream word with
-// cursor 0 of `fetch`; cursors from nwords on are not read.  1 <= nslots <= 4 tables.
+// What the lanes know about one window of 64 bit positions: lane j holds the 32 bits that start at position j and
+// the first-level entry of each table for them (a table the image does not have is asked as the last one it has).
+struct CoopWindow {
+    uint32_t peek, e0, e1, e2, e3;
+};
+
+// The window that starts at bit ws (a multiple of 64).  The wavefront keeps 64 consecutive stream words, one per
+// lane, from word w0 on, and reloads them when a window needs words beyond them (org_word: stream word with cursor
+// 0 of `fetch`; cursors from nwords on are not read).  The table reads are only issued here.
+template <class Fetch, class LutPtr>
+__device__ __forceinline__ CoopWindow coop_window(uint32_t ws, uint32_t& w0, uint32_t& held, bool& have, uint32_t org_word,
+                                                  uint32_t nwords, uint32_t nslots, uint32_t lane, Fetch fetch, LutPtr lut) {
+    uint32_t wb = (ws >> 5) - w0;
+    if (!have || wb + 2u > 63u) {
+        w0 = ws >> 5;
+        const uint32_t c = w0 - org_word + lane;
+        held = c < nwords ? fetch(c) : 0u;
+        wb = 0u;
+        have = true;
+    }
+    const uint32_t s0 = __builtin_amdgcn_readlane(held, wb), s1 = __builtin_amdgcn_readlane(held, wb + 1u);
+    const uint32_t s2 = __builtin_amdgcn_readlane(held, wb + 2u);
+    const uint32_t hi = lane < 32u ? s0 : s1, lo = lane < 32u ? s1 : s2;
+    CoopWindow w;
+    w.peek = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (lane & 31u)) >> 32);
+    const uint32_t idx = w.peek >> (32 - kLutK);
+    w.e0 = lut[idx];
+    w.e1 = lut[min(1u, nslots - 1u) * (uint32_t)kLutEntries + idx];
+    w.e2 = lut[min(2u, nslots - 1u) * (uint32_t)kLutEntries + idx];
+    w.e3 = lut[min(3u, nslots - 1u) * (uint32_t)kLutEntries + idx];
+    return w;
+}
+
+// p, u, z: wave-uniform state of the chain, advanced until p >= limit (limit a multiple of 64).  org_word, nwords:
+// see coop_window.  1 <= nslots <= 4 tables.
+// The windows lie on a 64-bit grid of the stream (a subsequence is a whole number of them, and a chain enters a
+// subsequence at most 31 bits behind its start, so no window is wasted): the window after the current one is known
+// before the chain has been followed through this one, and its table reads are issued first and answered
+// meanwhile.  Escapes are followed up in the walk, where only those on the chain matter.
 template <class Fetch, class LutPtr>
 __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, uint32_t& z_io, uint32_t& nb_out,
                                                int64_t& dc_out, uint32_t limit, uint32_t org_word, uint32_t nwords,
@@ -488,87 +533,78 @@ __device__ __forceinline__ void coop_span_sync(uint32_t& p_io, uint32_t& u_io, u
     // slots of the current unit's AC table and of the table of the DC symbol that starts it
     uint32_t ac_slot = cur & 7u;
     uint32_t dc_slot = (__builtin_amdgcn_readlane(unit_word, u == 0u ? upm - 1u : u - 1u) >> 3) & 7u;
-    // 64 consecutive stream words, one per lane, reloaded when the chain has walked through them
     uint32_t w0 = 0u, held = 0u;
     bool have = false;
-    while (p < limit) {
-        // The window: 64 bit positions, lane j looking at the j-th.  It starts at the chain's position, or, with
-        // fewer than 64 bits left, ends at the limit: either way the walk is over when it leaves the window.
-        const uint32_t ws = limit - p >= 64u ? p : limit - 64u;
-        uint32_t wb = (ws >> 5) - w0;
-        if (!have || wb + 3u > 63u) {
-            w0 = ws >> 5;
-            const uint32_t c = w0 - org_word + lane;
-            held = c < nwords ? fetch(c) : 0u;
-            wb = 0u;
-            have = true;
-        }
-        const uint32_t s0 = __builtin_amdgcn_readlane(held, wb), s1 = __builtin_amdgcn_readlane(held, wb + 1u);
-        const uint32_t s2 = __builtin_amdgcn_readlane(held, wb + 2u), s3 = __builtin_amdgcn_readlane(held, wb + 3u);
-        const uint32_t bit = (ws & 31u) + lane;  // < 95
-        const uint32_t off = bit >> 5;
-        const uint32_t hi = off == 0u ? s0 : (off == 1u ? s1 : s2);
-        const uint32_t lo = off == 0u ? s1 : (off == 1u ? s2 : s3);
-        const uint32_t peek = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (bit & 31u)) >> 32);
-        // first-level entries of all tables (a table the image does not have is asked as the last one it has);
-        // escapes are followed up in the walk, where only those on the chain matter
-        const uint32_t idx = peek >> (32 - kLutK);
-        uint32_t e[4];
-#pragma unroll
-        for (uint32_t s = 0u; s < 4u; ++s) e[s] = lut[min(s, nslots - 1u) * (uint32_t)kLutEntries + idx];
-        const uint32_t e01 = e[0] | (e[1] << 16), e23 = e[2] | (e[3] << 16);
-        uint32_t acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);  // the AC entry in the low 16 bits
-        uint32_t acs = coop_step(acv);
-        // Follow the chain through the window.  S = window position j (bits 0..6, at most 63 + 31) and zig-zag index
-        // z (bits 9..15, at most 63 + 63); adding a symbol's step advances both.  Bit 6 set: the window is behind
-        // us; bit 15: the data unit is complete; bit 16: the entry was an escape and nothing has been advanced.
+    if (p < limit) {
+        uint32_t ws = p & ~63u;
+        // S = window position j (bits 0..6, at most 63 + 31) and zig-zag index z (bits 9..15, at most 63 + 63);
+        // adding a symbol's step advances both.  Bit 6 set: the window is behind us; bit 15: the data unit is
+        // complete; bit 16: the entry was an escape and nothing has been advanced.
         uint32_t S = (p - ws) | (z << 9);
+        CoopWindow nxt = coop_window(ws, w0, held, have, org_word, nwords, nslots, lane, fetch, lut);
+        // (Without this the compiler merges these reads with the ones inside the loop into reads at the top of the
+        // loop, where every window would wait for them.)
+        asm volatile("" : "+v"(nxt.e0), "+v"(nxt.e1), "+v"(nxt.e2), "+v"(nxt.e3));
         for (;;) {
-            if ((S >> 9) == 0u) {  // DC symbol (z = 0, so S is j)
-                const uint32_t pair = __builtin_amdgcn_readlane((dc_slot & 2u) ? e23 : e01, S);
-                const uint32_t pk = __builtin_amdgcn_readlane(peek, S);
-                uint32_t r = pair >> ((dc_slot & 1u) << 4);
-                if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, pk);
-                const int32_t v = symbol_value(pk, lut_total(r), lut_size(r));
-                dc += (int64_t)v * (int64_t)(1u << ((cur >> 10) & 31u));
-                S += coop_step(r);  // z becomes 1, or stays 0 where no codeword starts
-                if (S & 0x40u) break;
-                if ((S >> 9) == 0u) continue;
-            }
-            // AC symbols up to the end of the unit or of the window.  A taken branch costs a lone wavefront far
-            // more than the three other instructions of a step, so the steps come eight in a row with one exit
-            // test each, and everything unusual leaves through that exit.
+            const uint32_t peek = nxt.peek;
+            const uint32_t e01 = nxt.e0 | (nxt.e1 << 16), e23 = nxt.e2 | (nxt.e3 << 16);
+            const bool more = ws + 64u < limit;
+            if (more) nxt = coop_window(ws + 64u, w0, held, have, org_word, nwords, nslots, lane, fetch, lut);
+            uint32_t acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);  // the AC entry in the low 16 bits
+            uint32_t acs = coop_step(acv);
             for (;;) {
-                bool out = false;
+                if ((S >> 9) == 0u) {  // DC symbol (z = 0, so S is j)
+                    const uint32_t pair = __builtin_amdgcn_readlane((dc_slot & 2u) ? e23 : e01, S);
+                    const uint32_t pk = __builtin_amdgcn_readlane(peek, S);
+                    uint32_t r = pair >> ((dc_slot & 1u) << 4);
+                    if (r & 0x8000u) r = coop_resolve(lut, dc_slot, r, pk);
+                    const int32_t v = symbol_value(pk, lut_total(r), lut_size(r));
+                    dc += (int64_t)v * (int64_t)(1u << ((cur >> 10) & 31u));
+                    S += coop_step(r);  // z becomes 1, or stays 0 where no codeword starts
+                    if (S & 0x40u) break;
+                    if ((S >> 9) == 0u) continue;
+                }
+                // AC symbols up to the end of the unit or of the window.  A taken branch costs a lone wavefront far
+                // more than the three other instructions of a step, so the steps come eight in a row with one exit
+                // test each, and everything unusual leaves through that exit.
+                for (;;) {
+                    bool out = false;
 #pragma unroll
-                for (int k = 0; k < kCoopUnroll; ++k) {
-                    S += __builtin_amdgcn_readlane(acs, S & 63u);
-                    if (__builtin_expect((S & 0x18040u) != 0u, 0)) {
-                        out = true;
-                        break;
+                    for (int k = 0; k < kCoopUnroll; ++k) {
+                        S += __builtin_amdgcn_readlane(acs, S & 63u);
+                        if (__builtin_expect((S & 0x18040u) != 0u, 0)) {
+                            out = true;
+                            break;
+                        }
                     }
+                    if (!out) continue;
+                    if (S & 0x10000u) {
+                        // The codeword at this position is longer than the first-level index.  Every lane whose
+                        // entry of this table is an escape follows it up now, at once: where codewords are long
+                        // (large coefficients) a window holds several on the chain, and one look-up by all lanes
+                        // costs less than one by the chain alone.  The step is then taken again.
+                        S &= 0xFFFFu;
+                        if (acv & 0x8000u) acv = coop_resolve_lane(lut, ac_slot, acv, peek);
+                        acs = coop_step(acv);
+                        continue;
+                    }
+                    break;
                 }
-                if (!out) continue;
-                if (S & 0x10000u) {  // the codeword is longer than the first-level index
-                    S &= 0xFFFFu;
-                    const uint32_t j = S & 63u;
-                    S += coop_step(coop_resolve(lut, ac_slot, (uint32_t)__builtin_amdgcn_readlane(acv, j),
-                                                (uint32_t)__builtin_amdgcn_readlane(peek, j)));
-                    if ((S & 0x8040u) == 0u) continue;
+                if (S & 0x8000u) {  // unit complete
+                    ++nb;
+                    S &= 0x7Fu;
+                    u = (cur >> 6) & 15u;
+                    dc_slot = (cur >> 3) & 7u;
+                    cur = __builtin_amdgcn_readlane(unit_word, u);
+                    ac_slot = cur & 7u;
+                    acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);
+                    acs = coop_step(acv);
                 }
-                break;
+                if (S & 0x40u) break;
             }
-            if (S & 0x8000u) {  // unit complete
-                ++nb;
-                S &= 0x7Fu;
-                u = (cur >> 6) & 15u;
-                dc_slot = (cur >> 3) & 7u;
-                cur = __builtin_amdgcn_readlane(unit_word, u);
-                ac_slot = cur & 7u;
-                acv = ((ac_slot & 2u) ? e23 : e01) >> ((ac_slot & 1u) << 4);
-                acs = coop_step(acv);
-            }
-            if (S & 0x40u) break;
+            if (!more) break;
+            S -= 64u;  // the same position, seen from the next window
+            ws += 64u;
         }
         p = ws + (S & 0x7Fu);
         z = S >> 9;

@@ -131,7 +131,9 @@ struct Emul {
 
 // The wavefront-per-chain decoder of jpgd_kernels.h (coop_unit_word, coop_span_sync) with its 64 lanes run
 // one after another: the same table words, the same 64-word stretch held by the lanes, the same four answers
-// per lane and the same walk through them.
+// per lane, the same grid of windows and the same walk through them (the kernel asks for the next window's
+// answers ahead of time and follows up the escapes of all lanes at the first one the chain meets; here each is
+// followed up when the chain meets it, which gives the same entries).
 uint32_t g_coop_max = kCoopMax;  // as the library sets it for four wavefronts; the tests also run with 0 (never), 8 and 64
 uint32_t g_sync_waves = kWG / 64;  // wavefronts per workgroup (the library launches 4, 8 or 16)
 
@@ -161,10 +163,14 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
     uint32_t dc_slot = (unit_word[u == 0u ? upm - 1u : u - 1u] >> 3) & 7u;
     uint32_t w0 = 0, held[64];
     bool have = false;
-    while (p < limit) {
-        const uint32_t ws = limit - p >= 64u ? p : limit - 64u;
+    if (p >= limit) return;
+    // windows of 64 bit positions on a 64-bit grid of the stream (a subsequence is a whole number of them); the
+    // chain enters a window where the last symbol of the window before ended
+    uint32_t ws = p & ~63u;
+    uint32_t S = (p - ws) | (z << 9);
+    for (;; ws += 64u) {
         uint32_t wb = (ws >> 5) - w0;
-        if (!have || wb + 3u > 63u) {
+        if (!have || wb + 2u > 63u) {
             w0 = ws >> 5;
             for (uint32_t lane = 0; lane < 64; ++lane) {
                 const uint32_t c = w0 - org_word + lane;
@@ -175,9 +181,9 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
         }
         uint32_t peek[64], e01[64], e23[64];
         for (uint32_t lane = 0; lane < 64; ++lane) {
-            const uint32_t bit = (ws & 31u) + lane, off = bit >> 5;
+            const uint32_t off = lane >> 5;
             const uint32_t hi = held[wb + off], lo = held[wb + off + 1u];
-            peek[lane] = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (bit & 31u)) >> 32);
+            peek[lane] = (uint32_t)(((((uint64_t)hi << 32) | (uint64_t)lo) << (lane & 31u)) >> 32);
             const uint32_t idx = peek[lane] >> (32 - kLutK);
             uint32_t e[4];
             for (uint32_t s = 0; s < 4u; ++s) e[s] = lut[std::min(s, nslots - 1u) * (uint32_t)kLutEntries + idx];
@@ -185,7 +191,7 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
             e23[lane] = e[2] | (e[3] << 16);
         }
         auto entry = [&](uint32_t slot, uint32_t j) { return ((slot & 2u) ? e23[j] : e01[j]) >> ((slot & 1u) << 4); };
-        uint32_t S = (p - ws) | (z << 9);
+        if ((S & 0x7Fu) >= 64u) abort();  // a symbol has at most 31 bits: the chain enters within the window
         for (;;) {
             if ((S >> 9) == 0u) {
                 uint32_t r = entry(dc_slot, S);
@@ -216,9 +222,11 @@ void coop_span_sync(uint32_t& p, uint32_t& u, uint32_t& z, uint32_t& nb, int64_t
             }
             if (S & 0x40u) break;
         }
-        p = ws + (S & 0x7Fu);
-        z = S >> 9;
+        if (ws + 64u >= limit) break;
+        S -= 64u;  // the same position, seen from the next window
     }
+    p = ws + (S & 0x7Fu);
+    z = S >> 9;
 }
 
 void sync_intra(Emul& E) {
