@@ -94,6 +94,35 @@ def profile_traffic(config: int):
     return out, stale
 
 
+def profile_issue(config: int):
+    """Share of the chip's vector issue slots a kernel fills and the lanes switched on in its average vector
+    instruction, from the SQ counters and kernel-trace durations of the same workload's summary in profiles/:
+    sum(SQ_INSTS_VALU) x 4 cycles / (1024 SIMDs x sum(duration) x 2.4 GHz).  {kernel: (issue, lanes)}."""
+    path = os.path.join(ROOT, "profiles", PROFILE_FILES.get(config, ""))
+    if not os.path.isfile(path):
+        return {}
+    dur, valu, lanes = {}, {}, {}
+    table = None
+    for line in open(path).read().splitlines():
+        if line.startswith("| kernel | calls | average ns |"):
+            table = "trace"
+        elif line.startswith("| kernel | waves | VALU instr |"):
+            table = "sq"
+        elif not line.startswith("|"):
+            table = None
+        elif table and not line.startswith("|---"):
+            cells = [c.strip() for c in line.strip("|").split("|")]
+            for short, prefixes in PROFILE_NAMES.items():
+                if any(cells[0] == pre or cells[0].startswith(pre + "<") for pre in prefixes):
+                    if table == "trace":
+                        dur[short] = dur.get(short, 0.0) + float(cells[2]) * 1e-9
+                    else:
+                        v = float(cells[2])
+                        valu[short] = valu.get(short, 0.0) + v
+                        lanes[short] = lanes.get(short, 0.0) + v * float(cells[6])
+    return {k: (valu[k] * 4.0 / (1024.0 * dur[k] * 2.4e9), lanes[k] / valu[k]) for k in valu if dur.get(k) and valu[k] > 0}
+
+
 def load_workload(c: int, args):
     from workloads import CONFIGS, config_jpeg
     wl = CONFIGS[c]
@@ -167,8 +196,9 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / steps
 
-    traffic, stale = profile_traffic(c) if not (args.subseq_bits or ri or args.quality or args.planar or args.scale != 1
-                                                or args.limit or args.overlap >= 0) else ({}, None)
+    as_profiled = not (args.subseq_bits or ri or args.quality or args.planar or args.scale != 1 or args.limit or args.overlap >= 0)
+    traffic, stale = profile_traffic(c) if as_profiled else ({}, None)
+    issue = profile_issue(c) if as_profiled else {}
     kernels = {}
     for k, name in enumerate(J.KERNELS):
         if rep.launches[k] == 0 or k == i_tail:
@@ -177,6 +207,9 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
         gbs = ab / 1e9 / (split[k] / 1e3) if split[k] > 0 else 0.0
         kernels[name] = {"ms": round(float(split[k]), 5), "alg_bytes": ab, "achieved_gbs": round(gbs, 2),
                          "frac": round(gbs / HBM_PEAK_GBS, 5), "traffic": traffic.get(name)}
+        if name in issue:   # from the committed rocprofv3 summary (stale with the traffic figures)
+            kernels[name]["valu_issue_frac"] = round(issue[name][0], 4)
+            kernels[name]["lanes_on_of_64"] = round(issue[name][1], 1)
         if name == "sync_intra" and sync_parts:
             kernels[name]["two_kernels"] = sync_parts
     res = {
@@ -424,8 +457,12 @@ def main() -> int:
                      "traffic": r["kernels"][dom]["traffic"], "traffic_stale": r["traffic_stale"],
                      "avg_launch_ms": round(r["dom_avg_ms"], 5), "timed_launches": r["dom_launches"],
                      "alg_bytes_per_launch": alg,
-                     "note": "the entropy kernels are bound by dependent instruction issue, not by HBM: see kernels{} "
-                             "for every kernel's fraction and profiles/ for the SQ counters"},
+                     "valu_issue_frac": r["kernels"][dom].get("valu_issue_frac"),
+                     "lanes_on_of_64": r["kernels"][dom].get("lanes_on_of_64"),
+                     "note": "the entropy kernels are bound by dependent instruction issue, not by HBM: valu_issue_frac is "
+                             "the share of the chip's vector issue slots the kernel fills (SQ_INSTS_VALU x 4 cycles over "
+                             "1024 SIMDs x duration x 2.4 GHz, from the rocprofv3 summary in profiles/); see kernels{} for "
+                             "every kernel's fractions"},
         "cpu_baseline": cpu,
         "kernels": r["kernels"],
         "kernel_sources_sha16": kernel_sources_sha16(),

@@ -46,6 +46,9 @@ def test_traffic_figures_come_from_the_committed_profile_summaries():
         assert stale in (True, False)
         for k in ("sync_intra", "write", "pixels"):
             assert traffic[k] > 0
+        issue = bench.profile_issue(c)      # share of the vector issue slots, lanes switched on: from the same summary
+        for k in ("sync_intra", "write", "pixels"):
+            assert 0.0 < issue[k][0] < 1.0 and 1.0 <= issue[k][1] <= 64.0
     assert len(bench.kernel_sources_sha16()) == 16
 
 
