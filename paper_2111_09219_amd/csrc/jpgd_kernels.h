@@ -634,11 +634,12 @@ constexpr uint32_t kHandWords = 6u * kWG;  // per sequence: 4 x kWG record words
 template <bool STAGED, bool RST, int PHASE>
 __device__ __forceinline__ void sync_intra_body(const Params& P) {
     static_assert(PHASE != kSyncTail || !STAGED, "the second kernel reads the stream from memory");
-    // Two symbols per step where the tables allow it (sync_symbol_pair), except in the kernels for calls with
-    // restart intervals, whose rules look at every symbol.  Measured on the 15360x8640 image: first kernel 0.85 ->
-    // 0.75 ms, second 1.00 -> 0.87 ms; 4096x4096 0.67 -> 0.59 ms; the 256-image batch 0.40 -> 0.36 ms; nothing on
-    // images whose rounds are mostly walked by whole wavefronts (1920x1088 with 128-bit subsequences).
-    constexpr bool PAIRS = !RST;
+    // Two symbols per step where the tables allow it (sync_symbol_pair); a workgroup whose stretch of the stream holds
+    // the start of a restart interval takes the loop that knows their rules instead, one symbol per step.  Measured
+    // on the 15360x8640 image: first kernel 0.85 -> 0.75 ms, second 1.00 -> 0.87 ms; 4096x4096 0.67 -> 0.59 ms; the
+    // 256-image batch 0.40 -> 0.36 ms; nothing on images whose rounds are mostly walked by whole wavefronts
+    // (1920x1088 with 128-bit subsequences).
+    constexpr bool PAIRS = true;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds_raw[];
     const uint32_t wg = blockIdx.x;
     const uint32_t ii = find_image(P, wg, [](const ImgDesc& d) { return d.seq0; });
