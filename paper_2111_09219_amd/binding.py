@@ -414,7 +414,8 @@ def prepare_batch(files, cfg: Config | None = None, device="cuda:0", want_pixels
     if not torch.cuda.is_available():
         raise RuntimeError("jpgd: no GPU visible; the decoder has no CPU path")
     cfg = cfg if cfg is not None else Config.make()
-    files = [np.ascontiguousarray(f, dtype=np.uint8) for f in files]
+    files = [np.ascontiguousarray(np.frombuffer(f, dtype=np.uint8) if isinstance(f, (bytes, bytearray, memoryview)) else f,
+                                  dtype=np.uint8) for f in files]
     infos = [jpgd_parse(f) for f in files]
     scan_offsets, coef_offsets, pixel_offsets = [], [], []
     so = co = po = 0

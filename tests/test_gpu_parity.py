@@ -57,6 +57,9 @@ def test_config1_gray_256():
         batch, rep = _decode([data], subseq_bits=L)
         assert rep.redo == 0
         _check_image(batch, 0, data)
+    batch, rep = _decode([data.tobytes(), bytearray(data.tobytes())])   # files as bytes objects
+    for i in range(2):
+        _check_image(batch, i, data)
 
 
 def test_config2_hd_444():
