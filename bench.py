@@ -35,7 +35,10 @@ PROFILE_NAMES = {"unstuff_count": ("jpgd::k_unstuff_count",), "unstuff_scan": ("
                  "sync_inter": ("jpgd::k_sync_inter",), "scan_totals": ("jpgd::k_group_totals",),
                  "scan_prefix": ("jpgd::k_group_scan",), "write": ("jpgd::k_write",), "pixels": ("jpgd::k_pixels",)}
 PROFILE_FILES = {1: "decode_path_gray256_q75.md", 2: "decode_path_hd1088_444_q90.md", 3: "decode_path_4k_420_q95_opt.md",
-                 4: "decode_path_batch256_420.md", 5: "decode_path_uhd16k_420_q92.md"}
+                 4: "decode_path_batch256_420.md", 5: "decode_path_uhd16k_420_q92.md",
+                 # the same file 200 times in one call (--config 2 --repeat 200): a batch of video frames, the
+                 # regime of the paper's measurements (Section 5)
+                 (2, 200): "decode_path_hd1088_444_q90_x200.md"}
 
 
 def algorithmic_bytes(kernel: str, Bs: int, B: int, S: int, K: int, out_bytes: int) -> int:
@@ -135,7 +138,7 @@ def load_workload(c: int, args):
     else:
         enc = config_jpeg(c, restart_interval=ri, quality=args.quality or None)
     files = [e.data for e in enc] if isinstance(enc, list) else [enc.data]
-    return wl, ri, files
+    return wl, ri, files * max(1, args.repeat)
 
 
 def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: bool):
@@ -197,8 +200,9 @@ def measure(J, torch, c: int, args, steps: int, warmup: int, bracket_dominant: b
     ms_per_step = dt * 1e3 / steps
 
     as_profiled = not (args.subseq_bits or ri or args.quality or args.planar or args.scale != 1 or args.limit or args.overlap >= 0)
-    traffic, stale = profile_traffic(c) if as_profiled else ({}, None)
-    issue = profile_issue(c) if as_profiled else {}
+    pkey = c if args.repeat <= 1 else (c, args.repeat)
+    traffic, stale = profile_traffic(pkey) if as_profiled else ({}, None)
+    issue = profile_issue(pkey) if as_profiled else {}
     kernels = {}
     for k, name in enumerate(J.KERNELS):
         if rep.launches[k] == 0 or k == i_tail:
@@ -362,6 +366,8 @@ def main() -> int:
     ap.add_argument("--overlap", type=int, default=-1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing; 0 skips it")
     ap.add_argument("--limit", type=int, default=0, help="images of the batch config to use (0 = all)")
+    ap.add_argument("--repeat", type=int, default=1, metavar="N",
+                    help="decode the workload's file(s) N times over in one call (a batch of N identical frames)")
     ap.add_argument("--restart-interval", type=int, default=0, metavar="MCUS",
                     help="encode the workload with restart markers every MCUS MCUs (-1 = one MCU row); the "
                          "configurations themselves have none")
